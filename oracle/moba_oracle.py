@@ -1,0 +1,230 @@
+"""ctypes front end of the CPU oracle (oracle/moba_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, the smoke check and the benchmark's
+CPU-baseline leg.  The GPU library never imports or calls anything here, and this
+module imports nothing from the GPU package.
+
+All tensors are numpy float64, row-major ``[bh, N, d]`` (batch*heads flattened).
+The arithmetic lives in the C file; this module only marshals arguments, plus two
+one-line numpy steps that are part of the definition:
+``D = rowsum(dO * O)`` (paper Appendix C.3, backward preprocessing) and the
+count of routed pairs.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "moba_oracle.c")
+_LIB = os.path.join(_HERE, "libmoba_oracle.so")
+
+ROUND_F32, ROUND_BF16, ROUND_NONE = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, OpenMP over independent rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-fno-fast-math",
+             "-ffp-contract=off", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_csr.restype = ctypes.c_int64
+        _lib.oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _f64(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i64(a):
+    a = np.ascontiguousarray(a, dtype=np.int64)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _out(shape, dtype=np.float64):
+    a = np.empty(shape, dtype=dtype)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_threads() -> int:
+    return int(_L().oracle_num_threads())
+
+
+def routes_per_slice(N: int, B: int, k: int) -> int:
+    """Number of (query, selected past block) pairs of one [N, d] slice:
+    the queries of block c each keep min(c, k) past blocks."""
+    n = N // B
+    return B * sum(min(c, k) for c in range(n))
+
+
+def round_io(x, mode):
+    x, px = _f64(x)
+    y, py = _out(x.shape)
+    _L().oracle_round_array(px, py, ctypes.c_int64(x.size), ctypes.c_int(mode))
+    return y
+
+
+def key_conv(K, w, heads, round_mode):
+    """Appendix B.  K [bh,N,d], w [heads,d,W] (lag-major last axis) -> K' [bh,N,d]."""
+    K, pK = _f64(K)
+    w, pw = _f64(w)
+    bh, N, d = K.shape
+    assert w.shape[0] == heads and w.shape[1] == d
+    Kp, pP = _out(K.shape)
+    _L().oracle_key_conv(pK, pw, pP, bh, heads, N, d, w.shape[2], round_mode)
+    return Kp
+
+
+def centroids(K, B):
+    """Section 2.  Mean key of each block, stored as fp32 values -> [bh, n, d]."""
+    K, pK = _f64(K)
+    bh, N, d = K.shape
+    assert N % B == 0
+    C, pC = _out((bh, N // B, d))
+    _L().oracle_centroids(pK, pC, bh, N, d, B)
+    return C
+
+
+def gate_scores(Q, C, rows, B):
+    """Gate scores of flat rows (s*N+t) against all n blocks; -inf for own/future."""
+    Q, pQ = _f64(Q)
+    C, pC = _f64(C)
+    bh, N, d = Q.shape
+    rows, pr = _i64(rows)
+    S, pS = _out((rows.size, N // B))
+    _L().oracle_gate_scores(pQ, pC, pr, ctypes.c_int64(rows.size), pS, N, d, B)
+    return S
+
+
+def topk(Q, C, B, k):
+    """Section 2 + Appendix C.1.  -> idx [bh,N,k] int32 (best first, -1 unused),
+    kth [bh,N] score of the last kept block (NaN if none)."""
+    Q, pQ = _f64(Q)
+    C, pC = _f64(C)
+    bh, N, d = Q.shape
+    idx, pi = _out((bh, N, max(k, 0)), np.int32)
+    kth, pk = _out((bh, N))
+    _L().oracle_topk(pQ, pC, pi, pk, bh, N, d, B, k)
+    return idx, kth
+
+
+def csr(idx, B):
+    """Appendix C.1.  Key-block-major query lists -> off [bh,n+1], qlist [bh,R]."""
+    idx, pi = _i32(idx)
+    bh, N, k = idx.shape
+    n = N // B
+    R = routes_per_slice(N, B, k)
+    off, po = _out((bh, n + 1), np.int32)
+    ql, pq = _out((bh, R), np.int32)
+    got = _L().oracle_csr(pi, po, pq, bh, N, B, k, ctypes.c_int64(R))
+    if got != R:
+        raise ValueError("routing does not keep min(c,k) blocks per query")
+    return off, ql
+
+
+def attn_fwd(Q, K, V, idx, B, scale, rows=None):
+    """Section 2.  O [nrows,d] and lse [nrows] for flat rows (default: all, then
+    shaped [bh,N,d] / [bh,N])."""
+    Q, pQ = _f64(Q)
+    K, pK = _f64(K)
+    V, pV = _f64(V)
+    idx, pi = _i32(idx)
+    bh, N, d = Q.shape
+    k = idx.shape[2]
+    full = rows is None
+    rows, pr = _i64(np.arange(bh * N) if full else rows)
+    O, pO = _out((rows.size, d))
+    lse, pl = _out((rows.size,))
+    _L().oracle_attn_fwd(pQ, pK, pV, pi, pr, ctypes.c_int64(rows.size), pO, pl,
+                         N, d, B, k, ctypes.c_double(scale))
+    if full:
+        return O.reshape(bh, N, d), lse.reshape(bh, N)
+    return O, lse
+
+
+def attn_bwd_dq(Q, K, V, idx, dO, lse, Dv, B, scale, rows=None):
+    """Appendix C.3.  dQ for flat rows; lse, Dv are full [bh,N] (listed rows read)."""
+    Q, pQ = _f64(Q)
+    K, pK = _f64(K)
+    V, pV = _f64(V)
+    dO, pg = _f64(dO)
+    lse, pl = _f64(lse)
+    Dv, pD = _f64(Dv)
+    idx, pi = _i32(idx)
+    bh, N, d = Q.shape
+    k = idx.shape[2]
+    full = rows is None
+    rows, pr = _i64(np.arange(bh * N) if full else rows)
+    dQ, pq = _out((rows.size, d))
+    _L().oracle_attn_bwd_dq(pQ, pK, pV, pi, pg, pl, pD, pr, ctypes.c_int64(rows.size), pq,
+                            N, d, B, k, ctypes.c_double(scale))
+    return dQ.reshape(bh, N, d) if full else dQ
+
+
+def attn_bwd_dkdv(Q, K, V, dO, lse, Dv, off, qlist, B, scale, blocks=None):
+    """Appendix C.3.  dK, dV for flat key blocks (s*n+j) -> [nblocks,B,d] each
+    (default: all blocks, shaped [bh,N,d])."""
+    Q, pQ = _f64(Q)
+    K, pK = _f64(K)
+    V, pV = _f64(V)
+    dO, pg = _f64(dO)
+    lse, pl = _f64(lse)
+    Dv, pD = _f64(Dv)
+    off, po = _i32(off)
+    qlist, pql = _i32(qlist)
+    bh, N, d = Q.shape
+    n = N // B
+    R = qlist.shape[1]
+    full = blocks is None
+    blocks, pb = _i64(np.arange(bh * n) if full else blocks)
+    dK, pdk = _out((blocks.size, B, d))
+    dV, pdv = _out((blocks.size, B, d))
+    _L().oracle_attn_bwd_dkdv(pQ, pK, pV, pg, pl, pD, po, pql, ctypes.c_int64(R),
+                              pb, ctypes.c_int64(blocks.size), pdk, pdv,
+                              N, d, B, ctypes.c_double(scale))
+    if full:
+        return dK.reshape(bh, N, d), dV.reshape(bh, N, d)
+    return dK, dV
+
+
+def attn_bwd(Q, K, V, idx, dO, B, scale):
+    """Whole backward at fixed routing: forward for (O, lse), D = rowsum(dO*O)
+    (Appendix C.3, preprocessing), then dQ, dK, dV."""
+    O, lse = attn_fwd(Q, K, V, idx, B, scale)
+    Dv = (np.asarray(dO, dtype=np.float64) * O).sum(-1)
+    off, ql = csr(idx, B)
+    dQ = attn_bwd_dq(Q, K, V, idx, dO, lse, Dv, B, scale)
+    dK, dV = attn_bwd_dkdv(Q, K, V, dO, lse, Dv, off, ql, B, scale)
+    return dQ, dK, dV
+
+
+def moba_forward(Q, K, V, B, k, scale, conv_w=None, heads=1, round_mode=ROUND_NONE):
+    """The whole forward chain of Section 2 (with Appendix B's conv if given):
+    conv -> centroids -> top-k -> attention.  Returns a dict of every stage."""
+    Kp = key_conv(K, conv_w, heads, round_mode) if conv_w is not None else np.asarray(K, np.float64)
+    C = centroids(Kp, B)
+    idx, kth = topk(Q, C, B, k)
+    O, lse = attn_fwd(Q, Kp, V, idx, B, scale)
+    return dict(K_eff=Kp, centroids=C, idx=idx, kth=kth, O=O, lse=lse)
