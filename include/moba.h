@@ -1,0 +1,144 @@
+/*
+ * moba.h -- C ABI of the MI355X (gfx950) Mixture of Block Attention library.
+ *
+ * The operator (paper "Optimizing Mixture of Block Attention", Section 2):
+ * the N keys of one head are cut into n = N/B blocks; a block's gate score for a
+ * query is q . mean(keys of the block); each query keeps its `topk` best *past*
+ * blocks (ties: lower block index) and always attends its own block under a causal
+ * mask; O = softmax(q K_S^T * scale) V_S over the kept tokens S.  An optional
+ * depthwise causal convolution (Appendix B) replaces K by
+ * K' = K + SiLU(conv(K)) before both the gate and attention.
+ *
+ * General rules for every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or keeps device memory.  `const moba_shape*` and the
+ *     size_t* / int64_t* outputs are HOST pointers.
+ *   - Tensors are contiguous, row-major [batch, heads, N, d]; element type is
+ *     `shape->dtype` (fp32, or bf16 as raw 16-bit words) for Q, K, V, K_eff, O, dO,
+ *     dQ, dK, dV.  Centroids, lse and conv weights are always fp32; indices int32.
+ *   - Arguments are checked on the host before anything is enqueued; a call that
+ *     returns non-zero has launched nothing.  Work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and the call
+ *     returns without synchronising.
+ *   - Return value: MOBA_OK (0) or a negative moba_status.  No exceptions, no abort.
+ *   - Supported: head_dim 64 or 128; seqlen a multiple of block; block >= 1;
+ *     topk >= 0 (topk >= n-1 is full causal attention); conv_width 0 (none) or 1..8;
+ *     at most 4096 key blocks per head for moba_topk.
+ *   - R below is the number of (query, kept past block) pairs of one [N, d]
+ *     slice, R = B * sum_{c<n} min(c, topk); it depends on the shape only
+ *     (moba_routes_per_slice).
+ */
+#ifndef MOBA_H_
+#define MOBA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum moba_status {
+    MOBA_OK = 0,
+    MOBA_EINVAL = -1,       /* null pointer, non-positive size, N % B != 0, topk < 0, bad dtype */
+    MOBA_EUNSUPPORTED = -2, /* legal but not built: head_dim, conv_width, too many blocks      */
+    MOBA_EWORKSPACE = -3,   /* workspace pointer null or smaller than moba_workspace_bytes    */
+    MOBA_EHIP = -4          /* a HIP launch failed; see moba_last_hip_error                   */
+} moba_status;
+
+typedef enum moba_dtype { MOBA_F32 = 0, MOBA_BF16 = 1 } moba_dtype;
+
+/* flags */
+#define MOBA_FLAG_REFERENCE_KERNELS 1u /* use the plain (non-MFMA) kernels for every stage */
+
+typedef struct moba_shape {
+    int32_t batch, heads, seqlen, head_dim;
+    int32_t block;         /* B: keys per block                                        */
+    int32_t topk;          /* k: kept PAST blocks per query; the own block is extra    */
+    int32_t conv_width;    /* W: 0 = no key convolution                                */
+    int32_t dtype;         /* moba_dtype                                               */
+    float   softmax_scale; /* <= 0 selects 1/sqrt(head_dim)                            */
+    uint32_t flags;        /* MOBA_FLAG_*                                              */
+} moba_shape;
+
+/* Host-only helpers.  R and the byte counts are written to host memory. */
+int moba_routes_per_slice(const moba_shape* shape, int64_t* R);
+int moba_workspace_bytes(const moba_shape* shape, size_t* topk_ws, size_t* fwd_ws, size_t* bwd_ws);
+
+/*
+ * Key convolution (Appendix B, k'_t = k_t + SiLU(sum_l W_l * k_{t-l}), terms with
+ * t-l < 0 dropped) followed by the block centroids (Section 2; Appendix C.1,
+ * centroid algorithm).
+ *   K         in   [b,h,N,d] dtype
+ *   conv_w    in   [heads,d,W] fp32, last axis = lag l; must be NULL iff conv_width == 0
+ *   K_eff     out  [b,h,N,d] dtype: the convolved keys rounded to dtype; required iff
+ *                  conv_width > 0 (with conv_width == 0 it may be NULL; if given, K is copied)
+ *   centroids out  [b,h,n,d] fp32: mean over each block of the (rounded) K_eff rows
+ */
+int moba_centroids(const moba_shape* shape, const void* K, const float* conv_w,
+                   void* K_eff, float* centroids, void* stream);
+
+/*
+ * Gate scores and causal top-k (Section 2; Appendix C.1, top-k selection algorithm)
+ * followed by the key-block-major query lists (Appendix C.1, varlen reformatting).
+ * The N x n score matrix is never written to memory.
+ *   Q         in   [b,h,N,d] dtype
+ *   centroids in   [b,h,n,d] fp32
+ *   topk_idx  out  [b,h,N,topk] int32: kept past blocks of each query in ascending
+ *                  block order, -1 in unused trailing slots
+ *   blk_off   out  [b,h,n+1] int32: exclusive prefix sums of the per-block list lengths
+ *   blk_q     out  [b,h,R] int32: for each key block the ids of the queries that kept
+ *                  it, ascending (deterministic); block j's list is
+ *                  blk_q[blk_off[j] .. blk_off[j+1])
+ *   ws             at least topk_ws bytes from moba_workspace_bytes
+ */
+int moba_topk(const moba_shape* shape, const void* Q, const float* centroids,
+              int32_t* topk_idx, int32_t* blk_off, int32_t* blk_q,
+              void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The list-building half of moba_topk alone (Appendix C.1, varlen reformatting), for a
+ * routing supplied by the caller.  topk_idx rows may list their blocks in any order;
+ * entries must be -1 or a past block of the query, without repeats, and every query of
+ * block c must keep exactly min(c, topk) blocks (not checked on the device).
+ */
+int moba_build_lists(const moba_shape* shape, const int32_t* topk_idx,
+                     int32_t* blk_off, int32_t* blk_q,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Attention over the kept blocks plus the causally masked own block
+ * (Section 2; Section 4.2 forward algorithm).  Routing is an input.
+ *   Q, K_eff, V   in   [b,h,N,d] dtype (K_eff = K when there is no convolution)
+ *   topk_idx, blk_off, blk_q   in   as produced by moba_topk / moba_build_lists
+ *   O         out  [b,h,N,d] dtype
+ *   lse       out  [b,h,N] fp32: natural log of sum_u exp(scale * q.k_u) over the kept keys
+ *   ws             at least fwd_ws bytes
+ */
+int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
+                 const int32_t* topk_idx, const int32_t* blk_off, const int32_t* blk_q,
+                 void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward at fixed routing (Section 4.2 backward; Appendix C.3):
+ * D = rowsum(dO o O), P = exp(S - lse), dV = P^T dO, dS = P o (dO V^T - D),
+ * dQ = scale * dS K, dK = scale * dS^T Q.  dK is the gradient with respect to K_eff.
+ * No gradient flows through the gate (centroids / top-k).
+ *   Q, K_eff, V, O, dO   in   [b,h,N,d] dtype;   lse in [b,h,N] fp32 (from moba_forward)
+ *   dQ, dK, dV           out  [b,h,N,d] dtype
+ *   ws                        at least bwd_ws bytes
+ */
+int moba_backward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
+                  const void* O, const float* lse, const void* dO,
+                  const int32_t* topk_idx, const int32_t* blk_off, const int32_t* blk_q,
+                  void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* moba_strerror(int status);
+/* hipError_t value of the most recent failed HIP call on the calling thread (0 if none). */
+int moba_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOBA_H_ */

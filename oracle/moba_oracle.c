@@ -132,10 +132,11 @@ void oracle_gate_scores(const double *Q, const double *C, const int64_t *rows, i
     }
 }
 
-/* idx: [bh, N, k] int32, best first, -1 in unused slots.
- * kth: [bh, N] score of the last selected block (NaN when none is selected). */
-void oracle_topk(const double *Q, const double *C, int32_t *idx, double *kth,
-                 int bh, int N, int d, int B, int k)
+/* Top-k of a list of query rows.  rows[i] = s*N + t.
+ * idx: [nrows, k] int32, best first, -1 in unused slots.
+ * kth: [nrows] score of the last selected block (NaN when none is selected). */
+void oracle_topk(const double *Q, const double *C, const int64_t *rows, int64_t nrows,
+                 int32_t *idx, double *kth, int N, int d, int B, int k)
 {
     int n = N / B;
     #pragma omp parallel
@@ -143,8 +144,8 @@ void oracle_topk(const double *Q, const double *C, int32_t *idx, double *kth,
         double *sc = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
         char *taken = (char *)malloc((size_t)(n > 0 ? n : 1));
         #pragma omp for schedule(dynamic, 64)
-        for (int64_t r = 0; r < (int64_t)bh * N; ++r) {
-            int64_t s = r / N; int t = (int)(r % N);
+        for (int64_t i = 0; i < nrows; ++i) {
+            int64_t r = rows[i], s = r / N; int t = (int)(r % N);
             int past = t / B;                      /* blocks 0..past-1 are candidates */
             const double *q = Q + r * d;
             for (int j = 0; j < past; ++j) {
@@ -156,15 +157,15 @@ void oracle_topk(const double *Q, const double *C, int32_t *idx, double *kth,
             int keep = past < k ? past : k;
             double last = NAN;
             for (int slot = 0; slot < k; ++slot) {
-                if (slot >= keep) { idx[r * k + slot] = -1; continue; }
+                if (slot >= keep) { idx[i * k + slot] = -1; continue; }
                 int best = -1;
                 for (int j = 0; j < past; ++j)        /* strict > keeps the lower index on ties */
                     if (!taken[j] && (best < 0 || sc[j] > sc[best])) best = j;
                 taken[best] = 1;
-                idx[r * k + slot] = best;
+                idx[i * k + slot] = best;
                 last = sc[best];
             }
-            kth[r] = last;
+            kth[i] = last;
         }
         free(sc); free(taken);
     }

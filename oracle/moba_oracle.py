@@ -118,15 +118,20 @@ def gate_scores(Q, C, rows, B):
     return S
 
 
-def topk(Q, C, B, k):
+def topk(Q, C, B, k, rows=None):
     """Section 2 + Appendix C.1.  -> idx [bh,N,k] int32 (best first, -1 unused),
-    kth [bh,N] score of the last kept block (NaN if none)."""
+    kth [bh,N] score of the last kept block (NaN if none).  With ``rows`` (flat
+    s*N+t) only those rows are evaluated: idx [nrows,k], kth [nrows]."""
     Q, pQ = _f64(Q)
     C, pC = _f64(C)
     bh, N, d = Q.shape
-    idx, pi = _out((bh, N, max(k, 0)), np.int32)
-    kth, pk = _out((bh, N))
-    _L().oracle_topk(pQ, pC, pi, pk, bh, N, d, B, k)
+    full = rows is None
+    rows, pr = _i64(np.arange(bh * N) if full else rows)
+    idx, pi = _out((rows.size, max(k, 0)), np.int32)
+    kth, pk = _out((rows.size,))
+    _L().oracle_topk(pQ, pC, pr, ctypes.c_int64(rows.size), pi, pk, N, d, B, k)
+    if full:
+        return idx.reshape(bh, N, max(k, 0)), kth.reshape(bh, N)
     return idx, kth
 
 

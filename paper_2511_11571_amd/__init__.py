@@ -1,0 +1,7 @@
+"""MI355X-native Mixture of Block Attention: thin Python binding over libmoba.so.
+
+Only argument marshalling happens here; every step of the path runs in the HIP
+kernels behind the C ABI declared in include/moba.h.
+"""
+from .binding import (MobaError, Shape, backward, build_lists, centroids, forward, lib,  # noqa: F401
+                      routes_per_slice, topk, workspace_bytes)

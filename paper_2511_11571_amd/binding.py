@@ -1,0 +1,183 @@
+"""ctypes binding of libmoba.so.  Function names mirror the C ABI (include/moba.h).
+
+PyTorch is used for device memory and streams only.  There is no fallback: if the
+library has not been built, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libmoba.so")
+
+F32, BF16 = 0, 1
+FLAG_REFERENCE_KERNELS = 1
+
+
+class MobaError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().moba_strerror(status).decode()
+        super().__init__(f"{where}: {msg} (status {status}, hip error {lib().moba_last_hip_error()})")
+
+
+class _CShape(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("seqlen", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("block", ctypes.c_int32), ("topk", ctypes.c_int32),
+                ("conv_width", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float), ("flags", ctypes.c_uint32)]
+
+
+@dataclass(frozen=True)
+class Shape:
+    batch: int
+    heads: int
+    seqlen: int
+    head_dim: int
+    block: int
+    topk: int
+    conv_width: int = 0
+    dtype: int = BF16
+    softmax_scale: float = 0.0
+    flags: int = 0
+
+    def c(self):
+        return _CShape(self.batch, self.heads, self.seqlen, self.head_dim, self.block, self.topk,
+                       self.conv_width, self.dtype, self.softmax_scale, self.flags)
+
+    @property
+    def n(self):
+        return self.seqlen // self.block
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == BF16 else torch.float32
+
+
+_lib = None
+
+
+def lib():
+    """Loads libmoba.so (built in-tree by paper_2511_11571_amd.build); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(_LIB_PATH)
+        L.moba_strerror.restype = ctypes.c_char_p
+        L.moba_strerror.argtypes = [ctypes.c_int]
+        L.moba_last_hip_error.restype = ctypes.c_int
+        for name in ("moba_routes_per_slice", "moba_workspace_bytes", "moba_centroids", "moba_topk",
+                     "moba_build_lists", "moba_forward", "moba_backward"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _p(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(st, where):
+    if st != 0:
+        raise MobaError(st, where)
+
+
+def routes_per_slice(shape: Shape) -> int:
+    R = ctypes.c_int64(0)
+    _check(lib().moba_routes_per_slice(ctypes.byref(shape.c()), ctypes.byref(R)), "moba_routes_per_slice")
+    return R.value
+
+
+def workspace_bytes(shape: Shape):
+    a, b, c = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib().moba_workspace_bytes(ctypes.byref(shape.c()), ctypes.byref(a), ctypes.byref(b),
+                                      ctypes.byref(c)), "moba_workspace_bytes")
+    return a.value, b.value, c.value
+
+
+def _ws(nbytes, like):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=like.device)
+
+
+def centroids(shape: Shape, K, conv_w=None, K_eff=None, out=None):
+    """-> (K_eff or K, centroids [b,h,n,d] fp32)."""
+    assert K.is_contiguous() and K.dtype == shape.torch_dtype
+    if shape.conv_width > 0 and K_eff is None:
+        K_eff = torch.empty_like(K)
+    if out is None:
+        out = torch.empty((shape.batch, shape.heads, shape.n, shape.head_dim), dtype=torch.float32,
+                          device=K.device)
+    _check(lib().moba_centroids(ctypes.byref(shape.c()), _p(K), _p(conv_w), _p(K_eff), _p(out),
+                                _stream()), "moba_centroids")
+    return (K_eff if K_eff is not None else K), out
+
+
+def _list_buffers(shape, like):
+    R = routes_per_slice(shape)
+    off = torch.empty((shape.batch, shape.heads, shape.n + 1), dtype=torch.int32, device=like.device)
+    ql = torch.empty((shape.batch, shape.heads, max(R, 1)), dtype=torch.int32, device=like.device)
+    return off, ql[..., :R] if R > 0 else ql[..., :0]
+
+
+def topk(shape: Shape, Q, cent, ws=None):
+    """-> (topk_idx [b,h,N,k] int32, blk_off [b,h,n+1] int32, blk_q [b,h,R] int32)."""
+    assert Q.is_contiguous() and cent.is_contiguous()
+    idx = torch.empty((shape.batch, shape.heads, shape.seqlen, shape.topk), dtype=torch.int32,
+                      device=Q.device)
+    off, ql = _list_buffers(shape, Q)
+    if ws is None:
+        ws = _ws(workspace_bytes(shape)[0], Q)
+    _check(lib().moba_topk(ctypes.byref(shape.c()), _p(Q), _p(cent), _p(idx), _p(off), _p(ql), _p(ws),
+                           ctypes.c_size_t(ws.numel()), _stream()), "moba_topk")
+    return idx, off, ql
+
+
+def build_lists(shape: Shape, idx, ws=None):
+    """-> (blk_off, blk_q) for a routing given by the caller."""
+    assert idx.is_contiguous() and idx.dtype == torch.int32
+    off, ql = _list_buffers(shape, idx)
+    if ws is None:
+        ws = _ws(workspace_bytes(shape)[0], idx)
+    _check(lib().moba_build_lists(ctypes.byref(shape.c()), _p(idx), _p(off), _p(ql), _p(ws),
+                                  ctypes.c_size_t(ws.numel()), _stream()), "moba_build_lists")
+    return off, ql
+
+
+def forward(shape: Shape, Q, K_eff, V, idx, off, ql, ws=None, O=None, lse=None):
+    """-> (O [b,h,N,d], lse [b,h,N] fp32)."""
+    for t in (Q, K_eff, V):
+        assert t.is_contiguous() and t.dtype == shape.torch_dtype
+    if O is None:
+        O = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    if ws is None:
+        ws = _ws(workspace_bytes(shape)[1], Q)
+    _check(lib().moba_forward(ctypes.byref(shape.c()), _p(Q), _p(K_eff), _p(V), _p(idx), _p(off),
+                              _p(ql), _p(O), _p(lse), _p(ws), ctypes.c_size_t(ws.numel()), _stream()),
+           "moba_forward")
+    return O, lse
+
+
+def backward(shape: Shape, Q, K_eff, V, O, lse, dO, idx, off, ql, ws=None, out=None):
+    """-> (dQ, dK, dV), each [b,h,N,d]."""
+    for t in (Q, K_eff, V, O, dO):
+        assert t.is_contiguous() and t.dtype == shape.torch_dtype
+    dQ, dK, dV = out if out is not None else (torch.empty_like(Q), torch.empty_like(Q),
+                                              torch.empty_like(Q))
+    if ws is None:
+        ws = _ws(workspace_bytes(shape)[2], Q)
+    _check(lib().moba_backward(ctypes.byref(shape.c()), _p(Q), _p(K_eff), _p(V), _p(O), _p(lse),
+                               _p(dO), _p(idx), _p(off), _p(ql), _p(dQ), _p(dK), _p(dV), _p(ws),
+                               ctypes.c_size_t(ws.numel()), _stream()), "moba_backward")
+    return dQ, dK, dV

@@ -1,0 +1,132 @@
+// Shared device helpers of the MoBA kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moba.h"
+
+namespace moba {
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+constexpr int kWave = 64;
+constexpr int kChunkQ = 256;       // queries per routing chunk (list building, query tiles)
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x)
+{
+    return __uint_as_float(((uint32_t)x) << 16);
+}
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// ---- 8-element vector access in the I/O type --------------------------------
+template <typename T> struct Vec8;
+
+template <> struct Vec8<float> {
+    static __device__ __forceinline__ void load(const float* p, float (&v)[8])
+    {
+        float4 a = *reinterpret_cast<const float4*>(p);
+        float4 b = *reinterpret_cast<const float4*>(p + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+    static __device__ __forceinline__ void store(float* p, const float (&v)[8])
+    {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+    // value after a round trip through the I/O type
+    static __device__ __forceinline__ float round(float x) { return x; }
+};
+
+template <> struct Vec8<bf16_t> {
+    static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8])
+    {
+        uint4 a = *reinterpret_cast<const uint4*>(p);
+        v[0] = __uint_as_float(a.x << 16); v[1] = __uint_as_float(a.x & 0xffff0000u);
+        v[2] = __uint_as_float(a.y << 16); v[3] = __uint_as_float(a.y & 0xffff0000u);
+        v[4] = __uint_as_float(a.z << 16); v[5] = __uint_as_float(a.z & 0xffff0000u);
+        v[6] = __uint_as_float(a.w << 16); v[7] = __uint_as_float(a.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8])
+    {
+        uint4 a;
+        a.x = pack_bf16x2(v[0], v[1]); a.y = pack_bf16x2(v[2], v[3]);
+        a.z = pack_bf16x2(v[4], v[5]); a.w = pack_bf16x2(v[6], v[7]);
+        *reinterpret_cast<uint4*>(p) = a;
+    }
+    static __device__ __forceinline__ float round(float x) { return bf16_to_f32(f32_to_bf16(x)); }
+};
+
+template <typename T> __device__ __forceinline__ float to_f32(T x);
+template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t x) { return bf16_to_f32(x); }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return f32_to_bf16(x); }
+
+// ---- wave-level reductions (64 lanes) ------------------------------------------
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+// number of set bits of `mask` below this lane
+__device__ __forceinline__ int lanes_below(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+
+// ---- host-side view of a validated shape ------------------------------------------
+struct Dims {
+    int bh, heads, N, D, B, n, k, W;
+    int dtype;
+    uint32_t flags;
+    float scale;
+    int64_t R;          // routes per slice
+    int nchunk;         // ceil(N / kChunkQ)
+};
+
+// launchers (one translation unit each); every one returns a hipError_t
+hipError_t launch_centroids(const Dims& s, const void* K, const float* w, void* Keff,
+                            float* cent, hipStream_t st);
+hipError_t launch_topk_reference(const Dims& s, const void* Q, const float* cent, int32_t* idx,
+                                 hipStream_t st);
+hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, int32_t* ql,
+                              void* ws, hipStream_t st);
+hipError_t launch_forward_reference(const Dims& s, const void* Q, const void* K, const void* V,
+                                    const int32_t* idx, void* O, float* lse, hipStream_t st);
+hipError_t launch_backward_reference(const Dims& s, const void* Q, const void* K, const void* V,
+                                     const void* O, const float* lse, const void* dO,
+                                     const int32_t* idx, const int32_t* off, const int32_t* ql,
+                                     void* dQ, void* dK, void* dV, float* Dvec, hipStream_t st);
+
+size_t lists_ws_bytes(const Dims& s);
+
+}  // namespace moba

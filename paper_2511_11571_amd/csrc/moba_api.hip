@@ -1,0 +1,175 @@
+// C ABI of the library: host-side argument checks, workspace layout and dispatch.
+// Every check happens before the first HIP call, so each error path can be
+// exercised on a machine without a GPU.
+#include <math.h>
+
+#include "common.h"
+
+using namespace moba;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return MOBA_OK;
+    g_last_hip_error = (int)e;
+    return MOBA_EHIP;
+}
+
+constexpr int kMaxBlocks = 4096;   // key blocks per head the scoring kernels keep in LDS
+constexpr int kMaxTopk = 4096;
+
+// Fills `d` from `shape`; returns MOBA_OK or the status to hand back.
+int make_dims(const moba_shape* sh, Dims& d)
+{
+    if (!sh) return MOBA_EINVAL;
+    if (sh->batch <= 0 || sh->heads <= 0 || sh->seqlen <= 0 || sh->head_dim <= 0) return MOBA_EINVAL;
+    if (sh->block <= 0 || sh->topk < 0 || sh->conv_width < 0) return MOBA_EINVAL;
+    if (sh->seqlen % sh->block != 0) return MOBA_EINVAL;
+    if (sh->dtype != MOBA_F32 && sh->dtype != MOBA_BF16) return MOBA_EINVAL;
+    if (sh->flags & ~(uint32_t)MOBA_FLAG_REFERENCE_KERNELS) return MOBA_EINVAL;
+    if (!(sh->softmax_scale == sh->softmax_scale) || isinf(sh->softmax_scale)) return MOBA_EINVAL;
+    if (sh->head_dim != 64 && sh->head_dim != 128) return MOBA_EUNSUPPORTED;
+    if (sh->conv_width > 8) return MOBA_EUNSUPPORTED;
+    if (sh->topk > kMaxTopk) return MOBA_EUNSUPPORTED;
+    if ((int64_t)sh->batch * sh->heads > 65535) return MOBA_EUNSUPPORTED;
+    d.bh = sh->batch * sh->heads;
+    d.heads = sh->heads;
+    d.N = sh->seqlen;
+    d.D = sh->head_dim;
+    d.B = sh->block;
+    d.n = d.N / d.B;
+    d.k = sh->topk;
+    d.W = sh->conv_width;
+    d.dtype = sh->dtype;
+    d.flags = sh->flags;
+    d.scale = sh->softmax_scale > 0.f ? sh->softmax_scale : 1.0f / sqrtf((float)d.D);
+    d.nchunk = (d.N + kChunkQ - 1) / kChunkQ;
+    // R = B * sum_{c<n} min(c, k) = B * (k*n - k(k+1)/2) for k < n, B * n(n-1)/2 otherwise
+    const int64_t n = d.n, k = d.k;
+    const int64_t blocks = k < n ? k * n - k * (k + 1) / 2 : n * (n - 1) / 2;
+    d.R = blocks * d.B;
+    if (d.R >= ((int64_t)1 << 31)) return MOBA_EUNSUPPORTED;   // list offsets are int32
+    return MOBA_OK;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+size_t topk_ws_bytes(const Dims& d) { return align256(lists_ws_bytes(d)); }
+size_t fwd_ws_bytes(const Dims&) { return 256; }
+size_t bwd_ws_bytes(const Dims& d) { return align256(sizeof(float) * (size_t)d.bh * d.N); }
+
+}  // namespace
+
+extern "C" {
+
+const char* moba_strerror(int status)
+{
+    switch (status) {
+        case MOBA_OK: return "ok";
+        case MOBA_EINVAL: return "invalid argument";
+        case MOBA_EUNSUPPORTED: return "shape or option not supported by this build";
+        case MOBA_EWORKSPACE: return "workspace missing or too small";
+        case MOBA_EHIP: return "HIP call failed";
+        default: return "unknown status";
+    }
+}
+
+int moba_last_hip_error(void) { return g_last_hip_error; }
+
+int moba_routes_per_slice(const moba_shape* shape, int64_t* R)
+{
+    Dims d;
+    const int st = make_dims(shape, d);
+    if (st != MOBA_OK) return st;
+    if (!R) return MOBA_EINVAL;
+    *R = d.R;
+    return MOBA_OK;
+}
+
+int moba_workspace_bytes(const moba_shape* shape, size_t* topk_ws, size_t* fwd_ws, size_t* bwd_ws)
+{
+    Dims d;
+    const int st = make_dims(shape, d);
+    if (st != MOBA_OK) return st;
+    if (topk_ws) *topk_ws = topk_ws_bytes(d);
+    if (fwd_ws) *fwd_ws = fwd_ws_bytes(d);
+    if (bwd_ws) *bwd_ws = bwd_ws_bytes(d);
+    return MOBA_OK;
+}
+
+int moba_centroids(const moba_shape* shape, const void* K, const float* conv_w, void* K_eff,
+                   float* centroids, void* stream)
+{
+    Dims d;
+    const int st = make_dims(shape, d);
+    if (st != MOBA_OK) return st;
+    if (!K || !centroids) return MOBA_EINVAL;
+    if ((d.W > 0) != (conv_w != nullptr)) return MOBA_EINVAL;
+    if (d.W > 0 && !K_eff) return MOBA_EINVAL;
+    return hip_status(launch_centroids(d, K, conv_w, K_eff, centroids, (hipStream_t)stream));
+}
+
+int moba_build_lists(const moba_shape* shape, const int32_t* topk_idx, int32_t* blk_off,
+                     int32_t* blk_q, void* ws, size_t ws_bytes, void* stream)
+{
+    Dims d;
+    const int st = make_dims(shape, d);
+    if (st != MOBA_OK) return st;
+    if (!blk_off) return MOBA_EINVAL;
+    if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
+    if (d.R > 0 && !blk_q) return MOBA_EINVAL;
+    if (!ws || ws_bytes < topk_ws_bytes(d)) return MOBA_EWORKSPACE;
+    return hip_status(launch_build_lists(d, topk_idx, blk_off, blk_q, ws, (hipStream_t)stream));
+}
+
+int moba_topk(const moba_shape* shape, const void* Q, const float* centroids, int32_t* topk_idx,
+              int32_t* blk_off, int32_t* blk_q, void* ws, size_t ws_bytes, void* stream)
+{
+    Dims d;
+    const int st = make_dims(shape, d);
+    if (st != MOBA_OK) return st;
+    if (!Q || !centroids || !blk_off) return MOBA_EINVAL;
+    if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
+    if (d.R > 0 && !blk_q) return MOBA_EINVAL;
+    if (d.n > kMaxBlocks) return MOBA_EUNSUPPORTED;
+    if (!ws || ws_bytes < topk_ws_bytes(d)) return MOBA_EWORKSPACE;
+    hipError_t e = launch_topk_reference(d, Q, centroids, topk_idx, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_status(e);
+    return hip_status(launch_build_lists(d, topk_idx, blk_off, blk_q, ws, (hipStream_t)stream));
+}
+
+int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
+                 const int32_t* topk_idx, const int32_t* blk_off, const int32_t* blk_q, void* O,
+                 float* lse, void* ws, size_t ws_bytes, void* stream)
+{
+    Dims d;
+    const int st = make_dims(shape, d);
+    if (st != MOBA_OK) return st;
+    if (!Q || !K_eff || !V || !O || !lse || !blk_off) return MOBA_EINVAL;
+    if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
+    if (d.R > 0 && !blk_q) return MOBA_EINVAL;
+    if (!ws || ws_bytes < fwd_ws_bytes(d)) return MOBA_EWORKSPACE;
+    return hip_status(
+        launch_forward_reference(d, Q, K_eff, V, topk_idx, O, lse, (hipStream_t)stream));
+}
+
+int moba_backward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
+                  const void* O, const float* lse, const void* dO, const int32_t* topk_idx,
+                  const int32_t* blk_off, const int32_t* blk_q, void* dQ, void* dK, void* dV,
+                  void* ws, size_t ws_bytes, void* stream)
+{
+    Dims d;
+    const int st = make_dims(shape, d);
+    if (st != MOBA_OK) return st;
+    if (!Q || !K_eff || !V || !O || !lse || !dO || !dQ || !dK || !dV || !blk_off) return MOBA_EINVAL;
+    if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
+    if (d.R > 0 && !blk_q) return MOBA_EINVAL;
+    if (!ws || ws_bytes < bwd_ws_bytes(d)) return MOBA_EWORKSPACE;
+    return hip_status(launch_backward_reference(d, Q, K_eff, V, O, lse, dO, topk_idx, blk_off, blk_q,
+                                                dQ, dK, dV, (float*)ws, (hipStream_t)stream));
+}
+
+}  // extern "C"

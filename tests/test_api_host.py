@@ -1,0 +1,88 @@
+"""Host-side behaviour of the C ABI: the library loads, exports every declared symbol,
+and rejects bad arguments before anything is launched (so this runs without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2511_11571_amd as moba
+from paper_2511_11571_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(os.path.join(ROOT, "paper_2511_11571_amd", "libmoba.so")):
+        from paper_2511_11571_amd import build
+        build.build()
+    return moba.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "moba.h")).read()
+    names = set(re.findall(r"\b(moba_[a-z_]+)\s*\(", header))
+    assert {"moba_centroids", "moba_topk", "moba_forward", "moba_backward"} <= names
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def _shape(**kw):
+    base = dict(batch=1, heads=2, seqlen=1024, head_dim=64, block=32, topk=4)
+    base.update(kw)
+    return binding.Shape(**base)
+
+
+def test_routes_and_workspace(lib):
+    sh = _shape()
+    n = 32
+    assert moba.routes_per_slice(sh) == 32 * sum(min(c, 4) for c in range(n))
+    assert moba.routes_per_slice(_shape(topk=0)) == 0
+    assert moba.routes_per_slice(_shape(topk=1000)) == 32 * n * (n - 1) // 2
+    a, b, c = moba.workspace_bytes(sh)
+    assert a >= 4 * 2 * 4 * n and b > 0 and c >= 4 * 2 * 1024
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(batch=0), -1), (dict(heads=-1), -1), (dict(seqlen=0), -1), (dict(block=0), -1),
+    (dict(seqlen=1000), -1),            # not a multiple of the block
+    (dict(topk=-1), -1), (dict(dtype=7), -1), (dict(conv_width=-2), -1), (dict(flags=8), -1),
+    (dict(head_dim=96), -2), (dict(conv_width=9), -2), (dict(topk=5000), -2),
+])
+def test_bad_shapes_are_rejected(lib, kw, status):
+    sh = _shape(**kw).c()
+    R = ctypes.c_int64(0)
+    assert lib.moba_routes_per_slice(ctypes.byref(sh), ctypes.byref(R)) == status
+    assert lib.moba_workspace_bytes(ctypes.byref(sh), None, None, None) == status
+    assert lib.moba_strerror(status)
+
+
+def test_null_pointers_and_short_workspace(lib):
+    sh = _shape().c()
+    z = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(256)          # never dereferenced: checks come first
+    big = ctypes.c_size_t(1 << 40)
+    assert lib.moba_routes_per_slice(None, None) == -1
+    assert lib.moba_centroids(ctypes.byref(sh), z, z, z, one, z) == -1
+    assert lib.moba_centroids(ctypes.byref(sh), one, one, z, one, z) == -1     # weights without conv
+    conv = _shape(conv_width=4).c()
+    assert lib.moba_centroids(ctypes.byref(conv), one, z, one, one, z) == -1   # conv without weights
+    assert lib.moba_centroids(ctypes.byref(conv), one, one, z, one, z) == -1   # conv needs K_eff
+    assert lib.moba_topk(ctypes.byref(sh), z, one, one, one, one, one, big, z) == -1
+    assert lib.moba_topk(ctypes.byref(sh), one, one, one, one, one, z, big, z) == -3
+    assert lib.moba_topk(ctypes.byref(sh), one, one, one, one, one, one, ctypes.c_size_t(8), z) == -3
+    assert lib.moba_build_lists(ctypes.byref(sh), z, one, one, one, big, z) == -1
+    assert lib.moba_forward(ctypes.byref(sh), one, one, one, one, one, one, z, one, one, big, z) == -1
+    assert lib.moba_forward(ctypes.byref(sh), one, one, one, one, one, one, one, one, z, big, z) == -3
+    assert lib.moba_backward(ctypes.byref(sh), one, one, one, one, one, one, one, one, one,
+                             one, one, z, one, big, z) == -1
+    assert lib.moba_backward(ctypes.byref(sh), one, one, one, one, one, one, one, one, one,
+                             one, one, one, one, ctypes.c_size_t(16), z) == -3
+    many = _shape(seqlen=32 * 5000).c()
+    assert lib.moba_topk(ctypes.byref(many), one, one, one, one, one, one, big, z) == -2
+
+
+def test_binding_raises(lib):
+    with pytest.raises(moba.MobaError):
+        moba.routes_per_slice(_shape(head_dim=80))

@@ -1,0 +1,251 @@
+"""GPU parity: every stage of the library, called through the C ABI, against the CPU
+oracle on the same seeded inputs.  Sizes here are ones the oracle finishes in
+seconds while still spanning several tiles, ragged query chunks and the degenerate
+cases; the benchmark-size checks live in test_gpu_full_size.py."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_11571_amd as moba
+import workloads
+from paper_2511_11571_amd import binding
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+REF = binding.FLAG_REFERENCE_KERNELS
+FLAGS = [pytest.param(0, id="default"), pytest.param(REF, id="plain")]
+
+
+def shape_of(w, flags=0):
+    return moba.Shape(w.batch, w.heads, w.N, w.d, w.B, w.k, w.conv_width,
+                      binding.BF16 if w.dtype == "bf16" else binding.F32, 0.0, flags)
+
+
+def dev(t):
+    return {k: (v.cuda() if v is not None else None) for k, v in t.items()}
+
+
+def np64(x):
+    a = x.detach().float().cpu().to(torch.float64).numpy()
+    return a.reshape((a.shape[0] * a.shape[1],) + a.shape[2:])
+
+
+def npi(x):
+    a = x.detach().cpu().numpy()
+    return a.reshape((a.shape[0] * a.shape[1],) + a.shape[2:])
+
+
+def oracle_inputs(orc, w, t):
+    Q, K, V, dO = (workloads.to_f64(t[x]) for x in ("Q", "K", "V", "dO"))
+    mode = orc.ROUND_BF16 if w.dtype == "bf16" else orc.ROUND_F32
+    Kp = K
+    if w.conv_width:
+        Kp = orc.key_conv(K, t["conv_w"].double().numpy(), w.heads, mode)
+    return Q, K, Kp, V, dO
+
+
+def to_io(w, a64, like):
+    """Oracle array [bh, ...] -> device tensor [b, h, ...] in the I/O type (exact when the
+    values are already representable, as K' is)."""
+    x = torch.from_numpy(a64).reshape(like.shape).to(w.torch_dtype)
+    return x.cuda()
+
+
+W = workloads.Workload
+
+SMALL = [
+    W("bf16_B32", 1, 2, 1024, 64, 32, 4, seed=11),
+    W("bf16_B64_d128", 2, 2, 768, 128, 64, 3, seed=12),
+    W("bf16_B16_ragged", 1, 3, 320, 64, 16, 5, seed=13),       # 320 = 256 + 64: ragged chunk
+    W("bf16_B128", 1, 2, 1024, 64, 128, 2, seed=14),
+    W("f32_B32", 1, 2, 512, 64, 32, 3, dtype="f32", seed=15),
+    W("f32_d128", 1, 1, 512, 128, 64, 2, dtype="f32", seed=16),
+    W("bf16_dense", 1, 2, 512, 64, 32, 100, seed=17),          # k >= n: full causal attention
+    W("bf16_k0", 1, 2, 512, 64, 32, 0, seed=18),               # own block only
+    W("bf16_one_block", 1, 1, 128, 64, 128, 4, seed=19),       # n = 1
+    W("bf16_B1", 1, 1, 256, 64, 1, 7, seed=20),                # centroid = key
+    W("bf16_skew", 1, 2, 2048, 64, 64, 6, skew=True, seed=21),
+]
+IDS = [w.name for w in SMALL]
+
+
+# ------------------------------------------------------------------ centroids / conv
+
+@pytest.mark.parametrize("w", SMALL[:6], ids=IDS[:6])
+def test_centroids_without_conv(oracle, w):
+    t = workloads.generate(w)
+    sh = shape_of(w)
+    Keff, cent = moba.centroids(sh, t["K"].cuda())
+    ref = oracle.centroids(workloads.to_f64(t["K"]), w.B)
+    assert parity.max_abs(np64(cent), ref) < 2e-6
+    # with no convolution an explicit K_eff buffer receives a copy of K
+    buf = torch.empty_like(t["K"]).cuda()
+    moba.centroids(sh, t["K"].cuda(), K_eff=buf)
+    assert torch.equal(buf.cpu(), t["K"])
+
+
+@pytest.mark.parametrize("dtype,d,width", [("bf16", 64, 4), ("bf16", 128, 3), ("bf16", 64, 1),
+                                           ("bf16", 64, 8), ("f32", 64, 5), ("f32", 128, 2)])
+def test_key_conv_and_centroids(oracle, dtype, d, width):
+    w = W("conv", 2, 3, 640, d, 32, 2, dtype=dtype, conv_width=width, seed=30 + width)
+    t = workloads.generate(w)
+    Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
+    Keff, cent = moba.centroids(shape_of(w), t["K"].cuda(), t["conv_w"].cuda())
+    got = np64(Keff)
+    if dtype == "bf16":
+        # the GPU rounds an fp32 result, the oracle a binary64 one: a 1-ulp difference is
+        # possible where the exact value sits next to a rounding boundary, and nowhere else
+        diff = got != Kp
+        assert diff.mean() < 2e-3
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(Kp), 1e-30))) - 7)
+        assert (np.abs(got - Kp)[diff] <= ulp[diff] * 1.0001).all()
+        clean = ~diff.reshape(w.bh, w.n, w.B, d).any(axis=2)          # blocks with no such element
+        ref = oracle.centroids(Kp, w.B)
+        assert np.abs(np64(cent) - ref)[clean].max() < 2e-6
+        assert np.abs(np64(cent) - ref).max() < 2e-6 + (np.abs(got - Kp).reshape(w.bh, w.n, w.B, d).sum(2) / w.B).max()
+    else:
+        assert parity.max_abs(got, Kp) < 2e-5
+        assert parity.max_abs(np64(cent), oracle.centroids(Kp, w.B)) < 2e-5
+
+
+# ------------------------------------------------------------------ routing
+
+@pytest.mark.parametrize("flags", FLAGS)
+@pytest.mark.parametrize("w", SMALL, ids=IDS)
+def test_topk_and_lists(oracle, w, flags):
+    t = workloads.generate(w)
+    Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
+    C = oracle.centroids(Kp, w.B)
+    ref_idx, kth = oracle.topk(Q, C, w.B, w.k)
+    sh = shape_of(w, flags)
+    cent = torch.from_numpy(C).float().reshape(w.batch, w.heads, w.n, w.d).cuda()
+    idx, off, ql = moba.topk(sh, t["Q"].cuda(), cent)
+    got = npi(idx).reshape(-1, w.k)
+    exact, exempt = parity.routing_check(oracle, got, ref_idx.reshape(-1, w.k), kth.reshape(-1),
+                                         Q, C, w.B)
+    assert exempt < 0.02
+    # rows are in ascending block order with the unused slots at the end
+    srt = np.where(got < 0, np.iinfo(np.int32).max, got)
+    assert (np.diff(srt, axis=-1) >= 0).all()
+    # the lists must be exactly the inverse of the GPU's own routing, ascending
+    g_off, g_ql = oracle.csr(npi(idx), w.B)
+    assert np.array_equal(npi(off), g_off)
+    assert np.array_equal(npi(ql), g_ql)
+
+
+def test_topk_ties_go_to_the_lower_block():
+    """K = 0 makes every gate score equal: the kept blocks must be 0..min(k,c)-1.  With
+    three bit-identical blocks the kept copies must be a prefix of them."""
+    w = W("ties", 1, 2, 1024, 64, 32, 5, seed=40)
+    t = workloads.generate(w)
+    sh = shape_of(w)
+    cent0 = torch.zeros((1, 2, w.n, w.d), dtype=torch.float32).cuda()
+    idx, _, _ = moba.topk(sh, t["Q"].cuda(), cent0)
+    got = npi(idx)
+    for tq in range(0, w.N, 7):
+        c = tq // w.B
+        want = list(range(min(w.k, c))) + [-1] * (w.k - min(w.k, c))
+        assert got[0, tq].tolist() == want and got[1, tq].tolist() == want
+    K = t["K"].clone()
+    for j in (9, 20):
+        K[:, :, j * w.B:(j + 1) * w.B] = K[:, :, 4 * w.B:5 * w.B]
+    _, cent = moba.centroids(sh, K.cuda())
+    idx, _, _ = moba.topk(sh, t["Q"].cuda(), cent)
+    got = npi(idx)
+    hits = 0
+    for s in range(2):
+        for tq in range(21 * w.B, w.N):
+            kept = sorted(set(got[s, tq].tolist()) & {4, 9, 20})
+            assert kept in ([], [4], [4, 9], [4, 9, 20])
+            hits += len(kept) > 0
+    assert hits > 0
+
+
+@pytest.mark.parametrize("w", [SMALL[0], SMALL[2], SMALL[6]], ids=[IDS[0], IDS[2], IDS[6]])
+def test_build_lists_from_a_given_routing(oracle, w):
+    t = workloads.generate(w)
+    Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
+    ref_idx, _ = oracle.topk(Q, oracle.centroids(Kp, w.B), w.B, w.k)     # best-first order
+    off, ql = moba.build_lists(shape_of(w), torch.from_numpy(ref_idx).reshape(
+        w.batch, w.heads, w.N, w.k).cuda())
+    r_off, r_ql = oracle.csr(ref_idx, w.B)
+    assert np.array_equal(npi(off), r_off)
+    assert np.array_equal(npi(ql), r_ql)
+
+
+# ------------------------------------------------------------------ attention at the oracle's routing
+
+@pytest.mark.parametrize("flags", FLAGS)
+@pytest.mark.parametrize("w", SMALL, ids=IDS)
+def test_forward_backward_at_oracle_routing(oracle, w, flags):
+    t = workloads.generate(w)
+    Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
+    ref_idx, _ = oracle.topk(Q, oracle.centroids(Kp, w.B), w.B, w.k)
+    sh = shape_of(w, flags)
+    d = dev(t)
+    idx = torch.from_numpy(ref_idx).reshape(w.batch, w.heads, w.N, w.k).cuda()
+    off, ql = moba.build_lists(sh, idx)
+    O, lse = moba.forward(sh, d["Q"], d["K"], d["V"], idx, off, ql)
+    rO, rlse = oracle.attn_fwd(Q, K, V, ref_idx, w.B, w.scale)
+    assert parity.max_abs(np64(O), rO) < parity.O_TOL[w.dtype]
+    assert parity.max_abs(np64(lse), rlse) < parity.LSE_TOL[w.dtype]
+    dQ, dK, dV = moba.backward(sh, d["Q"], d["K"], d["V"], O, lse, d["dO"], idx, off, ql)
+    # the oracle's backward starts from its own forward (binary64 O and lse)
+    rQ, rK, rV = oracle.attn_bwd(Q, K, V, ref_idx, dO, w.B, w.scale)
+    tol = parity.GRAD_TOL[w.dtype]
+    assert parity.rel_l2(np64(dQ), rQ) < tol
+    assert parity.rel_l2(np64(dK), rK) < tol
+    assert parity.rel_l2(np64(dV), rV) < tol
+
+
+# ------------------------------------------------------------------ the whole chain on its own routing
+
+@pytest.mark.parametrize("flags", FLAGS)
+@pytest.mark.parametrize("w", [W("chain_bf16", 1, 2, 1024, 64, 32, 4, backward=True, seed=50),
+                               W("chain_conv", 1, 2, 1024, 128, 64, 3, conv_width=4, seed=51),
+                               W("chain_f32", 1, 2, 512, 64, 32, 3, dtype="f32", seed=52)],
+                         ids=["bf16", "conv_d128", "f32"])
+def test_whole_chain(oracle, w, flags):
+    t = workloads.generate(w)
+    Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
+    sh = shape_of(w, flags)
+    d = dev(t)
+    Keff, cent = moba.centroids(sh, d["K"], d["conv_w"])
+    idx, off, ql = moba.topk(sh, d["Q"], cent)
+    O, lse = moba.forward(sh, d["Q"], Keff, d["V"], idx, off, ql)
+    dQ, dK, dV = moba.backward(sh, d["Q"], Keff, d["V"], O, lse, d["dO"], idx, off, ql)
+    C = oracle.centroids(Kp, w.B)
+    ref_idx, kth = oracle.topk(Q, C, w.B, w.k)
+    exact, exempt = parity.routing_check(oracle, npi(idx).reshape(-1, w.k), ref_idx.reshape(-1, w.k),
+                                         kth.reshape(-1), Q, C, w.B)
+    assert exempt < 0.02
+    rO, rlse = oracle.attn_fwd(Q, Kp, V, ref_idx, w.B, w.scale)
+    # rows whose routing is identical are comparable one by one
+    got_O = np64(O).reshape(-1, w.d)
+    assert np.abs(got_O - rO.reshape(-1, w.d))[exact].max() < parity.O_TOL[w.dtype]
+    assert np.abs(np64(lse).reshape(-1) - rlse.reshape(-1))[exact].max() < parity.LSE_TOL[w.dtype]
+    rQ, rK, rV = oracle.attn_bwd(Q, Kp, V, ref_idx, dO, w.B, w.scale)
+    tol = parity.GRAD_TOL[w.dtype] if exact.all() and not w.conv_width else 5e-2
+    assert parity.rel_l2(np64(dQ).reshape(-1, w.d)[exact], rQ.reshape(-1, w.d)[exact]) < tol
+    assert parity.rel_l2(np64(dK), rK) < tol
+    assert parity.rel_l2(np64(dV), rV) < tol
+
+
+def test_results_are_reproducible():
+    w = W("repro", 1, 2, 1024, 64, 32, 4, backward=True, seed=60)
+    d = dev(workloads.generate(w))
+    sh = shape_of(w)
+    outs = []
+    for _ in range(2):
+        Keff, cent = moba.centroids(sh, d["K"])
+        idx, off, ql = moba.topk(sh, d["Q"], cent)
+        O, lse = moba.forward(sh, d["Q"], Keff, d["V"], idx, off, ql)
+        grads = moba.backward(sh, d["Q"], Keff, d["V"], O, lse, d["dO"], idx, off, ql)
+        outs.append((idx, off, ql, O, lse) + tuple(grads))
+    for a, b in zip(*outs):
+        if a.dtype == torch.int32:
+            assert torch.equal(a, b)
+        else:
+            assert parity.rel_l2(np64(a) if a.dim() == 4 else a.double().cpu().numpy(),
+                                 np64(b) if b.dim() == 4 else b.double().cpu().numpy()) < 1e-5
