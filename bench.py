@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""MoBA forward+backward benchmark on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input that
+is already resident in HBM: key conv (if any) + centroids -> gate scores + top-k +
+key-block lists -> forward attention -> backward (D, dQ, dK/dV).  The default
+workload is the N = 32768, B = 32, top-k 64 configuration the headline metric is
+quoted on.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3      # MI355X fp32 vector
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5")
+    ap.add_argument("--reference-kernels", action="store_true",
+                    help="force the plain (non-MFMA) kernels")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-max-slices", type=int, default=0,
+                    help="cap on the (batch, head) slices of the CPU-baseline sample")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, t, target_seconds=15.0, max_slices=0):
+    """Times the CPU oracle, as it stands, on a bounded sample of the same workload: whole
+    (batch, head) slices, starting with slice 0 and adding slices until about
+    `target_seconds` of CPU work.  Each sampled slice runs the full chain (conv if any,
+    centroids, gate top-k, lists, forward, and for backward workloads D, dQ and dK/dV).
+    The rate uses the same effective flop count as the GPU metric (4d per attended pair
+    forward, 10d backward)."""
+    import numpy as np
+    import workloads
+    from oracle import moba_oracle as orc
+
+    def run(lo, hi):
+        b, h = w.batch, w.heads
+        sl = [(s // h, s % h) for s in range(lo, hi)]
+        pick = lambda x: np.stack([workloads.to_f64(t[x][bi:bi + 1, hi_:hi_ + 1])[0] for bi, hi_ in sl])
+        Q, K, V, dO = (pick(x) for x in ("Q", "K", "V", "dO"))
+        t0 = time.perf_counter()
+        Kp = K
+        if w.conv_width:
+            mode = orc.ROUND_BF16 if w.dtype == "bf16" else orc.ROUND_F32
+            cw = t["conv_w"].double().numpy()
+            Kp = np.stack([orc.key_conv(K[i:i + 1], cw[hh:hh + 1], 1, mode)[0]
+                           for i, (_, hh) in enumerate(sl)])
+        C = orc.centroids(Kp, w.B)
+        idx, _ = orc.topk(Q, C, w.B, w.k)
+        O, lse = orc.attn_fwd(Q, Kp, V, idx, w.B, w.scale)
+        if w.backward:
+            Dv = (dO * O).sum(-1)
+            off, ql = orc.csr(idx, w.B)
+            orc.attn_bwd_dq(Q, Kp, V, idx, dO, lse, Dv, w.B, w.scale)
+            orc.attn_bwd_dkdv(Q, Kp, V, dO, lse, Dv, off, ql, w.B, w.scale)
+        return time.perf_counter() - t0
+
+    dt = run(0, 1)
+    ns = 1
+    extra = min(w.bh - 1, int(target_seconds / max(dt, 1e-3)) - 1)
+    if max_slices:
+        extra = min(extra, max_slices - 1)
+    if extra > 0:
+        dt += run(1, 1 + extra)
+        ns += extra
+    pairs = ns * workloads.attended_pairs_per_slice(w.N, w.B, w.k)
+    flops = (4 + (10 if w.backward else 0)) * w.d * pairs
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+        "seconds": dt,
+        "sample": "%d of %d (batch, head) slices, whole chain (%scentroids, gate top-k, lists, "
+                  "forward%s); %d attended pairs" % (
+                      ns, w.bh, "key conv, " if w.conv_width else "",
+                      ", backward" if w.backward else "", pairs),
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (every (batch, head) slice is independent; "
+              "multi-GPU sharding is described in DESIGN.md but not built). Use --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads
+    import paper_2511_11571_amd as moba
+    from paper_2511_11571_amd import binding
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    w = workloads.CONFIGS[a.config]
+    t = workloads.generate(w)
+    d = {k: (v.cuda() if v is not None else None) for k, v in t.items()}
+    flags = binding.FLAG_REFERENCE_KERNELS if a.reference_kernels else 0
+    sh = moba.Shape(w.batch, w.heads, w.N, w.d, w.B, w.k, w.conv_width,
+                    binding.BF16 if w.dtype == "bf16" else binding.F32, 0.0, flags)
+    R = moba.routes_per_slice(sh)
+    ws_topk, ws_fwd, ws_bwd = (torch.empty(max(x, 256), dtype=torch.uint8, device="cuda")
+                               for x in moba.workspace_bytes(sh))
+    dev = torch.device("cuda")
+    Keff = torch.empty_like(d["K"]) if w.conv_width else None
+    cent = torch.empty((w.batch, w.heads, w.n, w.d), dtype=torch.float32, device=dev)
+    O = torch.empty_like(d["Q"])
+    lse = torch.empty((w.batch, w.heads, w.N), dtype=torch.float32, device=dev)
+    grads = tuple(torch.empty_like(d["Q"]) for _ in range(3))
+
+    stages = ["centroids", "topk_lists", "forward", "bwd_pre", "bwd_dq", "bwd_dkdv"]
+    if not w.backward:
+        stages = stages[:3]
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0)
+        Ke, c = moba.centroids(sh, d["K"], d["conv_w"], K_eff=Keff, out=cent)
+        mark(1)
+        idx, off, ql = moba.topk(sh, d["Q"], c, ws=ws_topk)
+        mark(2)
+        moba.forward(sh, d["Q"], Ke, d["V"], idx, off, ql, ws=ws_fwd, O=O, lse=lse)
+        mark(3)
+        if w.backward:
+            for i, part in enumerate((binding.BWD_PREPROCESS, binding.BWD_DQ, binding.BWD_DKDV)):
+                moba.backward(sh, d["Q"], Ke, d["V"], O, lse, d["dO"], idx, off, ql, ws=ws_bwd,
+                              out=grads, parts=part)
+                mark(4 + i)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)]
+          for _ in range(a.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(a.steps):
+        step(ev[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = 1e3 * wall / a.steps
+    stage_ms = {name: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(a.steps)) / a.steps
+                for i, name in enumerate(stages)}
+
+    pairs = w.bh * workloads.attended_pairs_per_slice(w.N, w.B, w.k)
+    fwd_flop = 4.0 * w.d * pairs
+    bwd_flop = 10.0 * w.d * pairs if w.backward else 0.0
+    value = (fwd_flop + bwd_flop) / (ms_step * 1e-3) / 1e12
+
+    # Roofline of the dominant kernel.  The dK/dV kernel executes 4 of the backward's
+    # matrix products (S, dP, dV, dK = 8d flop per pair), the dQ kernel 3 (S, dP, dQ = 6d),
+    # the forward 2 (4d).
+    kernel_flop = {"forward": fwd_flop, "bwd_dq": 6.0 * w.d * pairs, "bwd_dkdv": 8.0 * w.d * pairs}
+    dom = max((s for s in stages if s in kernel_flop), key=lambda s: stage_ms[s])
+    mfma = (w.dtype == "bf16") and not a.reference_kernels
+    peak = PEAK_BF16_TFLOPS if mfma else PEAK_FP32_TFLOPS
+    ach = kernel_flop[dom] / (stage_ms[dom] * 1e-3) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma" if mfma else "alu", "achieved": ach, "peak": peak,
+                "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                "ms_per_launch": stage_ms[dom], "flop_per_launch": kernel_flop[dom]}
+    # HBM-bound stages, for the record: algorithmic bytes / measured time
+    es = 2 if w.dtype == "bf16" else 4
+    cent_bytes = w.bh * (w.N * w.d * es * (2 if w.conv_width else 1) + w.n * w.d * 4)
+    topk_bytes = w.bh * (w.N * w.d * es + w.n * w.d * 4 + w.N * w.k * 4 + R * 4 + (w.n + 1) * 4)
+    hbm = {"centroids_GBs": cent_bytes / (stage_ms["centroids"] * 1e-3) / 1e9,
+           "topk_lists_GBs": topk_bytes / (stage_ms["topk_lists"] * 1e-3) / 1e9,
+           "peak_GBs": PEAK_HBM_GBS}
+
+    out = {
+        "metric": "moba_fwd_bwd_effective_tflops" if w.backward else "moba_fwd_effective_tflops",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "%s: batch %d, heads %d, N %d, d %d, B %d, top-k %d%s, %s" % (
+            w.name, w.batch, w.heads, w.N, w.d, w.B, w.k,
+            ", key conv W=%d" % w.conv_width if w.conv_width else "",
+            "forward+backward" if w.backward else "forward"),
+            "kernels": "plain" if a.reference_kernels else "default",
+            "attended_pairs": pairs, "fwd_gflop": fwd_flop / 1e9, "bwd_gflop": bwd_flop / 1e9},
+        "stage_ms": stage_ms,
+        "roofline": roofline,
+        "hbm_stages": hbm,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, t, max_slices=a.cpu_max_slices)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

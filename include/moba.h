@@ -133,6 +133,23 @@ int moba_backward(const moba_shape* shape, const void* Q, const void* K_eff, con
                   const int32_t* topk_idx, const int32_t* blk_off, const int32_t* blk_q,
                   void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * moba_backward split into its kernels, for callers that time or overlap them:
+ * `parts` is a bit set of MOBA_BWD_PREPROCESS (D = rowsum(dO o O) into the workspace),
+ * MOBA_BWD_DQ and MOBA_BWD_DKDV (both read D from the workspace, so PREPROCESS must have
+ * run on the same workspace first).  Output pointers of parts not requested may be NULL.
+ * moba_backward(...) is moba_backward_parts(..., MOBA_BWD_ALL).
+ */
+#define MOBA_BWD_PREPROCESS 1u
+#define MOBA_BWD_DQ 2u
+#define MOBA_BWD_DKDV 4u
+#define MOBA_BWD_ALL 7u
+int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
+                        const void* O, const float* lse, const void* dO,
+                        const int32_t* topk_idx, const int32_t* blk_off, const int32_t* blk_q,
+                        void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream,
+                        uint32_t parts);
+
 /* Static, NUL-terminated description of a status code. */
 const char* moba_strerror(int status);
 /* hipError_t value of the most recent failed HIP call on the calling thread (0 if none). */

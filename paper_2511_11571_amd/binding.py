@@ -73,7 +73,7 @@ def lib():
         L.moba_strerror.argtypes = [ctypes.c_int]
         L.moba_last_hip_error.restype = ctypes.c_int
         for name in ("moba_routes_per_slice", "moba_workspace_bytes", "moba_centroids", "moba_topk",
-                     "moba_build_lists", "moba_forward", "moba_backward"):
+                     "moba_build_lists", "moba_forward", "moba_backward", "moba_backward_parts"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -169,15 +169,25 @@ def forward(shape: Shape, Q, K_eff, V, idx, off, ql, ws=None, O=None, lse=None):
     return O, lse
 
 
-def backward(shape: Shape, Q, K_eff, V, O, lse, dO, idx, off, ql, ws=None, out=None):
-    """-> (dQ, dK, dV), each [b,h,N,d]."""
+BWD_PREPROCESS, BWD_DQ, BWD_DKDV, BWD_ALL = 1, 2, 4, 7
+
+
+def backward(shape: Shape, Q, K_eff, V, O, lse, dO, idx, off, ql, ws=None, out=None, parts=None):
+    """-> (dQ, dK, dV), each [b,h,N,d].  ``parts`` (a BWD_* bit set) runs only some of the
+    backward's kernels through moba_backward_parts."""
     for t in (Q, K_eff, V, O, dO):
         assert t.is_contiguous() and t.dtype == shape.torch_dtype
     dQ, dK, dV = out if out is not None else (torch.empty_like(Q), torch.empty_like(Q),
                                               torch.empty_like(Q))
     if ws is None:
         ws = _ws(workspace_bytes(shape)[2], Q)
-    _check(lib().moba_backward(ctypes.byref(shape.c()), _p(Q), _p(K_eff), _p(V), _p(O), _p(lse),
-                               _p(dO), _p(idx), _p(off), _p(ql), _p(dQ), _p(dK), _p(dV), _p(ws),
-                               ctypes.c_size_t(ws.numel()), _stream()), "moba_backward")
+    if parts is None:
+        _check(lib().moba_backward(ctypes.byref(shape.c()), _p(Q), _p(K_eff), _p(V), _p(O), _p(lse),
+                                   _p(dO), _p(idx), _p(off), _p(ql), _p(dQ), _p(dK), _p(dV), _p(ws),
+                                   ctypes.c_size_t(ws.numel()), _stream()), "moba_backward")
+    else:
+        _check(lib().moba_backward_parts(ctypes.byref(shape.c()), _p(Q), _p(K_eff), _p(V), _p(O),
+                                         _p(lse), _p(dO), _p(idx), _p(off), _p(ql), _p(dQ), _p(dK),
+                                         _p(dV), _p(ws), ctypes.c_size_t(ws.numel()), _stream(),
+                                         ctypes.c_uint32(parts)), "moba_backward_parts")
     return dQ, dK, dV

@@ -285,17 +285,21 @@ static hipError_t fwd_t(const Dims& s, const void* Q, const void* K, const void*
 template <typename T, int D>
 static hipError_t bwd_t(const Dims& s, const void* Q, const void* K, const void* V, const void* O,
                         const float* lse, const void* dO, const int32_t* idx, const int32_t* off,
-                        const int32_t* ql, void* dQ, void* dK, void* dV, float* Dvec, hipStream_t st)
+                        const int32_t* ql, void* dQ, void* dK, void* dV, float* Dvec, uint32_t parts,
+                        hipStream_t st)
 {
     const int64_t rows = (int64_t)s.bh * s.N;
     if (rows == 0) return hipSuccess;
     constexpr int RPB = 256 / (D / 8);
+    if (parts & MOBA_BWD_PREPROCESS)
     hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0,
                        st, (const T*)dO, (const T*)O, Dvec, rows);
     const size_t lds = sizeof(float) * 4 * (2 * D + 2 * kWave) + sizeof(int32_t) * 4 * (size_t)s.k;
+    if (parts & MOBA_BWD_DQ)
     hipLaunchKernelGGL((dq_reference_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)), dim3(256), lds,
                        st, (const T*)Q, (const T*)K, (const T*)V, (const T*)dO, lse, Dvec, idx,
                        (T*)dQ, s.N, s.B, s.k, s.scale, rows);
+    if (parts & MOBA_BWD_DKDV)
     hipLaunchKernelGGL((dkdv_reference_kernel<T, D>), dim3(s.n, (s.B + 31) / 32, s.bh), dim3(256), 0,
                        st, (const T*)Q, (const T*)K, (const T*)V, (const T*)dO, lse, Dvec, off, ql,
                        (T*)dK, (T*)dV, s.N, s.B, s.n, s.scale, s.R);
@@ -315,14 +319,15 @@ hipError_t launch_forward_reference(const Dims& s, const void* Q, const void* K,
 hipError_t launch_backward_reference(const Dims& s, const void* Q, const void* K, const void* V,
                                      const void* O, const float* lse, const void* dO,
                                      const int32_t* idx, const int32_t* off, const int32_t* ql,
-                                     void* dQ, void* dK, void* dV, float* Dvec, hipStream_t st)
+                                     void* dQ, void* dK, void* dV, float* Dvec, uint32_t parts,
+                                     hipStream_t st)
 {
     if (s.dtype == MOBA_BF16)
         return s.D == 64
-                   ? bwd_t<bf16_t, 64>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, st)
-                   : bwd_t<bf16_t, 128>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, st);
-    return s.D == 64 ? bwd_t<float, 64>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, st)
-                     : bwd_t<float, 128>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, st);
+                   ? bwd_t<bf16_t, 64>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, st)
+                   : bwd_t<bf16_t, 128>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, st);
+    return s.D == 64 ? bwd_t<float, 64>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, st)
+                     : bwd_t<float, 128>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, st);
 }
 
 }  // namespace moba

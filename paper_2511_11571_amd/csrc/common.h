@@ -125,7 +125,8 @@ hipError_t launch_forward_reference(const Dims& s, const void* Q, const void* K,
 hipError_t launch_backward_reference(const Dims& s, const void* Q, const void* K, const void* V,
                                      const void* O, const float* lse, const void* dO,
                                      const int32_t* idx, const int32_t* off, const int32_t* ql,
-                                     void* dQ, void* dK, void* dV, float* Dvec, hipStream_t st);
+                                     void* dQ, void* dK, void* dV, float* Dvec, uint32_t parts,
+                                     hipStream_t st);
 
 size_t lists_ws_bytes(const Dims& s);
 

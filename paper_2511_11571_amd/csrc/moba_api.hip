@@ -156,20 +156,34 @@ int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, cons
         launch_forward_reference(d, Q, K_eff, V, topk_idx, O, lse, (hipStream_t)stream));
 }
 
+int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
+                        const void* O, const float* lse, const void* dO, const int32_t* topk_idx,
+                        const int32_t* blk_off, const int32_t* blk_q, void* dQ, void* dK, void* dV,
+                        void* ws, size_t ws_bytes, void* stream, uint32_t parts)
+{
+    Dims d;
+    const int st = make_dims(shape, d);
+    if (st != MOBA_OK) return st;
+    if (parts == 0 || (parts & ~(uint32_t)MOBA_BWD_ALL)) return MOBA_EINVAL;
+    if (!Q || !K_eff || !V || !lse || !dO || !blk_off) return MOBA_EINVAL;
+    if ((parts & MOBA_BWD_PREPROCESS) && !O) return MOBA_EINVAL;
+    if ((parts & MOBA_BWD_DQ) && !dQ) return MOBA_EINVAL;
+    if ((parts & MOBA_BWD_DKDV) && (!dK || !dV)) return MOBA_EINVAL;
+    if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
+    if (d.R > 0 && !blk_q) return MOBA_EINVAL;
+    if (!ws || ws_bytes < bwd_ws_bytes(d)) return MOBA_EWORKSPACE;
+    return hip_status(launch_backward_reference(d, Q, K_eff, V, O, lse, dO, topk_idx, blk_off, blk_q,
+                                                dQ, dK, dV, (float*)ws, parts,
+                                                (hipStream_t)stream));
+}
+
 int moba_backward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
                   const void* O, const float* lse, const void* dO, const int32_t* topk_idx,
                   const int32_t* blk_off, const int32_t* blk_q, void* dQ, void* dK, void* dV,
                   void* ws, size_t ws_bytes, void* stream)
 {
-    Dims d;
-    const int st = make_dims(shape, d);
-    if (st != MOBA_OK) return st;
-    if (!Q || !K_eff || !V || !O || !lse || !dO || !dQ || !dK || !dV || !blk_off) return MOBA_EINVAL;
-    if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
-    if (d.R > 0 && !blk_q) return MOBA_EINVAL;
-    if (!ws || ws_bytes < bwd_ws_bytes(d)) return MOBA_EWORKSPACE;
-    return hip_status(launch_backward_reference(d, Q, K_eff, V, O, lse, dO, topk_idx, blk_off, blk_q,
-                                                dQ, dK, dV, (float*)ws, (hipStream_t)stream));
+    return moba_backward_parts(shape, Q, K_eff, V, O, lse, dO, topk_idx, blk_off, blk_q, dQ, dK, dV,
+                               ws, ws_bytes, stream, MOBA_BWD_ALL);
 }
 
 }  // extern "C"

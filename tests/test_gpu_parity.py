@@ -121,8 +121,8 @@ def test_topk_and_lists(oracle, w, flags):
     sh = shape_of(w, flags)
     cent = torch.from_numpy(C).float().reshape(w.batch, w.heads, w.n, w.d).cuda()
     idx, off, ql = moba.topk(sh, t["Q"].cuda(), cent)
-    got = npi(idx).reshape(-1, w.k)
-    exact, exempt = parity.routing_check(oracle, got, ref_idx.reshape(-1, w.k), kth.reshape(-1),
+    got = npi(idx).reshape(w.bh * w.N, w.k)
+    exact, exempt = parity.routing_check(oracle, got, ref_idx.reshape(w.bh * w.N, w.k), kth.reshape(-1),
                                          Q, C, w.B)
     assert exempt < 0.02
     # rows are in ascending block order with the unused slots at the end
@@ -217,7 +217,7 @@ def test_whole_chain(oracle, w, flags):
     dQ, dK, dV = moba.backward(sh, d["Q"], Keff, d["V"], O, lse, d["dO"], idx, off, ql)
     C = oracle.centroids(Kp, w.B)
     ref_idx, kth = oracle.topk(Q, C, w.B, w.k)
-    exact, exempt = parity.routing_check(oracle, npi(idx).reshape(-1, w.k), ref_idx.reshape(-1, w.k),
+    exact, exempt = parity.routing_check(oracle, npi(idx).reshape(w.bh * w.N, w.k), ref_idx.reshape(w.bh * w.N, w.k),
                                          kth.reshape(-1), Q, C, w.B)
     assert exempt < 0.02
     rO, rlse = oracle.attn_fwd(Q, Kp, V, ref_idx, w.B, w.scale)
