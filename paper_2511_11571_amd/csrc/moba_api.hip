@@ -3,7 +3,7 @@
 // exercised on a machine without a GPU.
 #include <math.h>
 
-#include "common.h"
+#include "mfma.h"
 
 using namespace moba;
 
@@ -58,7 +58,11 @@ int make_dims(const moba_shape* sh, Dims& d)
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 size_t topk_ws_bytes(const Dims& d) { return align256(lists_ws_bytes(d)); }
-size_t fwd_ws_bytes(const Dims&) { return 256; }
+// forward: slot-ordered transposed copy of V for the MFMA kernel
+size_t fwd_ws_bytes(const Dims& d)
+{
+    return mfma_path(d) ? align256(sizeof(bf16_t) * (size_t)d.bh * d.N * d.D) : 256;
+}
 size_t bwd_ws_bytes(const Dims& d) { return align256(sizeof(float) * (size_t)d.bh * d.N); }
 
 }  // namespace
@@ -152,6 +156,8 @@ int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, cons
     if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
     if (d.R > 0 && !blk_q) return MOBA_EINVAL;
     if (!ws || ws_bytes < fwd_ws_bytes(d)) return MOBA_EWORKSPACE;
+    if (mfma_path(d))
+        return hip_status(launch_forward_mfma(d, Q, K_eff, V, ws, topk_idx, O, lse, (hipStream_t)stream));
     return hip_status(
         launch_forward_reference(d, Q, K_eff, V, topk_idx, O, lse, (hipStream_t)stream));
 }

@@ -249,3 +249,30 @@ def test_results_are_reproducible():
         else:
             assert parity.rel_l2(np64(a) if a.dim() == 4 else a.double().cpu().numpy(),
                                  np64(b) if b.dim() == 4 else b.double().cpu().numpy()) < 1e-5
+
+
+@pytest.mark.parametrize("flags", FLAGS)
+def test_logit_far_above_the_own_block(oracle, flags):
+    """A routed key whose logit exceeds everything in the query's own block by ~80 (natural
+    log units): the fast forward path cannot represent exp(80) relative to its per-row
+    reference and must hand the row to its exact fallback."""
+    w = W("outlier", 1, 2, 1024, 64, 32, 4, backward=True, seed=70)
+    t = workloads.generate(w)
+    for tq, u in ((700, 100), (701, 333), (1023, 5)):
+        t["K"][0, :, u] = (10.0 * t["Q"][0, :, tq].float()).to(torch.bfloat16)
+    Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
+    ref_idx, _ = oracle.topk(Q, oracle.centroids(Kp, w.B), w.B, w.k)
+    assert 100 // w.B in ref_idx[0, 700] and 333 // w.B in ref_idx[1, 701]
+    sh = shape_of(w, flags)
+    d = dev(t)
+    idx = torch.from_numpy(ref_idx).reshape(w.batch, w.heads, w.N, w.k).cuda()
+    off, ql = moba.build_lists(sh, idx)
+    O, lse = moba.forward(sh, d["Q"], d["K"], d["V"], idx, off, ql)
+    rO, rlse = oracle.attn_fwd(Q, K, V, ref_idx, w.B, w.scale)
+    assert rlse[0, 700] > 60
+    assert parity.max_abs(np64(O), rO) < parity.O_TOL[w.dtype]
+    assert parity.max_abs(np64(lse), rlse) < 1e-2
+    dQ, dK, dV = moba.backward(sh, d["Q"], d["K"], d["V"], O, lse, d["dO"], idx, off, ql)
+    rQ, rK, rV = oracle.attn_bwd(Q, K, V, ref_idx, dO, w.B, w.scale)
+    for a, b in ((dQ, rQ), (dK, rK), (dV, rV)):
+        assert parity.rel_l2(np64(a), b) < parity.GRAD_TOL[w.dtype]
