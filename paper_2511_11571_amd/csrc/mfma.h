@@ -69,9 +69,11 @@ __host__ __device__ __forceinline__ constexpr int64_t slot_major_offset(int64_t 
     return (kap * (D / 16) + mt) * 512 + (int64_t)lane * 8;
 }
 
-hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, hipStream_t st);
+hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, uint32_t* vmax,
+                                  hipStream_t st);
+size_t forward_mfma_ws_bytes(const Dims& s);
 hipError_t launch_forward_mfma(const Dims& s, const void* Q, const void* K, const void* V,
-                               void* Vt, const int32_t* idx, void* O, float* lse, hipStream_t st);
+                               void* ws, const int32_t* idx, void* O, float* lse, hipStream_t st);
 
 // shapes the MFMA kernels cover: bf16 I/O and key blocks made of whole 32-key groups
 inline bool mfma_path(const Dims& s)

@@ -61,7 +61,7 @@ size_t topk_ws_bytes(const Dims& d) { return align256(lists_ws_bytes(d)); }
 // forward: slot-ordered transposed copy of V for the MFMA kernel
 size_t fwd_ws_bytes(const Dims& d)
 {
-    return mfma_path(d) ? align256(sizeof(bf16_t) * (size_t)d.bh * d.N * d.D) : 256;
+    return mfma_path(d) ? align256(forward_mfma_ws_bytes(d)) : 256;
 }
 size_t bwd_ws_bytes(const Dims& d) { return align256(sizeof(float) * (size_t)d.bh * d.N); }
 
