@@ -72,13 +72,6 @@ __global__ __launch_bounds__(256) void absmax_kernel(const bf16_t* __restrict__ 
     }
 }
 
-// exponent e with |x| * 2^-e <= 1 for every |x| <= vmax (vmax given as fp32 bits)
-__device__ __forceinline__ int scale_exponent(uint32_t vmax_bits)
-{
-    const int E = (int)((vmax_bits >> 23) & 0xffu);
-    return E == 0 ? 0 : E - 127 + 1;
-}
-
 template <int D>
 __global__ __launch_bounds__(256) void slot_major_copy_kernel(const bf16_t* __restrict__ X,
                                                               const uint32_t* __restrict__ vmax,
@@ -115,30 +108,35 @@ __global__ __launch_bounds__(256) void slot_major_copy_kernel(const bf16_t* __re
     }
 }
 
+// vmax[bh][D] <- largest magnitude of each channel of X, as fp32 bits
+hipError_t launch_absmax(const Dims& s, const void* X, uint32_t* vmax, hipStream_t st)
+{
+    if (s.N == 0) return hipSuccess;
+    const int cnt = s.bh * s.D, rows_per_wg = 1024;
+    hipLaunchKernelGGL(zero_words_kernel, dim3((cnt + 255) / 256), dim3(256), 0, st, vmax, cnt);
+    dim3 grid((s.N + rows_per_wg - 1) / rows_per_wg, s.bh);
+    if (s.D == 64)
+        hipLaunchKernelGGL(absmax_kernel<64>, grid, dim3(256), 0, st, (const bf16_t*)X, vmax, s.N,
+                           rows_per_wg);
+    else
+        hipLaunchKernelGGL(absmax_kernel<128>, grid, dim3(256), 0, st, (const bf16_t*)X, vmax, s.N,
+                           rows_per_wg);
+    return hipGetLastError();
+}
+
 // Xt <- slot-ordered transposed copy of X, each channel scaled by 2^-e (e from its largest
-// magnitude, written as fp32 bits to vmax[bh][D]); vmax == nullptr: plain copy.
-hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, uint32_t* vmax,
+// magnitude vmax[bh][D], fp32 bits); vmax == nullptr: plain copy.
+hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, const uint32_t* vmax,
                                   hipStream_t st)
 {
     const int64_t gps = s.N / 32, groups = (int64_t)s.bh * gps;
     if (groups == 0) return hipSuccess;
-    if (vmax) {
-        const int cnt = s.bh * s.D, rows_per_wg = 1024;
-        hipLaunchKernelGGL(zero_words_kernel, dim3((cnt + 255) / 256), dim3(256), 0, st, vmax, cnt);
-        dim3 grid((s.N + rows_per_wg - 1) / rows_per_wg, s.bh);
-        if (s.D == 64)
-            hipLaunchKernelGGL(absmax_kernel<64>, grid, dim3(256), 0, st, (const bf16_t*)X, vmax, s.N,
-                               rows_per_wg);
-        else
-            hipLaunchKernelGGL(absmax_kernel<128>, grid, dim3(256), 0, st, (const bf16_t*)X, vmax, s.N,
-                               rows_per_wg);
-    }
     if (s.D == 64)
         hipLaunchKernelGGL(slot_major_copy_kernel<64>, dim3((unsigned)groups), dim3(256), 0, st,
-                           (const bf16_t*)X, (const uint32_t*)vmax, (bf16_t*)Xt, gps);
+                           (const bf16_t*)X, vmax, (bf16_t*)Xt, gps);
     else
         hipLaunchKernelGGL(slot_major_copy_kernel<128>, dim3((unsigned)groups), dim3(256), 0, st,
-                           (const bf16_t*)X, (const uint32_t*)vmax, (bf16_t*)Xt, gps);
+                           (const bf16_t*)X, vmax, (bf16_t*)Xt, gps);
     return hipGetLastError();
 }
 
@@ -407,7 +405,9 @@ hipError_t launch_forward_mfma(const Dims& s, const void* Q, const void* K, cons
 {
     const size_t vt_bytes = (sizeof(bf16_t) * (size_t)s.bh * s.N * s.D + 255) & ~(size_t)255;
     uint32_t* vmax = reinterpret_cast<uint32_t*>((char*)ws + vt_bytes);
-    hipError_t e = launch_slot_major_copy(s, V, ws, vmax, st);
+    hipError_t e = launch_absmax(s, V, vmax, st);
+    if (e != hipSuccess) return e;
+    e = launch_slot_major_copy(s, V, ws, vmax, st);
     if (e != hipSuccess) return e;
     return s.D == 64 ? fwd_launch<64>(s, Q, K, ws, vmax, idx, O, lse, st)
                      : fwd_launch<128>(s, Q, K, ws, vmax, idx, O, lse, st);

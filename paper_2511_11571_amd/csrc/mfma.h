@@ -57,6 +57,13 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
+// exponent e with |x| * 2^-e <= 1 for every |x| <= vmax (vmax >= 0 given as fp32 bits)
+__device__ __forceinline__ int scale_exponent(uint32_t vmax_bits)
+{
+    const int E = (int)((vmax_bits >> 23) & 0xffu);
+    return E == 0 ? 0 : E - 127 + 1;
+}
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -69,11 +76,16 @@ __host__ __device__ __forceinline__ constexpr int64_t slot_major_offset(int64_t 
     return (kap * (D / 16) + mt) * 512 + (int64_t)lane * 8;
 }
 
-hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, uint32_t* vmax,
+hipError_t launch_absmax(const Dims& s, const void* X, uint32_t* vmax, hipStream_t st);
+hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, const uint32_t* vmax,
                                   hipStream_t st);
 size_t forward_mfma_ws_bytes(const Dims& s);
 hipError_t launch_forward_mfma(const Dims& s, const void* Q, const void* K, const void* V,
                                void* ws, const int32_t* idx, void* O, float* lse, hipStream_t st);
+
+size_t backward_mfma_ws_bytes(const Dims& s);
+hipError_t launch_dq_mfma(const Dims& s, const void* Q, const void* K, const void* V, const void* dO,
+                          const float* lse, const int32_t* idx, void* dQ, void* ws, hipStream_t st);
 
 // shapes the MFMA kernels cover: bf16 I/O and key blocks made of whole 32-key groups
 inline bool mfma_path(const Dims& s)

@@ -63,7 +63,10 @@ size_t fwd_ws_bytes(const Dims& d)
 {
     return mfma_path(d) ? align256(forward_mfma_ws_bytes(d)) : 256;
 }
-size_t bwd_ws_bytes(const Dims& d) { return align256(sizeof(float) * (size_t)d.bh * d.N); }
+size_t bwd_ws_bytes(const Dims& d)
+{
+    return mfma_path(d) ? align256(backward_mfma_ws_bytes(d)) : align256(sizeof(float) * (size_t)d.bh * d.N);
+}
 
 }  // namespace
 
@@ -178,9 +181,24 @@ int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_ef
     if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
     if (d.R > 0 && !blk_q) return MOBA_EINVAL;
     if (!ws || ws_bytes < bwd_ws_bytes(d)) return MOBA_EWORKSPACE;
+    hipStream_t hs = (hipStream_t)stream;
+    uint32_t plain = parts;
+    if (mfma_path(d)) {
+        // D first (plain row-dot kernel), then the MFMA kernels that exist; the rest stays plain
+        if (parts & MOBA_BWD_PREPROCESS) {
+            hipError_t e = launch_backward_reference(d, Q, K_eff, V, O, lse, dO, topk_idx, blk_off, blk_q,
+                                                     dQ, dK, dV, (float*)ws, MOBA_BWD_PREPROCESS, hs);
+            if (e != hipSuccess) return hip_status(e);
+        }
+        if (parts & MOBA_BWD_DQ) {
+            hipError_t e = launch_dq_mfma(d, Q, K_eff, V, dO, lse, topk_idx, dQ, ws, hs);
+            if (e != hipSuccess) return hip_status(e);
+        }
+        plain = parts & MOBA_BWD_DKDV;
+        if (!plain) return MOBA_OK;
+    }
     return hip_status(launch_backward_reference(d, Q, K_eff, V, O, lse, dO, topk_idx, blk_off, blk_q,
-                                                dQ, dK, dV, (float*)ws, parts,
-                                                (hipStream_t)stream));
+                                                dQ, dK, dV, (float*)ws, plain, hs));
 }
 
 int moba_backward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
