@@ -87,6 +87,10 @@ size_t backward_mfma_ws_bytes(const Dims& s);
 hipError_t launch_dq_mfma(const Dims& s, const void* Q, const void* K, const void* V, const void* dO,
                           const float* lse, const int32_t* idx, void* dQ, void* ws, hipStream_t st);
 
+hipError_t launch_dkdv_mfma(const Dims& s, const void* Q, const void* K, const void* V,
+                            const void* dO, const float* lse, const float* Dv, const int32_t* off,
+                            const int32_t* ql, void* dK, void* dV, hipStream_t st);
+
 // shapes the MFMA kernels cover: bf16 I/O and key blocks made of whole 32-key groups
 inline bool mfma_path(const Dims& s)
 {

@@ -194,8 +194,12 @@ int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_ef
             hipError_t e = launch_dq_mfma(d, Q, K_eff, V, dO, lse, topk_idx, dQ, ws, hs);
             if (e != hipSuccess) return hip_status(e);
         }
-        plain = parts & MOBA_BWD_DKDV;
-        if (!plain) return MOBA_OK;
+        if (parts & MOBA_BWD_DKDV) {
+            hipError_t e = launch_dkdv_mfma(d, Q, K_eff, V, dO, lse, (const float*)ws, blk_off, blk_q,
+                                            dK, dV, hs);
+            if (e != hipSuccess) return hip_status(e);
+        }
+        return MOBA_OK;
     }
     return hip_status(launch_backward_reference(d, Q, K_eff, V, O, lse, dO, topk_idx, blk_off, blk_q,
                                                 dQ, dK, dV, (float*)ws, plain, hs));
