@@ -99,7 +99,8 @@ def test_key_conv_and_centroids(oracle, dtype, d, width):
         diff = got != Kp
         assert diff.mean() < 2e-3
         ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(Kp), 1e-30))) - 7)
-        assert (np.abs(got - Kp)[diff] <= ulp[diff] * 1.0001).all()
+        # plus the fp32 evaluation error itself where k + SiLU(.) nearly cancels
+        assert (np.abs(got - Kp)[diff] <= ulp[diff] * 1.0001 + 1e-6 * (1 + np.abs(K))[diff]).all()
         clean = ~diff.reshape(w.bh, w.n, w.B, d).any(axis=2)          # blocks with no such element
         ref = oracle.centroids(Kp, w.B)
         assert np.abs(np64(cent) - ref)[clean].max() < 2e-6
