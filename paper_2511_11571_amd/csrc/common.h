@@ -103,6 +103,15 @@ __device__ __forceinline__ int lanes_below(uint64_t mask)
                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
 
+// monotone map of a gate score to uint32 (larger score <=> larger key); -0 is folded into +0
+// first so that equal scores always have equal keys
+__device__ __forceinline__ uint32_t order_key(float s)
+{
+    s += 0.0f;
+    uint32_t b = __float_as_uint(s);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
 // ---- host-side view of a validated shape ------------------------------------------
 struct Dims {
     int bh, heads, N, D, B, n, k, W;

@@ -91,6 +91,11 @@ hipError_t launch_dkdv_mfma(const Dims& s, const void* Q, const void* K, const v
                             const void* dO, const float* lse, const float* Dv, const int32_t* off,
                             const int32_t* ql, void* dK, void* dV, hipStream_t st);
 
+size_t topk_mfma_ws_bytes(const Dims& s);
+bool topk_mfma_supported(const Dims& s);
+hipError_t launch_topk_mfma(const Dims& s, const void* Q, const float* cent, int32_t* idx, void* ws,
+                            hipStream_t st);
+
 // shapes the MFMA kernels cover: bf16 I/O and key blocks made of whole 32-key groups
 inline bool mfma_path(const Dims& s)
 {

@@ -57,7 +57,11 @@ int make_dims(const moba_shape* sh, Dims& d)
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-size_t topk_ws_bytes(const Dims& d) { return align256(lists_ws_bytes(d)); }
+// top-k: [chunk x block counts of the list builder][three bf16 terms of the centroids]
+size_t topk_ws_bytes(const Dims& d)
+{
+    return align256(lists_ws_bytes(d)) + align256(topk_mfma_ws_bytes(d));
+}
 // forward: slot-ordered transposed copy of V for the MFMA kernel
 size_t fwd_ws_bytes(const Dims& d)
 {
@@ -143,7 +147,10 @@ int moba_topk(const moba_shape* shape, const void* Q, const float* centroids, in
     if (d.R > 0 && !blk_q) return MOBA_EINVAL;
     if (d.n > kMaxBlocks) return MOBA_EUNSUPPORTED;
     if (!ws || ws_bytes < topk_ws_bytes(d)) return MOBA_EWORKSPACE;
-    hipError_t e = launch_topk_reference(d, Q, centroids, topk_idx, (hipStream_t)stream);
+    hipError_t e = topk_mfma_supported(d)
+                       ? launch_topk_mfma(d, Q, centroids, topk_idx, (char*)ws + align256(lists_ws_bytes(d)),
+                                          (hipStream_t)stream)
+                       : launch_topk_reference(d, Q, centroids, topk_idx, (hipStream_t)stream);
     if (e != hipSuccess) return hip_status(e);
     return hip_status(launch_build_lists(d, topk_idx, blk_off, blk_q, ws, (hipStream_t)stream));
 }

@@ -1,0 +1,278 @@
+// Gate scoring and causal top-k on bf16 MFMA (paper Section 2; Appendix C.1, fused
+// top-k selection: scores are produced tile by tile and never written to memory).
+//
+// Scores must be fp32-accurate (the routing is compared with a 1e-4 score gap), so the
+// fp32 centroids are split into three bf16 terms hi + mid + lo (24 mantissa bits); the
+// queries are bf16 already, every product is exact in fp32 and only the fp32 accumulation
+// rounds.  One wave owns 64 consecutive queries and sweeps the centroid tiles of their
+// past blocks: 16 blocks x 64 queries per step, 3 terms x d/32 MFMAs per 16 queries.
+//
+// Selection replaces the paper's per-row insertion sort (k = 64 of ~1000 candidates makes
+// insertion far too long) by an exact radix search that recomputes the cheap scores instead
+// of storing them: each sweep histograms the order-preserving integer keys of the
+// still-undecided interval of every query into 64 bins (LDS integer atomics), the bin that
+// holds the k-th largest key becomes the next interval, and a query is decided as soon as
+// that bin holds exactly as many keys as are still needed (typically after two sweeps) or
+// its width reaches one key (ties; the lower block index wins).  A last sweep marks the kept
+// blocks in a per-query bit row, which is written out in ascending block order.
+#include "mfma.h"
+
+namespace moba {
+
+constexpr int kHistWords = 32;            // 64 bins of 16 bits per query
+constexpr int kTopkMfmaMaxBlocks = 2048;  // bit row of a query: at most 64 words
+
+__global__ void split3_kernel(const float* __restrict__ c, bf16_t* __restrict__ out, int64_t count)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    const float x = c[i];
+    const bf16_t hi = f32_to_bf16(x);
+    const float r1 = x - bf16_to_f32(hi);
+    const bf16_t mid = f32_to_bf16(r1);
+    const float r2 = r1 - bf16_to_f32(mid);
+    out[i] = hi;
+    out[count + i] = mid;
+    out[2 * count + i] = f32_to_bf16(r2);
+}
+
+// One sweep over the centroid tiles of a 64-query strip.  f(qt, sc, j0): sc[i] is the score of
+// query 16*qt + m16 against block j0 + i (j0 = 16*tile + 4*g).
+template <int D, typename F>
+__device__ __forceinline__ void sweep_tiles(const bf16_t* __restrict__ c3, int64_t cstride,
+                                            int64_t cbase, int n, int tile_lo, int tile_hi,
+                                            const Frag (&qb)[4][D / 32], int m16, int g, F f)
+{
+    constexpr int KS = D / 32;
+    for (int jt = tile_lo; jt < tile_hi; ++jt) {
+        const int row = min(16 * jt + m16, n - 1);
+        Frag a[3][KS];
+#pragma unroll
+        for (int term = 0; term < 3; ++term)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                a[term][ks].q = *reinterpret_cast<const uint4*>(c3 + term * cstride + (cbase + row) * D + 8 * g + 32 * ks);
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt) {
+            f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int term = 2; term >= 0; --term)       // smallest terms first
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) sc = mfma16(a[term][ks], qb[qt][ks], sc);
+            f(qt, sc, 16 * jt + 4 * g);
+        }
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void topk_mfma_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ c3, int64_t cstride,
+    int32_t* __restrict__ idx, int N, int B, int n, int k, int strips_per_slice,
+    int64_t total_strips, int Wn)
+{
+    extern __shared__ uint32_t smem[];
+    constexpr int KS = D / 32;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int m16 = lane & 15, g = lane >> 4;
+    const int64_t strip = (int64_t)blockIdx.x * 4 + wave;
+    if (strip >= total_strips) return;             // waves are independent: no workgroup barrier below
+    uint32_t* hist = smem + (size_t)wave * (64 * kHistWords + 6 * 64 + 64 * Wn);
+    uint32_t* st_lo = hist + 64 * kHistWords;
+    uint32_t* st_sh = st_lo + 64;
+    uint32_t* st_need = st_sh + 64;
+    uint32_t* st_state = st_need + 64;             // 0 undecided, 1 keep key >= lo, 2 keep key > lo + ties
+    uint32_t* st_past = st_state + 64;
+    uint32_t* st_nb = st_past + 64;                // bins of the current interval (64, fewer at the end)
+    uint32_t* selm = st_nb + 64;                   // [64][Wn] kept-block bits
+
+    const int s = (int)(strip / strips_per_slice);
+    const int t0 = (int)(strip % strips_per_slice) * 64;
+    const int rows_here = min(64, N - t0);
+    const int64_t cbase = (int64_t)s * n;
+    int32_t* out = idx + ((int64_t)s * N + t0) * k;
+
+    {   // lane = query: initial state
+        const int past = lane < rows_here ? (t0 + lane) / B : 0;
+        st_past[lane] = past;
+        st_lo[lane] = 0u;
+        st_sh[lane] = 26u;
+        st_nb[lane] = 64u;
+        st_need[lane] = (uint32_t)min(k, past);
+        st_state[lane] = past <= k ? 1u : 0u;      // few candidates: keep them all (every key >= 0)
+    }
+    for (int i = lane; i < 64 * Wn; i += kWave) selm[i] = 0u;
+    const int pmax = (t0 + rows_here - 1) / B;
+    const int ntile = (pmax + 15) / 16;
+
+    Frag qb[4][KS];
+#pragma unroll
+    for (int qt = 0; qt < 4; ++qt)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int64_t r = min(t0 + 16 * qt + m16, N - 1);
+            qb[qt][ks].q = *reinterpret_cast<const uint4*>(Q + ((int64_t)s * N + r) * D + 8 * g + 32 * ks);
+        }
+    __builtin_amdgcn_wave_barrier();
+
+    // ---- radix search for the k-th largest key of every undecided query
+    while (__any(st_state[lane] == 0u)) {
+        for (int i = 0; i < kHistWords; ++i) hist[lane * kHistWords + i] = 0u;
+        uint32_t lo4[4], sh4[4], past4[4], nb4[4];
+        bool act4[4];
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt) {
+            const int q = 16 * qt + m16;
+            lo4[qt] = st_lo[q]; sh4[qt] = st_sh[q]; past4[qt] = st_past[q]; nb4[qt] = st_nb[q];
+            act4[qt] = st_state[q] == 0u;
+        }
+        __builtin_amdgcn_wave_barrier();
+        sweep_tiles<D>(c3, cstride, cbase, n, 0, ntile, qb, m16, g,
+                       [&](int qt, const f32x4_t& sc, int j0) {
+                           if (!act4[qt]) return;
+                           uint32_t* row = hist + (16 * qt + m16) * kHistWords;
+#pragma unroll
+                           for (int i = 0; i < 4; ++i) {
+                               const uint32_t key = order_key(sc[i]);
+                               const uint32_t bin = (key - lo4[qt]) >> sh4[qt];
+                               if ((uint32_t)(j0 + i) < past4[qt] && key >= lo4[qt] && bin < nb4[qt])
+                                   atomicAdd(&row[bin >> 1], 1u << (16 * (bin & 1u)));
+                           }
+                       });
+        __builtin_amdgcn_wave_barrier();
+        if (st_state[lane] == 0u) {                  // lane = query: walk the bins from the top
+            const uint32_t need = st_need[lane], lo = st_lo[lane], sh = st_sh[lane];
+            uint32_t cum = 0, c = 0;
+            int b = 63;
+            for (; b >= 0; --b) {
+                c = (hist[lane * kHistWords + (b >> 1)] >> (16 * (b & 1))) & 0xffffu;
+                if (cum + c >= need) break;
+                cum += c;
+            }
+            b = max(b, 0);
+            const uint32_t need2 = need - cum;
+            st_lo[lane] = lo + ((uint32_t)b << sh);
+            st_need[lane] = need2;
+            if (c == need2) st_state[lane] = 1u;
+            else if (sh == 0u) st_state[lane] = 2u;
+            else if (sh >= 6u) st_sh[lane] = sh - 6u;            // 64 bins again
+            else { st_sh[lane] = 0u; st_nb[lane] = 1u << sh; }   // last step: one key per bin
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- mark the kept blocks
+    {
+        uint32_t lo4[4], past4[4], mode4[4];
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt) {
+            const int q = 16 * qt + m16;
+            lo4[qt] = st_lo[q]; past4[qt] = st_past[q]; mode4[qt] = st_state[q];
+        }
+        sweep_tiles<D>(c3, cstride, cbase, n, 0, ntile, qb, m16, g,
+                       [&](int qt, const f32x4_t& sc, int j0) {
+                           uint32_t bits = 0;
+#pragma unroll
+                           for (int i = 0; i < 4; ++i) {
+                               const uint32_t key = order_key(sc[i]);
+                               const bool keep = mode4[qt] == 1u ? key >= lo4[qt] : key > lo4[qt];
+                               if ((uint32_t)(j0 + i) < past4[qt] && keep) bits |= 1u << i;
+                           }
+                           if (bits) atomicOr(&selm[(16 * qt + m16) * Wn + (j0 >> 5)], bits << (j0 & 31));
+                       });
+        __builtin_amdgcn_wave_barrier();
+        // ties at the threshold: the lowest block indices among the equal keys, 1024 blocks at a time
+        if (__any(st_state[lane] == 2u)) {
+            for (int r0 = 0; r0 < 16 * ntile; r0 += 1024) {
+                for (int i = 0; i < kHistWords; ++i) hist[lane * kHistWords + i] = 0u;
+                __builtin_amdgcn_wave_barrier();
+                sweep_tiles<D>(c3, cstride, cbase, n, r0 / 16, min(ntile, (r0 + 1024) / 16), qb, m16, g,
+                               [&](int qt, const f32x4_t& sc, int j0) {
+                                   if (mode4[qt] != 2u) return;
+                                   uint32_t bits = 0;
+#pragma unroll
+                                   for (int i = 0; i < 4; ++i)
+                                       if ((uint32_t)(j0 + i) < past4[qt] && order_key(sc[i]) == lo4[qt]) bits |= 1u << i;
+                                   if (bits) atomicOr(&hist[(16 * qt + m16) * kHistWords + ((j0 - r0) >> 5)], bits << (j0 & 31));
+                               });
+                __builtin_amdgcn_wave_barrier();
+                if (st_state[lane] == 2u) {
+                    uint32_t need = st_need[lane];
+                    for (int w = 0; w < kHistWords && need > 0; ++w) {
+                        uint32_t word = hist[lane * kHistWords + w];
+                        while (word && need > 0) {
+                            const int b = __ffs(word) - 1;
+                            selm[lane * Wn + (r0 >> 5) + w] |= 1u << b;
+                            word &= word - 1;
+                            --need;
+                        }
+                    }
+                    st_need[lane] = need;
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    }
+
+    // ---- write the rows: kept blocks ascending, then -1
+    for (int q = 0; q < rows_here; ++q) {
+        uint32_t word = lane < Wn ? selm[q * Wn + lane] : 0u;
+        const int c = __popc(word);
+        int pre = c;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(pre, o, 64);
+            if (lane >= o) pre += v;
+        }
+        const int total = __shfl(pre, 63, 64);
+        int pos = pre - c;
+        int32_t* row = out + (int64_t)q * k;
+        while (word) {
+            const int b = __ffs(word) - 1;
+            if (pos < k) row[pos] = 32 * lane + b;
+            ++pos;
+            word &= word - 1;
+        }
+        for (int c0 = total + lane; c0 < k; c0 += kWave) row[c0] = -1;
+    }
+}
+
+size_t topk_mfma_ws_bytes(const Dims& s)
+{
+    return 3 * sizeof(bf16_t) * (size_t)s.bh * s.n * s.D;
+}
+
+bool topk_mfma_supported(const Dims& s)
+{
+    return s.dtype == MOBA_BF16 && !(s.flags & MOBA_FLAG_REFERENCE_KERNELS) &&
+           s.n <= kTopkMfmaMaxBlocks && s.k > 0;
+}
+
+template <int D>
+static hipError_t topk_launch(const Dims& s, const void* Q, const bf16_t* c3, int32_t* idx,
+                              hipStream_t st)
+{
+    const int sps = (s.N + 63) / 64;
+    const int64_t strips = (int64_t)sps * s.bh;
+    const int Wn = (s.n + 31) / 32;
+    const size_t lds = sizeof(uint32_t) * 4 * (size_t)(64 * kHistWords + 6 * 64 + 64 * Wn);
+    hipError_t e = hipFuncSetAttribute((const void*)topk_mfma_kernel<D>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((topk_mfma_kernel<D>), dim3((unsigned)((strips + 3) / 4)), dim3(256), lds, st,
+                       (const bf16_t*)Q, c3, (int64_t)s.bh * s.n * s.D, idx, s.N, s.B, s.n, s.k, sps,
+                       strips, Wn);
+    return hipGetLastError();
+}
+
+hipError_t launch_topk_mfma(const Dims& s, const void* Q, const float* cent, int32_t* idx, void* ws,
+                            hipStream_t st)
+{
+    const int64_t count = (int64_t)s.bh * s.n * s.D;
+    if (count == 0) return hipSuccess;
+    bf16_t* c3 = (bf16_t*)ws;
+    hipLaunchKernelGGL(split3_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, cent, c3,
+                       count);
+    return s.D == 64 ? topk_launch<64>(s, Q, c3, idx, st) : topk_launch<128>(s, Q, c3, idx, st);
+}
+
+}  // namespace moba

@@ -10,14 +10,6 @@ namespace moba {
 
 constexpr int kTopkMaxBlocks = 4096;   // LDS row length per wave
 
-// monotone map float -> uint32 (larger float <=> larger key); -0 is folded into +0 first
-__device__ __forceinline__ uint32_t order_key(float s)
-{
-    s += 0.0f;
-    uint32_t b = __float_as_uint(s);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-
 template <typename T, int D>
 __global__ __launch_bounds__(256) void topk_reference_kernel(
     const T* __restrict__ Q, const float* __restrict__ cent, int32_t* __restrict__ idx,
