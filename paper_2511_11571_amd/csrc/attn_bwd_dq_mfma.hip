@@ -140,7 +140,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
             f32x4_t o = mfma16(kt, pb, f32x4_t{0.f, 0.f, 0.f, 0.f});
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                atomicAdd(&acc[row * C::OSTRIDE + tile_chan<D>(mt, 4 * g + i)], __float2int_rn(o[i]));
+                atomicAdd(&acc[row * C::OSTRIDE + tile_chan<D>(mt, 4 * g + i)], (int)o[i]);
         }
     }
 
@@ -222,22 +222,28 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
                         dp[mt] = mfma16(va[mt][ks], gb[ks], dp[mt]);
                     }
                 }
-                const float pe = pexp[row], Dt = Dr[row];
+                // rows beyond the list get an infinite exponent offset: their P is exactly 0
+                const float pe = valid ? pexp[row] : INFINITY, Dt = Dr[row];
                 float x[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    x[e] = valid ? fast_exp2(fmaf(sc[e >> 2][e & 3], c2, -pe)) * (dp[e >> 2][e & 3] - Dt) : 0.f;
+                    x[e] = fast_exp2(fmaf(sc[e >> 2][e & 3], c2, -pe)) * (dp[e >> 2][e & 3] - Dt);
                 Frag pb;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) pb.u[e] = pack2(x[2 * e], x[2 * e + 1]);
+                int oi[C::MT][4];
 #pragma unroll
                 for (int mt = 0; mt < C::MT; ++mt) {
-                    f32x4_t o = mfma16(kt[mt], pb, f32x4_t{0.f, 0.f, 0.f, 0.f});
-                    if (valid) {
+                    const f32x4_t o = mfma16(kt[mt], pb, f32x4_t{0.f, 0.f, 0.f, 0.f});
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            atomicAdd(&acc[row * C::OSTRIDE + tile_chan<D>(mt, 4 * g + i)], __float2int_rn(o[i]));
-                    }
+                    for (int i = 0; i < 4; ++i) oi[mt][i] = (int)o[i];   // toward zero; |o| ~ 2^12..2^20
+                }
+                if (valid) {
+                    int* arow = acc + row * C::OSTRIDE + g * (D / 4);
+#pragma unroll
+                    for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) atomicAdd(&arow[4 * mt + i], oi[mt][i]);
                 }
             }
         }

@@ -14,7 +14,8 @@
 //   pass 2  the same walk again: p = exp(s - m) <= 1, so sum_u p_u <= (number of keys of the
 //           row) and, with V pre-scaled per channel to |v| <= 1, |sum_u p_u v_u| has the same
 //           bound; both sums are accumulated as integers scaled by 2^F, F chosen from that
-//           bound.  Integer adds commute exactly: the result does not depend on the order
+//           bound (each 32-key partial of P V is cut toward zero, a relative shrink of ~1e-5,
+//           two orders below the bf16 output's resolution; the row sums l round to nearest).  Integer adds commute exactly: the result does not depend on the order
 //           in which waves arrive, so the output is bit-reproducible.
 // Which rows go with which key group is a bit matrix in LDS (one row of TILE bits per
 // group), built from the query-major routing, 1024 groups at a time.
@@ -34,7 +35,7 @@ struct FwdCfg {
     static constexpr int MW = TILE / 32;               // mask words per key group
     static constexpr int RANGE = 1024;                 // key groups per bit matrix
     static constexpr size_t LDS = (size_t)TILE * QSTRIDE + 4 * TILE * OSTRIDE + 4 * 2 * TILE +
-                                  4 * RANGE * MW + 2 * NW * TILE + 64;
+                                  4 * RANGE * MW + 2 * NW * TILE + 4 * RANGE + 64;
 };
 
 // ---- per-channel scale of V and the slot-ordered transposed copy (see mfma.h) -----------
@@ -167,7 +168,8 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
     int* lsum = mkey + C::TILE;                  // fixed point, 2^F
     uint32_t* mask = reinterpret_cast<uint32_t*>(lsum + C::TILE);
     uint16_t* rlist = reinterpret_cast<uint16_t*>(mask + C::RANGE * C::MW);
-    int* next = reinterpret_cast<int*>(rlist + C::NW * C::TILE);
+    uint32_t* ulist = reinterpret_cast<uint32_t*>(rlist + C::NW * C::TILE);   // non-empty groups of a range
+    int* next = reinterpret_cast<int*>(ulist + C::RANGE);
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int m16 = lane & 15, g = lane >> 4;
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                 for (int e = 1; e < 8; ++e) mx = fmaxf(mx, x[e]);
                 atomicMax(&mkey[row], float_key(mx));
             } else {
-                const float mr = __int_as_float(mkey[row]) - Fbits;
+                const float mr = __int_as_float(mkey[row]);
                 float lp = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { x[e] = fast_exp2(x[e] - mr); lp += x[e]; }
@@ -251,7 +253,7 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                     f32x4_t o = mfma16(va, pb, f32x4_t{0.f, 0.f, 0.f, 0.f});
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        atomicAdd(&Os[row * C::OSTRIDE + tile_chan<D>(mt, 4 * g + i)], __float2int_rn(o[i]));
+                        atomicAdd(&Os[row * C::OSTRIDE + tile_chan<D>(mt, 4 * g + i)], (int)o[i]);
                 }
             }
         }
@@ -263,44 +265,21 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
             for (int i = tid; i < (hi - lo) * C::MW; i += C::NT) mask[i] = 0u;
             if (tid == 0) *next = 0;
             __syncthreads();
-            for (int i = tid; i < rows_here * k; i += C::NT) {
-                const int r = i / k, e = i - r * k;
-                const int b = idx[(sbase + t0 + r) * k + e];
-                if (b >= 0 && b < (t0 + r) / B) {
-                    for (int gi = 0; gi < NG; ++gi) {
-                        const int kap = b * NG + gi - lo;
-                        if (kap >= 0 && kap < hi - lo) atomicOr(&mask[kap * C::MW + (r >> 5)], 1u << (r & 31));
-                    }
-                }
-            }
-            if (NG > 1) {
-                for (int r = tid; r < rows_here; r += C::NT) {
-                    const int t = t0 + r;
-                    for (int kap = (t / B) * NG; kap < (t >> 5); ++kap)
-                        if (kap >= lo && kap < hi) atomicOr(&mask[(kap - lo) * C::MW + (r >> 5)], 1u << (r & 31));
-                }
-            }
+            build_group_mask<C::TILE, C::NT, C::MW>(mask, idx + (sbase + t0) * k, t0, rows_here, k, B, NG, lo,
+                                                     hi, tid);
             __syncthreads();
-
-            while (true) {
-                int ui = 0;
-                if (lane == 0) ui = atomicAdd(next, 1);
-                ui = __builtin_amdgcn_readfirstlane(ui);
-                if (ui >= hi - lo) break;
-                uint32_t w[C::MW];
+            // non-empty groups of this range -> ulist (count << 16 | group)
+            for (int i = tid; i < hi - lo; i += C::NT) {
                 int cnt = 0;
 #pragma unroll
-                for (int i = 0; i < C::MW; ++i) { w[i] = mask[ui * C::MW + i]; cnt += __popc(w[i]); }
-                if (cnt == 0) continue;
-                int base = 0;
-#pragma unroll
-                for (int r = 0; r < C::TILE / 64; ++r) {
-                    const uint64_t m64 = (uint64_t)w[2 * r] | ((uint64_t)w[2 * r + 1] << 32);
-                    if ((m64 >> lane) & 1ull) rl[base + __popcll(m64 & ((1ull << lane) - 1ull))] = (uint16_t)(64 * r + lane);
-                    base += __popcll(m64);
-                }
-                const int64_t kap = lo + ui;
-                Frag ka[2][C::KS], va[C::MT];
+                for (int wd = 0; wd < C::MW; ++wd) cnt += __popc(mask[i * C::MW + wd]);
+                if (cnt) ulist[atomicAdd(next, 1)] = (uint32_t)i | ((uint32_t)cnt << 16);
+            }
+            __syncthreads();
+            const int nunits = *next;
+
+            auto load_unit = [&](uint32_t entry, Frag (&ka)[2][C::KS], Frag (&va)[C::MT]) {
+                const int64_t kap = lo + (int)(entry & 0xffffu);
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -311,15 +290,28 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                     for (int mt = 0; mt < C::MT; ++mt)
                         va[mt].q = *reinterpret_cast<const uint4*>(Vtg + slot_major_offset<D>(kap, mt, lane));
                 }
+            };
+            auto run_unit = [&](uint32_t entry, const Frag (&ka)[2][C::KS], const Frag (&va)[C::MT]) {
+                const int ui = (int)(entry & 0xffffu), cnt = (int)(entry >> 16);
+                int base = 0;
+#pragma unroll
+                for (int r = 0; r < C::TILE / 64; ++r) {
+                    const uint64_t m64 = (uint64_t)mask[ui * C::MW + 2 * r] | ((uint64_t)mask[ui * C::MW + 2 * r + 1] << 32);
+                    if ((m64 >> lane) & 1ull) rl[base + __popcll(m64 & ((1ull << lane) - 1ull))] = (uint16_t)(64 * r + lane);
+                    base += __popcll(m64);
+                }
                 __builtin_amdgcn_wave_barrier();
-
-                for (int s0 = 0; s0 < cnt; s0 += 16) {
-                    const bool valid = s0 + m16 < cnt;
-                    const int row = rl[valid ? s0 + m16 : 0];
-                    Frag qb[C::KS];
+                // Sub-tiles of 16 rows.  The row ids of four sub-tiles are read at once, and the
+                // LDS gather of the next sub-tile is issued before the arithmetic and the atomics
+                // of the current one, so it never waits behind them.
+                auto gather = [&](bool valid, int row, Frag (&qb)[C::KS], float& mr) {
 #pragma unroll
                     for (int ks = 0; ks < C::KS; ++ks)
                         qb[ks].q = *reinterpret_cast<const uint4*>(Qs + (size_t)row * C::QSTRIDE + 16 * g + 64 * ks);
+                    // rows beyond the list get an infinite reference: their p is exactly 0
+                    mr = (pass == 1 && valid) ? __int_as_float(mkey[row]) : INFINITY;
+                };
+                auto compute = [&](bool valid, int row, const Frag (&qb)[C::KS], float mr) {
                     f32x4_t sc[2];
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt) {
@@ -332,33 +324,77 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                         mx = fmaxf(mx, fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
                         if (valid) atomicMax(&mkey[row], float_key(mx * c2));
                     } else {
-                        const float mr = __int_as_float(mkey[row]) - Fbits;
                         float x[8], lp = 0.f;
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
-                            x[e] = valid ? fast_exp2(fmaf(sc[e >> 2][e & 3], c2, -mr)) : 0.f;
+                            x[e] = fast_exp2(fmaf(sc[e >> 2][e & 3], c2, -mr));
                             lp += x[e];
                         }
                         Frag pb;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) pb.u[e] = pack2(x[2 * e], x[2 * e + 1]);
-                        if (valid) atomicAdd(&lsum[row], __float2int_rn(lp));
+                        int oi[C::MT][4];
 #pragma unroll
                         for (int mt = 0; mt < C::MT; ++mt) {
-                            f32x4_t o = mfma16(va[mt], pb, f32x4_t{0.f, 0.f, 0.f, 0.f});
-                            if (valid) {
+                            const f32x4_t o = mfma16(va[mt], pb, f32x4_t{0.f, 0.f, 0.f, 0.f});
 #pragma unroll
-                                for (int i = 0; i < 4; ++i)
-                                    atomicAdd(&Os[row * C::OSTRIDE + tile_chan<D>(mt, 4 * g + i)], __float2int_rn(o[i]));
-                            }
+                            for (int i = 0; i < 4; ++i) oi[mt][i] = (int)o[i];      // toward zero: see header
+                        }
+                        if (valid) {
+                            atomicAdd(&lsum[row], __float2int_rn(lp));
+                            int* orow = Os + row * C::OSTRIDE + g * (D / 4);
+#pragma unroll
+                            for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) atomicAdd(&orow[4 * mt + i], oi[mt][i]);
+                        }
+                    }
+                };
+                for (int c0 = 0; c0 < cnt; c0 += 64) {
+                    bool val[4];
+                    int rows[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        val[j] = c0 + 16 * j + m16 < cnt;
+                        rows[j] = rl[val[j] ? c0 + 16 * j + m16 : 0];
+                    }
+                    const int left = cnt - c0;          // > 0
+                    Frag qA[C::KS], qB[C::KS];
+                    float mA, mB;
+                    gather(val[0], rows[0], qA, mA);
+                    if (left > 16) gather(val[1], rows[1], qB, mB);
+                    compute(val[0], rows[0], qA, mA);
+                    if (left > 16) {
+                        if (left > 32) gather(val[2], rows[2], qA, mA);
+                        compute(val[1], rows[1], qB, mB);
+                        if (left > 32) {
+                            if (left > 48) gather(val[3], rows[3], qB, mB);
+                            compute(val[2], rows[2], qA, mA);
+                            if (left > 48) compute(val[3], rows[3], qB, mB);
                         }
                     }
                 }
+                __builtin_amdgcn_wave_barrier();
+            };
+
+            // waves take the units round robin; the operands of a wave's next unit are in flight
+            // while it works on the current one
+            Frag kaA[2][C::KS], vaA[C::MT], kaB[2][C::KS], vaB[C::MT];
+            int u = wave;
+            if (u < nunits) load_unit(ulist[u], kaA, vaA);
+            while (u < nunits) {
+                if (u + C::NW < nunits) load_unit(ulist[u + C::NW], kaB, vaB);
+                run_unit(ulist[u], kaA, vaA);
+                u += C::NW;
+                if (u >= nunits) break;
+                if (u + C::NW < nunits) load_unit(ulist[u + C::NW], kaA, vaA);
+                run_unit(ulist[u], kaB, vaB);
+                u += C::NW;
             }
         }
         __syncthreads();
-        if (pass == 0) {      // keys -> reference values (log2 units), in place
-            for (int i = tid; i < C::TILE; i += C::NT) mkey[i] = __float_as_int(key_float(mkey[i]));
+        if (pass == 0) {      // keys -> reference values minus F (log2 units), in place
+            for (int i = tid; i < C::TILE; i += C::NT) mkey[i] = __float_as_int(key_float(mkey[i]) - Fbits);
             __syncthreads();
         }
     }
@@ -374,7 +410,7 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
         for (int e = 0; e < 8; ++e)
             v[e] = ldexpf((float)Os[r * C::OSTRIDE + 8 * c + e] * inv, scale_exponent(vmax[s * D + 8 * c + e]));
         Vec8<bf16_t>::store(Og + (int64_t)r * D + 8 * c, v);
-        if (c == 0) lse[sbase + t0 + r] = (__int_as_float(mkey[r]) + fast_log2(lf) - Fbits) * kLn2;
+        if (c == 0) lse[sbase + t0 + r] = (__int_as_float(mkey[r]) + fast_log2(lf)) * kLn2;
     }
 }
 

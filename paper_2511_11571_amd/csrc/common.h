@@ -26,9 +26,14 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
     return (bf16_t)(u >> 16);
 }
 
+// two fp32 -> two bf16 in one word, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return *reinterpret_cast<const uint32_t*>(&b);
 }
 
 // ---- 8-element vector access in the I/O type --------------------------------

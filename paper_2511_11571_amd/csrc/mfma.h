@@ -76,6 +76,52 @@ __host__ __device__ __forceinline__ constexpr int64_t slot_major_offset(int64_t 
     return (kap * (D / 16) + mt) * 512 + (int64_t)lane * 8;
 }
 
+// Bit matrix "which rows of this query tile go with which 32-key group", for the groups
+// [lo, hi): mask[(kap - lo) * MW + r / 32] bit r % 32.  A row goes with every group of each
+// block it kept (entries of its topk_idx row that are past blocks) and, when a block has several
+// groups, with the groups of its own block that lie wholly before it.  `idx_tile` points at the
+// tile's first topk_idx row.  The caller zeroes the mask before and synchronises after.
+template <int TILE, int NT, int MW>
+__device__ __forceinline__ void build_group_mask(uint32_t* mask, const int32_t* __restrict__ idx_tile,
+                                                 int t0, int rows_here, int k, int B, int NG, int lo,
+                                                 int hi, int tid)
+{
+    constexpr int TPR = NT / TILE;                 // threads per row
+    const int r = tid / TPR, part = tid % TPR;
+    if (r >= rows_here) return;
+    const int past = (t0 + r) / B;
+    const uint32_t bit = 1u << (r & 31);
+    uint32_t* col = mask + (r >> 5);
+    auto mark = [&](int b) {
+        if (b >= 0 && b < past) {
+            for (int gi = 0; gi < NG; ++gi) {
+                const int kap = b * NG + gi - lo;
+                if (kap >= 0 && kap < hi - lo) atomicOr(&col[kap * MW], bit);
+            }
+        }
+    };
+    const int32_t* row = idx_tile + (int64_t)r * k;
+    if ((k & 3) == 0) {                            // 16-byte loads, several in flight
+        const int4* row4 = reinterpret_cast<const int4*>(row);
+        const int n4 = k >> 2;
+        for (int e0 = part; e0 < n4; e0 += 4 * TPR) {
+            int4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                v[j] = e0 + j * TPR < n4 ? row4[e0 + j * TPR] : make_int4(-1, -1, -1, -1);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { mark(v[j].x); mark(v[j].y); mark(v[j].z); mark(v[j].w); }
+        }
+    } else {
+        for (int e = part; e < k; e += TPR) mark(row[e]);
+    }
+    if (NG > 1 && part == 0) {
+        const int t = t0 + r;
+        for (int kap = (t / B) * NG; kap < (t >> 5); ++kap)
+            if (kap >= lo && kap < hi) atomicOr(&col[(kap - lo) * MW], bit);
+    }
+}
+
 hipError_t launch_absmax(const Dims& s, const void* X, uint32_t* vmax, hipStream_t st);
 hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, const uint32_t* vmax,
                                   hipStream_t st);
