@@ -135,13 +135,13 @@ def main():
         mark(0)
         Ke, c = moba.centroids(sh, d["K"], d["conv_w"], K_eff=Keff, out=cent)
         mark(1)
-        idx, off, ql = moba.topk(sh, d["Q"], c, ws=ws_topk)
+        idx, lists = moba.topk(sh, d["Q"], c, ws=ws_topk)
         mark(2)
-        moba.forward(sh, d["Q"], Ke, d["V"], idx, off, ql, ws=ws_fwd, O=O, lse=lse)
+        moba.forward(sh, d["Q"], Ke, d["V"], idx, lists, ws=ws_fwd, O=O, lse=lse)
         mark(3)
         if w.backward:
             for i, part in enumerate((binding.BWD_PREPROCESS, binding.BWD_DQ, binding.BWD_DKDV)):
-                moba.backward(sh, d["Q"], Ke, d["V"], O, lse, d["dO"], idx, off, ql, ws=ws_bwd,
+                moba.backward(sh, d["Q"], Ke, d["V"], O, lse, d["dO"], idx, lists, ws=ws_bwd,
                               out=grads, parts=part)
                 mark(4 + i)
 

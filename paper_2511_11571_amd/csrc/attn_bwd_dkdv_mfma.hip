@@ -81,30 +81,54 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
             dVT[mt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         }
 
-    for (int a0 = 32 * wave; a0 < total; a0 += 32 * C::NW) {
-        // the two query rows this lane gathers (step rows m16 and 16 + m16)
-        int t[2];
-        bool ok[2];
+    // The gathers are the long pole (two dependent global loads: list entry, then the row), so
+    // they run ahead of the arithmetic: row ids two steps ahead, rows one step ahead.
+    auto ids = [&](int a0, int (&t)[2], bool (&ok)[2]) {
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
             const int a = a0 + 16 * qt + m16;
             ok[qt] = a < total;
             t[qt] = !ok[qt] ? own0 : (a < nlist ? qs[lo + a] : own0 + (a - nlist));
         }
-        Frag qa[2][C::KS], ga[2][C::KS];
+    };
+    auto fetch = [&](const int (&t)[2], const bool (&ok)[2], Frag (&qa)[2][C::KS], Frag (&ga)[2][C::KS],
+                     float (&lv)[2], float (&dv)[2]) {
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
+        for (int qt = 0; qt < 2; ++qt) {
 #pragma unroll
             for (int ks = 0; ks < C::KS; ++ks) {
                 const int64_t o = (sbase + t[qt]) * D + 8 * g + 32 * ks;
                 qa[qt][ks].q = *reinterpret_cast<const uint4*>(Q + o);
                 ga[qt][ks].q = *reinterpret_cast<const uint4*>(dO + o);
             }
+            lv[qt] = INFINITY;                        // rows past the list: P = 0
+            dv[qt] = 0.f;
+            if (g == 0 && ok[qt]) {
+                lv[qt] = lse[sbase + t[qt]] * kLog2e;
+                dv[qt] = Dv[sbase + t[qt]];
+            }
+        }
+    };
+    const int stride = 32 * C::NW;
+    int tN[2];
+    bool okN[2];
+    Frag qa[2][C::KS], ga[2][C::KS], qaN[2][C::KS], gaN[2][C::KS];
+    float lv[2], dv[2], lvN[2], dvN[2];
+    {
+        int t0[2];
+        bool ok0[2];
+        ids(32 * wave, t0, ok0);
+        fetch(t0, ok0, qa, ga, lv, dv);
+        ids(32 * wave + stride, tN, okN);
+    }
+    for (int a0 = 32 * wave; a0 < total; a0 += stride) {
+        fetch(tN, okN, qaN, gaN, lvN, dvN);
+        ids(a0 + 2 * stride, tN, okN);
         if (g == 0) {
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt) {
-                ls[16 * qt + m16] = ok[qt] ? lse[sbase + t[qt]] * kLog2e : INFINITY;   // P = 0
-                Ds[16 * qt + m16] = ok[qt] ? Dv[sbase + t[qt]] : 0.f;
+                ls[16 * qt + m16] = lv[qt];
+                Ds[16 * qt + m16] = dv[qt];
             }
         }
 #pragma unroll
@@ -177,6 +201,13 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
             }
         }
         __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ++ks) { qa[qt][ks] = qaN[qt][ks]; ga[qt][ks] = gaN[qt][ks]; }
+            lv[qt] = lvN[qt];
+            dv[qt] = dvN[qt];
+        }
     }
 
     // sum the four waves' accumulators through LDS: red[tensor][key][channel]

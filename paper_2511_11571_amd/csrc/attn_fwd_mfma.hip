@@ -437,7 +437,8 @@ size_t forward_mfma_ws_bytes(const Dims& s)
 
 // ws: [bh*N*D bf16 slot-ordered scaled V][pad to 256][bh*D fp32 bits: channel maxima]
 hipError_t launch_forward_mfma(const Dims& s, const void* Q, const void* K, const void* V,
-                               void* ws, const int32_t* idx, void* O, float* lse, hipStream_t st)
+                               void* ws, const int32_t* idx, const int32_t* off, const int32_t* ql,
+                               const int32_t* chunk, void* O, float* lse, hipStream_t st)
 {
     const size_t vt_bytes = (sizeof(bf16_t) * (size_t)s.bh * s.N * s.D + 255) & ~(size_t)255;
     uint32_t* vmax = reinterpret_cast<uint32_t*>((char*)ws + vt_bytes);

@@ -10,7 +10,7 @@ namespace moba {
 typedef uint16_t bf16_t;   // raw bfloat16 bits
 
 constexpr int kWave = 64;
-constexpr int kChunkQ = 256;       // queries per routing chunk (list building, query tiles)
+constexpr int kChunkQ = MOBA_CHUNK_QUERIES;   // queries per routing chunk (blk_chunk granularity)
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t x)
 {
@@ -133,7 +133,7 @@ hipError_t launch_centroids(const Dims& s, const void* K, const float* w, void* 
 hipError_t launch_topk_reference(const Dims& s, const void* Q, const float* cent, int32_t* idx,
                                  hipStream_t st);
 hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, int32_t* ql,
-                              void* ws, hipStream_t st);
+                              int32_t* blk_chunk, hipStream_t st);
 hipError_t launch_forward_reference(const Dims& s, const void* Q, const void* K, const void* V,
                                     const int32_t* idx, void* O, float* lse, hipStream_t st);
 hipError_t launch_backward_reference(const Dims& s, const void* Q, const void* K, const void* V,
@@ -142,6 +142,5 @@ hipError_t launch_backward_reference(const Dims& s, const void* Q, const void* K
                                      void* dQ, void* dK, void* dV, float* Dvec, uint32_t parts,
                                      hipStream_t st);
 
-size_t lists_ws_bytes(const Dims& s);
 
 }  // namespace moba

@@ -54,6 +54,18 @@ def to_io(w, a64, like):
 
 W = workloads.Workload
 
+
+def check_chunk_offsets(w, chunk, off, ql):
+    """blk_chunk[c][j] must count the entries of block j's list that belong to queries
+    before chunk c (128 queries per chunk); its last row holds the list lengths."""
+    nchunk = (w.N + 127) // 128
+    assert chunk.shape == (w.bh, nchunk + 1, w.n)
+    for s in range(w.bh):
+        for j in range(w.n):
+            lst = ql[s, off[s, j]:off[s, j + 1]]
+            want = np.searchsorted(lst, 128 * np.arange(nchunk + 1), side="left")
+            assert np.array_equal(chunk[s, :, j], want), (s, j)
+
 SMALL = [
     W("bf16_B32", 1, 2, 1024, 64, 32, 4, seed=11),
     W("bf16_B64_d128", 2, 2, 768, 128, 64, 3, seed=12),
@@ -121,7 +133,7 @@ def test_topk_and_lists(oracle, w, flags):
     ref_idx, kth = oracle.topk(Q, C, w.B, w.k)
     sh = shape_of(w, flags)
     cent = torch.from_numpy(C).float().reshape(w.batch, w.heads, w.n, w.d).cuda()
-    idx, off, ql = moba.topk(sh, t["Q"].cuda(), cent)
+    idx, (off, ql, chunk) = moba.topk(sh, t["Q"].cuda(), cent)
     got = npi(idx).reshape(w.bh * w.N, w.k)
     exact, exempt = parity.routing_check(oracle, got, ref_idx.reshape(w.bh * w.N, w.k), kth.reshape(-1),
                                          Q, C, w.B)
@@ -133,6 +145,7 @@ def test_topk_and_lists(oracle, w, flags):
     g_off, g_ql = oracle.csr(npi(idx), w.B)
     assert np.array_equal(npi(off), g_off)
     assert np.array_equal(npi(ql), g_ql)
+    check_chunk_offsets(w, npi(chunk), g_off, g_ql)
 
 
 def test_topk_ties_go_to_the_lower_block():
@@ -142,7 +155,7 @@ def test_topk_ties_go_to_the_lower_block():
     t = workloads.generate(w)
     sh = shape_of(w)
     cent0 = torch.zeros((1, 2, w.n, w.d), dtype=torch.float32).cuda()
-    idx, _, _ = moba.topk(sh, t["Q"].cuda(), cent0)
+    idx, _ = moba.topk(sh, t["Q"].cuda(), cent0)
     got = npi(idx)
     for tq in range(0, w.N, 7):
         c = tq // w.B
@@ -152,7 +165,7 @@ def test_topk_ties_go_to_the_lower_block():
     for j in (9, 20):
         K[:, :, j * w.B:(j + 1) * w.B] = K[:, :, 4 * w.B:5 * w.B]
     _, cent = moba.centroids(sh, K.cuda())
-    idx, _, _ = moba.topk(sh, t["Q"].cuda(), cent)
+    idx, _ = moba.topk(sh, t["Q"].cuda(), cent)
     got = npi(idx)
     hits = 0
     for s in range(2):
@@ -168,11 +181,12 @@ def test_build_lists_from_a_given_routing(oracle, w):
     t = workloads.generate(w)
     Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
     ref_idx, _ = oracle.topk(Q, oracle.centroids(Kp, w.B), w.B, w.k)     # best-first order
-    off, ql = moba.build_lists(shape_of(w), torch.from_numpy(ref_idx).reshape(
+    off, ql, chunk = moba.build_lists(shape_of(w), torch.from_numpy(ref_idx).reshape(
         w.batch, w.heads, w.N, w.k).cuda())
     r_off, r_ql = oracle.csr(ref_idx, w.B)
     assert np.array_equal(npi(off), r_off)
     assert np.array_equal(npi(ql), r_ql)
+    check_chunk_offsets(w, npi(chunk), r_off, r_ql)
 
 
 # ------------------------------------------------------------------ attention at the oracle's routing
@@ -186,12 +200,12 @@ def test_forward_backward_at_oracle_routing(oracle, w, flags):
     sh = shape_of(w, flags)
     d = dev(t)
     idx = torch.from_numpy(ref_idx).reshape(w.batch, w.heads, w.N, w.k).cuda()
-    off, ql = moba.build_lists(sh, idx)
-    O, lse = moba.forward(sh, d["Q"], d["K"], d["V"], idx, off, ql)
+    lists = moba.build_lists(sh, idx)
+    O, lse = moba.forward(sh, d["Q"], d["K"], d["V"], idx, lists)
     rO, rlse = oracle.attn_fwd(Q, K, V, ref_idx, w.B, w.scale)
     assert parity.max_abs(np64(O), rO) < parity.O_TOL[w.dtype]
     assert parity.max_abs(np64(lse), rlse) < parity.LSE_TOL[w.dtype]
-    dQ, dK, dV = moba.backward(sh, d["Q"], d["K"], d["V"], O, lse, d["dO"], idx, off, ql)
+    dQ, dK, dV = moba.backward(sh, d["Q"], d["K"], d["V"], O, lse, d["dO"], idx, lists)
     # the oracle's backward starts from its own forward (binary64 O and lse)
     rQ, rK, rV = oracle.attn_bwd(Q, K, V, ref_idx, dO, w.B, w.scale)
     tol = parity.GRAD_TOL[w.dtype]
@@ -213,9 +227,9 @@ def test_whole_chain(oracle, w, flags):
     sh = shape_of(w, flags)
     d = dev(t)
     Keff, cent = moba.centroids(sh, d["K"], d["conv_w"])
-    idx, off, ql = moba.topk(sh, d["Q"], cent)
-    O, lse = moba.forward(sh, d["Q"], Keff, d["V"], idx, off, ql)
-    dQ, dK, dV = moba.backward(sh, d["Q"], Keff, d["V"], O, lse, d["dO"], idx, off, ql)
+    idx, lists = moba.topk(sh, d["Q"], cent)
+    O, lse = moba.forward(sh, d["Q"], Keff, d["V"], idx, lists)
+    dQ, dK, dV = moba.backward(sh, d["Q"], Keff, d["V"], O, lse, d["dO"], idx, lists)
     C = oracle.centroids(Kp, w.B)
     ref_idx, kth = oracle.topk(Q, C, w.B, w.k)
     exact, exempt = parity.routing_check(oracle, npi(idx).reshape(w.bh * w.N, w.k), ref_idx.reshape(w.bh * w.N, w.k),
@@ -240,10 +254,10 @@ def test_results_are_reproducible():
     outs = []
     for _ in range(2):
         Keff, cent = moba.centroids(sh, d["K"])
-        idx, off, ql = moba.topk(sh, d["Q"], cent)
-        O, lse = moba.forward(sh, d["Q"], Keff, d["V"], idx, off, ql)
-        grads = moba.backward(sh, d["Q"], Keff, d["V"], O, lse, d["dO"], idx, off, ql)
-        outs.append((idx, off, ql, O, lse) + tuple(grads))
+        idx, lists = moba.topk(sh, d["Q"], cent)
+        O, lse = moba.forward(sh, d["Q"], Keff, d["V"], idx, lists)
+        grads = moba.backward(sh, d["Q"], Keff, d["V"], O, lse, d["dO"], idx, lists)
+        outs.append((idx,) + tuple(lists) + (O, lse) + tuple(grads))
     for a, b in zip(*outs):
         if a.dtype == torch.int32:
             assert torch.equal(a, b)
@@ -267,13 +281,13 @@ def test_logit_far_above_the_own_block(oracle, flags):
     sh = shape_of(w, flags)
     d = dev(t)
     idx = torch.from_numpy(ref_idx).reshape(w.batch, w.heads, w.N, w.k).cuda()
-    off, ql = moba.build_lists(sh, idx)
-    O, lse = moba.forward(sh, d["Q"], d["K"], d["V"], idx, off, ql)
+    lists = moba.build_lists(sh, idx)
+    O, lse = moba.forward(sh, d["Q"], d["K"], d["V"], idx, lists)
     rO, rlse = oracle.attn_fwd(Q, K, V, ref_idx, w.B, w.scale)
     assert rlse[0, 700] > 60
     assert parity.max_abs(np64(O), rO) < parity.O_TOL[w.dtype]
     assert parity.max_abs(np64(lse), rlse) < 1e-2
-    dQ, dK, dV = moba.backward(sh, d["Q"], d["K"], d["V"], O, lse, d["dO"], idx, off, ql)
+    dQ, dK, dV = moba.backward(sh, d["Q"], d["K"], d["V"], O, lse, d["dO"], idx, lists)
     rQ, rK, rV = oracle.attn_bwd(Q, K, V, ref_idx, dO, w.B, w.scale)
     for a, b in ((dQ, rQ), (dK, rK), (dV, rV)):
         assert parity.rel_l2(np64(a), b) < parity.GRAD_TOL[w.dtype]
