@@ -15,11 +15,14 @@
 // that bin holds exactly as many keys as are still needed (typically after two sweeps) or
 // its width reaches one key (ties; the lower block index wins).  A last sweep marks the kept
 // blocks in a per-query bit row, which is written out in ascending block order.
+#include <type_traits>
+
 #include "mfma.h"
 
 namespace moba {
 
 constexpr int kHistWords = 32;            // 64 bins of 16 bits per query
+constexpr int kHistStride = 33;           // odd row stride: queries land on different LDS banks
 constexpr int kTopkMfmaMaxBlocks = 2048;  // bit row of a query: at most 64 words
 
 __global__ void split3_kernel(const float* __restrict__ c, bf16_t* __restrict__ out, int64_t count)
@@ -34,6 +37,13 @@ __global__ void split3_kernel(const float* __restrict__ c, bf16_t* __restrict__ 
     out[i] = hi;
     out[count + i] = mid;
     out[2 * count + i] = f32_to_bf16(r2);
+}
+
+// the score whose order_key is `key`; `none` when the key does not belong to a number
+__device__ __forceinline__ float key_score(uint32_t key, float none)
+{
+    const uint32_t bits = (key & 0x80000000u) ? (key & 0x7fffffffu) : ~key;
+    return (bits & 0x7fffffffu) > 0x7f800000u ? none : __uint_as_float(bits);
 }
 
 // One sweep over the centroid tiles of a 64-query strip.  f(qt, sc, j0): sc[i] is the score of
@@ -52,15 +62,19 @@ __device__ __forceinline__ void sweep_tiles(const bf16_t* __restrict__ c3, int64
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
                 a[term][ks].q = *reinterpret_cast<const uint4*>(c3 + term * cstride + (cbase + row) * D + 8 * g + 32 * ks);
+        // the four 16-query tiles are independent accumulation chains: issue them interleaved so
+        // that no MFMA waits for the one before it
+        f32x4_t sc[4];
 #pragma unroll
-        for (int qt = 0; qt < 4; ++qt) {
-            f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int qt = 0; qt < 4; ++qt) sc[qt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int term = 2; term >= 0; --term)       // smallest terms first
+        for (int term = 2; term >= 0; --term)           // smallest terms first
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) sc = mfma16(a[term][ks], qb[qt][ks], sc);
-            f(qt, sc, 16 * jt + 4 * g);
-        }
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int qt = 0; qt < 4; ++qt) sc[qt] = mfma16(a[term][ks], qb[qt][ks], sc[qt]);
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt) f(qt, sc[qt], 16 * jt + 4 * g);
     }
 }
 
@@ -76,8 +90,8 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
     const int m16 = lane & 15, g = lane >> 4;
     const int64_t strip = (int64_t)blockIdx.x * 4 + wave;
     if (strip >= total_strips) return;             // waves are independent: no workgroup barrier below
-    uint32_t* hist = smem + (size_t)wave * (64 * kHistWords + 6 * 64 + 64 * Wn);
-    uint32_t* st_lo = hist + 64 * kHistWords;
+    uint32_t* hist = smem + (size_t)wave * (64 * kHistStride + 6 * 64 + 64 * Wn);
+    uint32_t* st_lo = hist + 64 * kHistStride;
     uint32_t* st_sh = st_lo + 64;
     uint32_t* st_need = st_sh + 64;
     uint32_t* st_state = st_need + 64;             // 0 undecided, 1 keep key >= lo, 2 keep key > lo + ties
@@ -114,37 +128,55 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
         }
     __builtin_amdgcn_wave_barrier();
 
-    // ---- radix search for the k-th largest key of every undecided query
+    // Interior tiles hold only blocks that are past blocks of every query of the strip; the
+    // tail tiles need the per-query causal test.
+    const int ntile_int = min(ntile, (t0 / B) / 16);
+    auto sweep = [&](int tlo, int thi, auto f) {
+        const int mid = min(max(ntile_int, tlo), thi);
+        sweep_tiles<D>(c3, cstride, cbase, n, tlo, mid, qb, m16, g,
+                       [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::false_type()); });
+        sweep_tiles<D>(c3, cstride, cbase, n, mid, thi, qb, m16, g,
+                       [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::true_type()); });
+    };
+
+    // ---- radix search for the k-th largest key of every undecided query.  Membership of a
+    // score in the query's current key interval is tested on the float itself (two compares);
+    // only members pay for the key, the bin and the atomic.
     while (__any(st_state[lane] == 0u)) {
-        for (int i = 0; i < kHistWords; ++i) hist[lane * kHistWords + i] = 0u;
-        uint32_t lo4[4], sh4[4], past4[4], nb4[4];
+        for (int i = 0; i < kHistWords; ++i) hist[lane * kHistStride + i] = 0u;
+        uint32_t lo4[4], sh4[4], past4[4];
+        float flo4[4], fhi4[4];
         bool act4[4];
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) {
             const int q = 16 * qt + m16;
-            lo4[qt] = st_lo[q]; sh4[qt] = st_sh[q]; past4[qt] = st_past[q]; nb4[qt] = st_nb[q];
+            lo4[qt] = st_lo[q]; sh4[qt] = st_sh[q]; past4[qt] = st_past[q];
             act4[qt] = st_state[q] == 0u;
+            flo4[qt] = key_score(lo4[qt], -INFINITY);
+            const uint64_t hi = (uint64_t)lo4[qt] + ((uint64_t)st_nb[q] << sh4[qt]);
+            fhi4[qt] = hi > 0xff800000ull ? NAN : key_score((uint32_t)hi, NAN);   // NaN: no upper end
         }
         __builtin_amdgcn_wave_barrier();
-        sweep_tiles<D>(c3, cstride, cbase, n, 0, ntile, qb, m16, g,
-                       [&](int qt, const f32x4_t& sc, int j0) {
-                           if (!act4[qt]) return;
-                           uint32_t* row = hist + (16 * qt + m16) * kHistWords;
+        sweep(0, ntile, [&](int qt, const f32x4_t& sc, int j0, auto tail) {
+            if (!act4[qt]) return;
+            uint32_t* row = hist + (16 * qt + m16) * kHistStride;
 #pragma unroll
-                           for (int i = 0; i < 4; ++i) {
-                               const uint32_t key = order_key(sc[i]);
-                               const uint32_t bin = (key - lo4[qt]) >> sh4[qt];
-                               if ((uint32_t)(j0 + i) < past4[qt] && key >= lo4[qt] && bin < nb4[qt])
-                                   atomicAdd(&row[bin >> 1], 1u << (16 * (bin & 1u)));
-                           }
-                       });
+            for (int i = 0; i < 4; ++i) {
+                bool in = sc[i] >= flo4[qt] && !(sc[i] >= fhi4[qt]);
+                if (decltype(tail)::value) in = in && (uint32_t)(j0 + i) < past4[qt];
+                if (in) {
+                    const uint32_t bin = (order_key(sc[i]) - lo4[qt]) >> sh4[qt];
+                    atomicAdd(&row[bin >> 1], 1u << (16 * (bin & 1u)));
+                }
+            }
+        });
         __builtin_amdgcn_wave_barrier();
         if (st_state[lane] == 0u) {                  // lane = query: walk the bins from the top
             const uint32_t need = st_need[lane], lo = st_lo[lane], sh = st_sh[lane];
             uint32_t cum = 0, c = 0;
             int b = 63;
             for (; b >= 0; --b) {
-                c = (hist[lane * kHistWords + (b >> 1)] >> (16 * (b & 1))) & 0xffffu;
+                c = (hist[lane * kHistStride + (b >> 1)] >> (16 * (b & 1))) & 0xffffu;
                 if (cum + c >= need) break;
                 cum += c;
             }
@@ -154,51 +186,53 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
             st_need[lane] = need2;
             if (c == need2) st_state[lane] = 1u;
             else if (sh == 0u) st_state[lane] = 2u;
-            else if (sh >= 6u) st_sh[lane] = sh - 6u;            // 64 bins again
-            else { st_sh[lane] = 0u; st_nb[lane] = 1u << sh; }   // last step: one key per bin
+            else if (sh >= 6u) { st_sh[lane] = sh - 6u; st_nb[lane] = 64u; }   // 64 bins again
+            else { st_sh[lane] = 0u; st_nb[lane] = 1u << sh; }               // last step: one key per bin
         }
         __builtin_amdgcn_wave_barrier();
     }
 
-    // ---- mark the kept blocks
+    // ---- mark the kept blocks: score >= threshold (state 1) or > threshold plus ties (state 2)
     {
-        uint32_t lo4[4], past4[4], mode4[4];
+        uint32_t past4[4];
+        float thr4[4];
+        bool strict4[4];
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) {
             const int q = 16 * qt + m16;
-            lo4[qt] = st_lo[q]; past4[qt] = st_past[q]; mode4[qt] = st_state[q];
+            past4[qt] = st_past[q];
+            strict4[qt] = st_state[q] == 2u;
+            thr4[qt] = key_score(st_lo[q], -INFINITY);
         }
-        sweep_tiles<D>(c3, cstride, cbase, n, 0, ntile, qb, m16, g,
-                       [&](int qt, const f32x4_t& sc, int j0) {
-                           uint32_t bits = 0;
+        sweep(0, ntile, [&](int qt, const f32x4_t& sc, int j0, auto tail) {
+            uint32_t bits = 0;
 #pragma unroll
-                           for (int i = 0; i < 4; ++i) {
-                               const uint32_t key = order_key(sc[i]);
-                               const bool keep = mode4[qt] == 1u ? key >= lo4[qt] : key > lo4[qt];
-                               if ((uint32_t)(j0 + i) < past4[qt] && keep) bits |= 1u << i;
-                           }
-                           if (bits) atomicOr(&selm[(16 * qt + m16) * Wn + (j0 >> 5)], bits << (j0 & 31));
-                       });
+            for (int i = 0; i < 4; ++i) {
+                bool keep = strict4[qt] ? sc[i] > thr4[qt] : sc[i] >= thr4[qt];
+                if (decltype(tail)::value) keep = keep && (uint32_t)(j0 + i) < past4[qt];
+                if (keep) bits |= 1u << i;
+            }
+            if (bits) atomicOr(&selm[(16 * qt + m16) * Wn + (j0 >> 5)], bits << (j0 & 31));
+        });
         __builtin_amdgcn_wave_barrier();
-        // ties at the threshold: the lowest block indices among the equal keys, 1024 blocks at a time
+        // ties at the threshold: the lowest block indices among the equal scores, 1024 blocks at a time
         if (__any(st_state[lane] == 2u)) {
             for (int r0 = 0; r0 < 16 * ntile; r0 += 1024) {
-                for (int i = 0; i < kHistWords; ++i) hist[lane * kHistWords + i] = 0u;
+                for (int i = 0; i < kHistWords; ++i) hist[lane * kHistStride + i] = 0u;
                 __builtin_amdgcn_wave_barrier();
-                sweep_tiles<D>(c3, cstride, cbase, n, r0 / 16, min(ntile, (r0 + 1024) / 16), qb, m16, g,
-                               [&](int qt, const f32x4_t& sc, int j0) {
-                                   if (mode4[qt] != 2u) return;
-                                   uint32_t bits = 0;
+                sweep(r0 / 16, min(ntile, (r0 + 1024) / 16), [&](int qt, const f32x4_t& sc, int j0, auto tail) {
+                    if (!strict4[qt]) return;
+                    uint32_t bits = 0;
 #pragma unroll
-                                   for (int i = 0; i < 4; ++i)
-                                       if ((uint32_t)(j0 + i) < past4[qt] && order_key(sc[i]) == lo4[qt]) bits |= 1u << i;
-                                   if (bits) atomicOr(&hist[(16 * qt + m16) * kHistWords + ((j0 - r0) >> 5)], bits << (j0 & 31));
-                               });
+                    for (int i = 0; i < 4; ++i)
+                        if ((uint32_t)(j0 + i) < past4[qt] && sc[i] == thr4[qt]) bits |= 1u << i;
+                    if (bits) atomicOr(&hist[(16 * qt + m16) * kHistStride + ((j0 - r0) >> 5)], bits << (j0 & 31));
+                });
                 __builtin_amdgcn_wave_barrier();
                 if (st_state[lane] == 2u) {
                     uint32_t need = st_need[lane];
                     for (int w = 0; w < kHistWords && need > 0; ++w) {
-                        uint32_t word = hist[lane * kHistWords + w];
+                        uint32_t word = hist[lane * kHistStride + w];
                         while (word && need > 0) {
                             const int b = __ffs(word) - 1;
                             selm[lane * Wn + (r0 >> 5) + w] |= 1u << b;
@@ -213,26 +247,20 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
         }
     }
 
-    // ---- write the rows: kept blocks ascending, then -1
-    for (int q = 0; q < rows_here; ++q) {
-        uint32_t word = lane < Wn ? selm[q * Wn + lane] : 0u;
-        const int c = __popc(word);
-        int pre = c;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int v = __shfl_up(pre, o, 64);
-            if (lane >= o) pre += v;
+    // ---- write the rows (lane = query): kept blocks ascending, then -1
+    if (lane < rows_here) {
+        int32_t* row = out + (int64_t)lane * k;
+        int pos = 0;
+        for (int w = 0; w < Wn; ++w) {
+            uint32_t word = selm[lane * Wn + w];
+            while (word) {
+                const int b = __ffs(word) - 1;
+                if (pos < k) row[pos] = 32 * w + b;
+                ++pos;
+                word &= word - 1;
+            }
         }
-        const int total = __shfl(pre, 63, 64);
-        int pos = pre - c;
-        int32_t* row = out + (int64_t)q * k;
-        while (word) {
-            const int b = __ffs(word) - 1;
-            if (pos < k) row[pos] = 32 * lane + b;
-            ++pos;
-            word &= word - 1;
-        }
-        for (int c0 = total + lane; c0 < k; c0 += kWave) row[c0] = -1;
+        for (; pos < k; ++pos) row[pos] = -1;
     }
 }
 
@@ -253,8 +281,8 @@ static hipError_t topk_launch(const Dims& s, const void* Q, const bf16_t* c3, in
 {
     const int sps = (s.N + 63) / 64;
     const int64_t strips = (int64_t)sps * s.bh;
-    const int Wn = (s.n + 31) / 32;
-    const size_t lds = sizeof(uint32_t) * 4 * (size_t)(64 * kHistWords + 6 * 64 + 64 * Wn);
+    const int Wn = ((s.n + 31) / 32) | 1;      // words per bit row, odd for the same reason
+    const size_t lds = sizeof(uint32_t) * 4 * (size_t)(64 * kHistStride + 6 * 64 + 64 * Wn);
     hipError_t e = hipFuncSetAttribute((const void*)topk_mfma_kernel<D>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
