@@ -15,27 +15,47 @@
 //           row) and, with V pre-scaled per channel to |v| <= 1, |sum_u p_u v_u| has the same
 //           bound; both sums are accumulated as integers scaled by 2^F, F chosen from that
 //           bound (each 32-key partial of P V is cut toward zero, a relative shrink of ~1e-5,
-//           two orders below the bf16 output's resolution; the row sums l round to nearest).  Integer adds commute exactly: the result does not depend on the order
-//           in which waves arrive, so the output is bit-reproducible.
-// Which rows go with which key group is a bit matrix in LDS (one row of TILE bits per
-// group), built from the query-major routing, 1024 groups at a time.
+//           two orders below the bf16 output's resolution; the row sums l round to nearest).
+//           Integer adds commute exactly: the result does not depend on the order in which
+//           waves arrive, so the output is bit-reproducible.
+// Which rows go with which key block is a set of compact row lists in LDS (one byte per
+// (row, block) pair, sorted by block), built once per tile from the query-major routing by a
+// counting sort and used by both passes; the earlier 32-key groups of a row's own block
+// (B > 32) are dense work and go with the own group.
+//
+// What bounds the kernel is the operand traffic, not the arithmetic: with scattered routing a
+// 256-query tile meets a key block with ~16 of its rows, so every 1-2 MFMA sub-tiles need a
+// fresh 4 KB of K (both passes) and 4 KB of V.  Hence (a) K and V are read from copies laid
+// out in MFMA operand order, 1 KB of consecutive bytes per load instruction (four times the
+// rate of the row-major pattern on this chip), (b) the workgroups of one XCD work on the same
+// slice and walk its blocks in ascending order, so these reads hit that XCD's L2, and (c) 16
+// waves per workgroup keep loads, LDS traffic and MFMA work of different units overlapped.
 #include "mfma.h"
 
 namespace moba {
 
+#ifndef MOBA_FWD_NW64
+#define MOBA_FWD_NW64 16
+#define MOBA_FWD_UPRE64 false
+#define MOBA_FWD_SPIPE64 false
+#endif
+
 template <int D>
 struct FwdCfg {
     static constexpr int TILE = D == 64 ? 256 : 128;   // queries per workgroup
-    static constexpr int NW = 8;                       // waves per workgroup
+    static constexpr int NW = D == 64 ? MOBA_FWD_NW64 : 8;   // waves per workgroup
     static constexpr int NT = NW * kWave;
     static constexpr int QSTRIDE = D * 2 + 16;         // bytes per Q row in LDS
     static constexpr int OSTRIDE = D + 1;              // words per accumulator row
     static constexpr int MT = D / 16;                  // 16-channel tiles of a row
     static constexpr int KS = D / 32;                  // contraction steps of q.k
-    static constexpr int MW = TILE / 32;               // mask words per key group
-    static constexpr int RANGE = 1024;                 // key groups per bit matrix
+    static constexpr int RANGE = 1024;                 // key blocks per set of row lists (at most)
+    static constexpr int LCAP = 16384;                 // (row, block) pairs per set of row lists
+    static constexpr bool UPRE = D == 64 ? MOBA_FWD_UPRE64 : true;   // K operands fetched one unit ahead
+    static constexpr bool PREV = D == 64;              // ... and the V operands too (registers allow)
+    static constexpr bool SPIPE = D == 64 ? MOBA_FWD_SPIPE64 : true; // Q gather one sub-tile ahead
     static constexpr size_t LDS = (size_t)TILE * QSTRIDE + 4 * TILE * OSTRIDE + 4 * 2 * TILE +
-                                  4 * RANGE * MW + 2 * NW * TILE + 4 * RANGE + 64;
+                                  4 * 2 * (RANGE + 1) + 4 * NW + 4 + LCAP + 64;
 };
 
 // ---- per-channel scale of V and the slot-ordered transposed copy (see mfma.h) -----------
@@ -141,6 +161,39 @@ hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, const 
     return hipGetLastError();
 }
 
+// Xa <- copy of X in MFMA operand order: the 16 bytes lane (m, g) feeds to the MFMA as rows
+// 16 mt + m, channels 32 ks + 8 g .. + 8 of 32-key group kap sit at
+// ((kap * 2 + mt) * (D / 32) + ks) * 1024 + 16 * lane.  One load instruction of a wave then
+// covers 1 KB of consecutive bytes; reading the same operand from the row-major tensor (16
+// rows x 64 bytes per instruction) runs at a quarter of that rate on this chip.
+template <int D>
+__global__ __launch_bounds__(256) void operand_copy_kernel(const bf16_t* __restrict__ X,
+                                                           bf16_t* __restrict__ Xa, int64_t chunks)
+{
+    constexpr int KS = D / 32;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= chunks) return;
+    const int lane = (int)(i % 64), ks = (int)((i / 64) % KS), mt = (int)((i / (64 * KS)) % 2);
+    const int64_t kap = i / (64 * KS * 2);
+    const int m = lane & 15, g = lane >> 4;
+    const uint4 v = *reinterpret_cast<const uint4*>(X + (kap * 32 + 16 * mt + m) * D + 32 * ks + 8 * g);
+    *reinterpret_cast<uint4*>(Xa + i * 8) = v;
+}
+
+hipError_t launch_operand_copy(const Dims& s, const void* X, void* Xa, hipStream_t st)
+{
+    const int64_t chunks = (int64_t)s.bh * s.N * s.D / 8;
+    if (chunks == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((chunks + 255) / 256);
+    if (s.D == 64)
+        hipLaunchKernelGGL(operand_copy_kernel<64>, dim3(grid), dim3(256), 0, st, (const bf16_t*)X,
+                           (bf16_t*)Xa, chunks);
+    else
+        hipLaunchKernelGGL(operand_copy_kernel<128>, dim3(grid), dim3(256), 0, st, (const bf16_t*)X,
+                           (bf16_t*)Xa, chunks);
+    return hipGetLastError();
+}
+
 // ---- the tile kernel -------------------------------------------------------------------
 
 // monotone map fp32 -> int32 (and back): larger float <=> larger int
@@ -156,7 +209,7 @@ __device__ __forceinline__ float key_float(int k)
 
 template <int D>
 __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
-    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt,
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Ka, const bf16_t* __restrict__ Vt,
     const uint32_t* __restrict__ vmax, const int32_t* __restrict__ idx, bf16_t* __restrict__ O,
     float* __restrict__ lse, int N, int B, int k, float scale, int ntiles, int bh)
 {
@@ -166,25 +219,29 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
     int* Os = reinterpret_cast<int*>(Qs + (size_t)C::TILE * C::QSTRIDE);   // fixed point, 2^F
     int* mkey = Os + C::TILE * C::OSTRIDE;       // pass 1: key of the row max; then m (log2 units) as float bits
     int* lsum = mkey + C::TILE;                  // fixed point, 2^F
-    uint32_t* mask = reinterpret_cast<uint32_t*>(lsum + C::TILE);
-    uint16_t* rlist = reinterpret_cast<uint16_t*>(mask + C::RANGE * C::MW);
-    uint32_t* ulist = reinterpret_cast<uint32_t*>(rlist + C::NW * C::TILE);   // non-empty groups of a range
-    int* next = reinterpret_cast<int*>(ulist + C::RANGE);
+    uint32_t* cur = reinterpret_cast<uint32_t*>(lsum + C::TILE);
+    uint32_t* offs = cur + C::RANGE + 1;
+    uint32_t* wsum = offs + C::RANGE + 1;
+    int* next = reinterpret_cast<int*>(wsum + C::NW);
+    uint8_t* rows8 = reinterpret_cast<uint8_t*>(next + 1);
+    uint16_t* ulist = reinterpret_cast<uint16_t*>(cur);   // non-empty blocks of a range (over the builder's scratch)
 
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int m16 = lane & 15, g = lane >> 4;
-    // consecutive workgroups take different slices of the same tile index (late, long tiles first)
-    const int s = blockIdx.x % bh;
-    const int tile = ntiles - 1 - blockIdx.x / bh;
+    int s, pos;
+    if (!schedule(blockIdx.x, bh, ntiles, s, pos)) return;
+    const int tile = ntiles - 1 - pos;                 // late, long tiles first
     const int t0 = tile * C::TILE;
     const int rows_here = min(C::TILE, N - t0);
     const int NG = B / 32;
     const float c2 = scale * kLog2e;
     const int64_t sbase = (int64_t)s * N;
     const bf16_t* Qg = Q + (sbase + t0) * D;
-    const bf16_t* Kg = K + sbase * D;
-    const bf16_t* Vtg = Vt + sbase * D;
-    uint16_t* rl = rlist + wave * C::TILE;
+    const char* Kg = reinterpret_cast<const char*>(Ka + sbase * D);
+    const char* Vtg = reinterpret_cast<const char*>(Vt + sbase * D);
+    const uint32_t vlane = (uint32_t)lane * 16u;   // this lane's bytes inside a K or V operand
+    const uint32_t qlane = 16u * g;
 
     // Fixed-point scale: a row attends at most nkeys keys, so sum p <= nkeys < 2^(31-F).
     const int nkeys = min(t0 + rows_here, (k + 1) * B);
@@ -201,115 +258,134 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
     for (int i = tid; i < C::TILE; i += C::NT) { mkey[i] = (int)0x80000000; lsum[i] = 0; }
     __syncthreads();
 
-    const int gmax = (t0 + rows_here - 1) >> 5;        // groups below the last row's own group
+    // blocks strictly before the own block of the tile's last row, taken `range` at a time so
+    // that a range's (row, block) pairs fit rows8
+    const int pastmax = (t0 + rows_here - 1) / B;
+    const int range = (int64_t)k * C::TILE <= C::LCAP ? C::RANGE : C::LCAP / C::TILE;
+    const bool one_range = pastmax <= range;
+
+    auto load_k = [&](int kap, Frag (&ka)[2][C::KS]) {
+        const char* kb = Kg + (int64_t)kap * (64 * D);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ++ks)
+                ka[mt][ks].q = *reinterpret_cast<const uint4*>(kb + vlane + (mt * C::KS + ks) * 1024);
+    };
+    auto load_v = [&](int kap, Frag (&va)[C::MT]) {
+        const char* vb = Vtg + (int64_t)kap * (64 * D);
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt)
+            va[mt].q = *reinterpret_cast<const uint4*>(vb + vlane + mt * 1024);
+    };
+    auto gather_q = [&](int row, Frag (&qb)[C::KS]) {
+        const unsigned char* qr = Qs + (uint32_t)row * C::QSTRIDE + qlane;
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) qb[ks].q = *reinterpret_cast<const uint4*>(qr + 64 * ks);
+    };
+    // x: eight scores of this lane's row (log2 units, reference subtracted) -> probabilities,
+    // row-sum and P V into the row's accumulators
+    auto accumulate = [&](int row, float (&x)[8], const Frag (&va)[C::MT], bool valid) {
+        float lp = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { x[e] = fast_exp2(x[e]); lp += x[e]; }
+        Frag pb;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pb.u[e] = pack2(x[2 * e], x[2 * e + 1]);
+        int oi[C::MT][4];
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt) {
+            const f32x4_t o = mfma16(va[mt], pb, f32x4_t{0.f, 0.f, 0.f, 0.f});
+#pragma unroll
+            for (int i = 0; i < 4; ++i) oi[mt][i] = (int)o[i];      // toward zero: see header
+        }
+        if (valid) {
+            atomicAdd(&lsum[row], __float2int_rn(lp));
+            int* orow = Os + (uint32_t)row * C::OSTRIDE + g * (D / 4);
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) atomicAdd(&orow[4 * mt + i], oi[mt][i]);
+        }
+    };
 
     for (int pass = 0; pass < 2; ++pass) {
-        // own 32-key groups, causal
+        // own block: the row's own 32-key group under the causal mask and, for B > 32, the
+        // block's earlier groups in full
         for (int p = wave; p < rows_here / 16; p += C::NW) {
             const int unit = p >> 1, st = p & 1;
             const int row = 32 * unit + 16 * st + m16;
-            const int64_t kap = (t0 >> 5) + unit;
+            const int kown = (t0 >> 5) + unit;
+            const int kfirst = NG == 1 ? kown : kown - kown % NG;
             Frag qb[C::KS];
+            gather_q(row, qb);
+            const float mr = pass == 1 ? __int_as_float(mkey[row]) : 0.f;
+            float mx = -INFINITY;
+            for (int kap = kfirst; kap <= kown; ++kap) {
+                const bool own = kap == kown;
+                Frag ka[2][C::KS], va[C::MT];
+                load_k(kap, ka);
+                if (pass == 1) load_v(kap, va);
+                f32x4_t sc[2];
 #pragma unroll
-            for (int ks = 0; ks < C::KS; ++ks)
-                qb[ks].q = *reinterpret_cast<const uint4*>(Qs + (size_t)row * C::QSTRIDE + 16 * g + 64 * ks);
-            f32x4_t sc[2];
+                for (int mt = 0; mt < 2; ++mt) {
+                    sc[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    if (!own || mt <= st) {
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                sc[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                if (mt <= st) {
-#pragma unroll
-                    for (int ks = 0; ks < C::KS; ++ks) {
-                        Frag ka;
-                        ka.q = *reinterpret_cast<const uint4*>(Kg + (kap * 32 + 16 * mt + m16) * D + 8 * g + 32 * ks);
-                        sc[mt] = mfma16(ka, qb[ks], sc[mt]);
+                        for (int ks = 0; ks < C::KS; ++ks) sc[mt] = mfma16(ka[mt][ks], qb[ks], sc[mt]);
                     }
                 }
-            }
-            float x[8];
+                float x[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const bool vis = 16 * (e >> 2) + 4 * g + (e & 3) <= 16 * st + m16;
-                x[e] = vis ? sc[e >> 2][e & 3] * c2 : -INFINITY;
-            }
-            if (pass == 0) {
-                float mx = x[0];
+                for (int e = 0; e < 8; ++e) {
+                    const bool vis = !own || 16 * (e >> 2) + 4 * g + (e & 3) <= 16 * st + m16;
+                    x[e] = vis ? fmaf(sc[e >> 2][e & 3], c2, -mr) : -INFINITY;
+                }
+                if (pass == 0) {
 #pragma unroll
-                for (int e = 1; e < 8; ++e) mx = fmaxf(mx, x[e]);
-                atomicMax(&mkey[row], float_key(mx));
-            } else {
-                const float mr = __int_as_float(mkey[row]);
-                float lp = 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) { x[e] = fast_exp2(x[e] - mr); lp += x[e]; }
-                atomicAdd(&lsum[row], __float2int_rn(lp));
-                Frag pb;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) pb.u[e] = pack2(x[2 * e], x[2 * e + 1]);
-#pragma unroll
-                for (int mt = 0; mt < C::MT; ++mt) {
-                    Frag va;
-                    va.q = *reinterpret_cast<const uint4*>(Vtg + slot_major_offset<D>(kap, mt, lane));
-                    f32x4_t o = mfma16(va, pb, f32x4_t{0.f, 0.f, 0.f, 0.f});
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        atomicAdd(&Os[row * C::OSTRIDE + tile_chan<D>(mt, 4 * g + i)], (int)o[i]);
+                    for (int e = 0; e < 8; ++e) mx = fmaxf(mx, x[e]);
+                } else {
+                    accumulate(row, x, va, true);
                 }
             }
+            if (pass == 0) atomicMax(&mkey[row], float_key(mx));
         }
 
-        // routed groups (and, for B > 32, the earlier groups of the own block)
-        for (int lo = 0; lo < gmax; lo += C::RANGE) {
-            const int hi = min(gmax, lo + C::RANGE);
-            __syncthreads();
-            for (int i = tid; i < (hi - lo) * C::MW; i += C::NT) mask[i] = 0u;
-            if (tid == 0) *next = 0;
-            __syncthreads();
-            build_group_mask<C::TILE, C::NT, C::MW>(mask, idx + (sbase + t0) * k, t0, rows_here, k, B, NG, lo,
-                                                     hi, tid);
-            __syncthreads();
-            // non-empty groups of this range -> ulist (count << 16 | group)
-            for (int i = tid; i < hi - lo; i += C::NT) {
-                int cnt = 0;
-#pragma unroll
-                for (int wd = 0; wd < C::MW; ++wd) cnt += __popc(mask[i * C::MW + wd]);
-                if (cnt) ulist[atomicAdd(next, 1)] = (uint32_t)i | ((uint32_t)cnt << 16);
+        // routed blocks
+        for (int lo = 0; lo < pastmax; lo += range) {
+            const int hi = min(pastmax, lo + range);
+            if (pass == 0 || !one_range) {
+                __syncthreads();
+                build_block_lists<C::TILE, C::NT>(idx + (sbase + t0) * k, t0, rows_here, k, B, lo, hi,
+                                                  cur, offs, rows8, C::LCAP, wsum, tid);
+                // Non-empty blocks of this range, ascending: the workgroups of an XCD then walk
+                // K and V in the same order and find each other's blocks in the L2.
+                list_nonempty<C::NT>(offs, hi - lo, ulist, next, wsum, tid);
             }
-            __syncthreads();
-            const int nunits = *next;
+            const int nblk = *next;
 
-            auto load_unit = [&](uint32_t entry, Frag (&ka)[2][C::KS], Frag (&va)[C::MT]) {
-                const int64_t kap = lo + (int)(entry & 0xffffu);
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int ks = 0; ks < C::KS; ++ks)
-                        ka[mt][ks].q = *reinterpret_cast<const uint4*>(Kg + (kap * 32 + 16 * mt + m16) * D + 8 * g + 32 * ks);
-                if (pass == 1) {
-#pragma unroll
-                    for (int mt = 0; mt < C::MT; ++mt)
-                        va[mt].q = *reinterpret_cast<const uint4*>(Vtg + slot_major_offset<D>(kap, mt, lane));
-                }
+            // one unit = one 32-key group of a listed block
+            auto load_unit = [&](int e, int gi, Frag (&ka)[2][C::KS], Frag (&va)[C::MT], int& beg,
+                                 int& end) {
+                const int j = __builtin_amdgcn_readfirstlane((int)ulist[e]);
+                beg = offs[j];
+                end = offs[j + 1];
+                const int kap = (lo + j) * NG + gi;
+                load_k(kap, ka);
+                if (C::PREV && pass == 1) load_v(kap, va);
+                return kap;
             };
-            auto run_unit = [&](uint32_t entry, const Frag (&ka)[2][C::KS], const Frag (&va)[C::MT]) {
-                const int ui = (int)(entry & 0xffffu), cnt = (int)(entry >> 16);
-                int base = 0;
-#pragma unroll
-                for (int r = 0; r < C::TILE / 64; ++r) {
-                    const uint64_t m64 = (uint64_t)mask[ui * C::MW + 2 * r] | ((uint64_t)mask[ui * C::MW + 2 * r + 1] << 32);
-                    if ((m64 >> lane) & 1ull) rl[base + __popcll(m64 & ((1ull << lane) - 1ull))] = (uint16_t)(64 * r + lane);
-                    base += __popcll(m64);
-                }
-                __builtin_amdgcn_wave_barrier();
+            auto run_unit = [&](int kap, int beg_v, int end_v, const Frag (&ka)[2][C::KS], Frag (&va)[C::MT]) {
+                if (!C::PREV && pass == 1) load_v(kap, va);
+                const int beg = __builtin_amdgcn_readfirstlane(beg_v);
+                const int end = min(__builtin_amdgcn_readfirstlane(end_v), (int)C::LCAP);
                 // Sub-tiles of 16 rows.  The row ids of four sub-tiles are read at once, and the
                 // LDS gather of the next sub-tile is issued before the arithmetic and the atomics
-                // of the current one, so it never waits behind them.
-                auto gather = [&](bool valid, int row, Frag (&qb)[C::KS], float& mr) {
-#pragma unroll
-                    for (int ks = 0; ks < C::KS; ++ks)
-                        qb[ks].q = *reinterpret_cast<const uint4*>(Qs + (size_t)row * C::QSTRIDE + 16 * g + 64 * ks);
-                    // rows beyond the list get an infinite reference: their p is exactly 0
-                    mr = (pass == 1 && valid) ? __int_as_float(mkey[row]) : INFINITY;
+                // of the current one, so it never waits behind them.  Lanes beyond the list work
+                // on whatever row id they read (always inside the tile) and add nothing.
+                auto gather = [&](int row, Frag (&qb)[C::KS], float& mr) {
+                    gather_q(row, qb);
+                    mr = pass == 1 ? __int_as_float(mkey[row]) : 0.f;
                 };
                 auto compute = [&](bool valid, int row, const Frag (&qb)[C::KS], float mr) {
                     f32x4_t sc[2];
@@ -324,72 +400,81 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                         mx = fmaxf(mx, fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
                         if (valid) atomicMax(&mkey[row], float_key(mx * c2));
                     } else {
-                        float x[8], lp = 0.f;
+                        float x[8];
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            x[e] = fast_exp2(fmaf(sc[e >> 2][e & 3], c2, -mr));
-                            lp += x[e];
-                        }
-                        Frag pb;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) pb.u[e] = pack2(x[2 * e], x[2 * e + 1]);
-                        int oi[C::MT][4];
-#pragma unroll
-                        for (int mt = 0; mt < C::MT; ++mt) {
-                            const f32x4_t o = mfma16(va[mt], pb, f32x4_t{0.f, 0.f, 0.f, 0.f});
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) oi[mt][i] = (int)o[i];      // toward zero: see header
-                        }
-                        if (valid) {
-                            atomicAdd(&lsum[row], __float2int_rn(lp));
-                            int* orow = Os + row * C::OSTRIDE + g * (D / 4);
-#pragma unroll
-                            for (int mt = 0; mt < C::MT; ++mt)
-#pragma unroll
-                                for (int i = 0; i < 4; ++i) atomicAdd(&orow[4 * mt + i], oi[mt][i]);
-                        }
+                        for (int e = 0; e < 8; ++e) x[e] = fmaf(sc[e >> 2][e & 3], c2, -mr);
+                        accumulate(row, x, va, valid);
                     }
                 };
-                for (int c0 = 0; c0 < cnt; c0 += 64) {
-                    bool val[4];
-                    int rows[4];
+                if constexpr (C::SPIPE) {
+                    for (int c0 = beg; c0 < end; c0 += 64) {
+                        const int left = end - c0;          // > 0
+                        bool val[4];
+                        int rows[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        val[j] = c0 + 16 * j + m16 < cnt;
-                        rows[j] = rl[val[j] ? c0 + 16 * j + m16 : 0];
-                    }
-                    const int left = cnt - c0;          // > 0
-                    Frag qA[C::KS], qB[C::KS];
-                    float mA, mB;
-                    gather(val[0], rows[0], qA, mA);
-                    if (left > 16) gather(val[1], rows[1], qB, mB);
-                    compute(val[0], rows[0], qA, mA);
-                    if (left > 16) {
-                        if (left > 32) gather(val[2], rows[2], qA, mA);
-                        compute(val[1], rows[1], qB, mB);
-                        if (left > 32) {
-                            if (left > 48) gather(val[3], rows[3], qB, mB);
-                            compute(val[2], rows[2], qA, mA);
-                            if (left > 48) compute(val[3], rows[3], qB, mB);
+                        for (int j = 0; j < 4; ++j) {
+                            val[j] = 16 * j + m16 < left;
+                            rows[j] = rows8[c0 + 16 * j + m16] & (C::TILE - 1);
+                        }
+                        Frag qA[C::KS], qB[C::KS];
+                        float mA, mB;
+                        gather(rows[0], qA, mA);
+                        if (left > 16) gather(rows[1], qB, mB);
+                        compute(val[0], rows[0], qA, mA);
+                        if (left > 16) {
+                            if (left > 32) gather(rows[2], qA, mA);
+                            compute(val[1], rows[1], qB, mB);
+                            if (left > 32) {
+                                if (left > 48) gather(rows[3], qB, mB);
+                                compute(val[2], rows[2], qA, mA);
+                                if (left > 48) compute(val[3], rows[3], qB, mB);
+                            }
                         }
                     }
+                } else {
+                    for (int c0 = beg; c0 < end; c0 += 16) {
+                        const bool valid = m16 < end - c0;
+                        const int row = rows8[c0 + m16] & (C::TILE - 1);
+                        Frag qA[C::KS];
+                        float mA;
+                        gather(row, qA, mA);
+                        compute(valid, row, qA, mA);
+                    }
                 }
-                __builtin_amdgcn_wave_barrier();
             };
 
-            // waves take the units round robin; the operands of a wave's next unit are in flight
-            // while it works on the current one
-            Frag kaA[2][C::KS], vaA[C::MT], kaB[2][C::KS], vaB[C::MT];
-            int u = wave;
-            if (u < nunits) load_unit(ulist[u], kaA, vaA);
-            while (u < nunits) {
-                if (u + C::NW < nunits) load_unit(ulist[u + C::NW], kaB, vaB);
-                run_unit(ulist[u], kaA, vaA);
-                u += C::NW;
-                if (u >= nunits) break;
-                if (u + C::NW < nunits) load_unit(ulist[u + C::NW], kaA, vaA);
-                run_unit(ulist[u], kaB, vaB);
-                u += C::NW;
+            // waves take the listed blocks round robin; the operands of a wave's next unit are in
+            // flight while it works on the current one
+            if constexpr (C::UPRE) {
+                Frag kaA[2][C::KS], vaA[C::MT], kaB[2][C::KS];
+                Frag vaB_[C::PREV ? C::MT : 1];
+                Frag (&vaB)[C::MT] = *reinterpret_cast<Frag (*)[C::MT]>(C::PREV ? (void*)&vaB_ : (void*)&vaA);
+                int begA = 0, endA = 0, begB = 0, endB = 0, kapA = 0, kapB = 0;
+                int e = wave, gi = 0;
+                auto advance = [&](int& e2, int& gi2) {
+                    if (++gi2 == NG) { gi2 = 0; e2 += C::NW; }
+                };
+                if (e < nblk) kapA = load_unit(e, gi, kaA, vaA, begA, endA);
+                while (e < nblk) {
+                    int en = e, gn = gi;
+                    advance(en, gn);
+                    if (en < nblk) kapB = load_unit(en, gn, kaB, vaB, begB, endB);
+                    run_unit(kapA, begA, endA, kaA, vaA);
+                    e = en; gi = gn;
+                    if (e >= nblk) break;
+                    advance(en, gn);
+                    if (en < nblk) kapA = load_unit(en, gn, kaA, vaA, begA, endA);
+                    run_unit(kapB, begB, endB, kaB, vaB);
+                    e = en; gi = gn;
+                }
+            } else {
+                for (int e = wave; e < nblk; e += C::NW)
+                    for (int gi = 0; gi < NG; ++gi) {
+                        Frag ka[2][C::KS], va[C::MT];
+                        int beg, end;
+                        const int kap = load_unit(e, gi, ka, va, beg, end);
+                        run_unit(kap, beg, end, ka, va);
+                    }
             }
         }
         __syncthreads();
@@ -424,7 +509,7 @@ static hipError_t fwd_launch(const Dims& s, const void* Q, const void* K, const 
     hipError_t e = hipFuncSetAttribute((const void*)forward_mfma_kernel<D>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((forward_mfma_kernel<D>), dim3((unsigned)(ntiles * s.bh)), dim3(C::NT), C::LDS,
+    hipLaunchKernelGGL((forward_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, ntiles)), dim3(C::NT), C::LDS,
                        st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)Vt, vmax, idx,
                        (bf16_t*)O, lse, s.N, s.B, s.k, s.scale, ntiles, s.bh);
     return hipGetLastError();
@@ -432,22 +517,26 @@ static hipError_t fwd_launch(const Dims& s, const void* Q, const void* K, const 
 
 size_t forward_mfma_ws_bytes(const Dims& s)
 {
-    return sizeof(bf16_t) * (size_t)s.bh * s.N * s.D + 256 + sizeof(uint32_t) * (size_t)s.bh * s.D;
+    return 2 * (sizeof(bf16_t) * (size_t)s.bh * s.N * s.D + 256) + sizeof(uint32_t) * (size_t)s.bh * s.D;
 }
 
-// ws: [bh*N*D bf16 slot-ordered scaled V][pad to 256][bh*D fp32 bits: channel maxima]
+// ws: [bh*N*D bf16 slot-ordered scaled V][pad to 256][bh*N*D bf16 operand-ordered K][pad to 256]
+//     [bh*D fp32 bits: channel maxima of V]
 hipError_t launch_forward_mfma(const Dims& s, const void* Q, const void* K, const void* V,
                                void* ws, const int32_t* idx, const int32_t* off, const int32_t* ql,
                                const int32_t* chunk, void* O, float* lse, hipStream_t st)
 {
     const size_t vt_bytes = (sizeof(bf16_t) * (size_t)s.bh * s.N * s.D + 255) & ~(size_t)255;
-    uint32_t* vmax = reinterpret_cast<uint32_t*>((char*)ws + vt_bytes);
+    void* Ka = (char*)ws + vt_bytes;
+    uint32_t* vmax = reinterpret_cast<uint32_t*>((char*)ws + 2 * vt_bytes);
     hipError_t e = launch_absmax(s, V, vmax, st);
     if (e != hipSuccess) return e;
     e = launch_slot_major_copy(s, V, ws, vmax, st);
     if (e != hipSuccess) return e;
-    return s.D == 64 ? fwd_launch<64>(s, Q, K, ws, vmax, idx, O, lse, st)
-                     : fwd_launch<128>(s, Q, K, ws, vmax, idx, O, lse, st);
+    e = launch_operand_copy(s, K, Ka, st);
+    if (e != hipSuccess) return e;
+    return s.D == 64 ? fwd_launch<64>(s, Q, Ka, ws, vmax, idx, O, lse, st)
+                     : fwd_launch<128>(s, Q, Ka, ws, vmax, idx, O, lse, st);
 }
 
 }  // namespace moba

@@ -76,52 +76,151 @@ __host__ __device__ __forceinline__ constexpr int64_t slot_major_offset(int64_t 
     return (kap * (D / 16) + mt) * 512 + (int64_t)lane * 8;
 }
 
-// Bit matrix "which rows of this query tile go with which 32-key group", for the groups
-// [lo, hi): mask[(kap - lo) * MW + r / 32] bit r % 32.  A row goes with every group of each
-// block it kept (entries of its topk_idx row that are past blocks) and, when a block has several
-// groups, with the groups of its own block that lie wholly before it.  `idx_tile` points at the
-// tile's first topk_idx row.  The caller zeroes the mask before and synchronises after.
-template <int TILE, int NT, int MW>
-__device__ __forceinline__ void build_group_mask(uint32_t* mask, const int32_t* __restrict__ idx_tile,
-                                                 int t0, int rows_here, int k, int B, int NG, int lo,
-                                                 int hi, int tid)
+// ---- workgroup -> (slice, position) ------------------------------------------------------
+// Workgroups are dealt to the chip's 8 XCDs round robin (workgroup i runs on XCD i % 8) and
+// every XCD has an L2 of its own.  The workgroups resident on one XCD at a time should
+// therefore read the same K / V (or Q / dO) rows: with a multiple of 8 slices, XCD x works
+// through the slices x, x + 8, ... one after the other; with 1, 2 or 4 slices, 8 / bh XCDs
+// share the positions of a slice.  Anything else falls back to slice-interleaved order.
+constexpr int kXcds = 8;
+__host__ __device__ inline int schedule_grid(int bh, int npos)
 {
-    constexpr int TPR = NT / TILE;                 // threads per row
-    const int r = tid / TPR, part = tid % TPR;
-    if (r >= rows_here) return;
-    const int past = (t0 + r) / B;
-    const uint32_t bit = 1u << (r & 31);
-    uint32_t* col = mask + (r >> 5);
-    auto mark = [&](int b) {
-        if (b >= 0 && b < past) {
-            for (int gi = 0; gi < NG; ++gi) {
-                const int kap = b * NG + gi - lo;
-                if (kap >= 0 && kap < hi - lo) atomicOr(&col[kap * MW], bit);
-            }
-        }
-    };
-    const int32_t* row = idx_tile + (int64_t)r * k;
-    if ((k & 3) == 0) {                            // 16-byte loads, several in flight
-        const int4* row4 = reinterpret_cast<const int4*>(row);
-        const int n4 = k >> 2;
-        for (int e0 = part; e0 < n4; e0 += 4 * TPR) {
-            int4 v[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                v[j] = e0 + j * TPR < n4 ? row4[e0 + j * TPR] : make_int4(-1, -1, -1, -1);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) { mark(v[j].x); mark(v[j].y); mark(v[j].z); mark(v[j].w); }
-        }
-    } else {
-        for (int e = part; e < k; e += TPR) mark(row[e]);
+    if (bh % kXcds != 0 && kXcds % bh == 0) {
+        const int X = kXcds / bh;
+        return kXcds * ((npos + X - 1) / X);
     }
-    if (NG > 1 && part == 0) {
-        const int t = t0 + r;
-        for (int kap = (t / B) * NG; kap < (t >> 5); ++kap)
-            if (kap >= lo && kap < hi) atomicOr(&col[(kap - lo) * MW], bit);
+    return bh * npos;
+}
+// false: this workgroup has nothing to do
+__device__ __forceinline__ bool schedule(int bid, int bh, int npos, int& s, int& pos)
+{
+    const int xcd = bid % kXcds, local = bid / kXcds;
+    if (bh % kXcds == 0) {
+        s = xcd + kXcds * (local / npos);
+        pos = local % npos;
+        return true;
     }
+    if (kXcds % bh == 0) {
+        s = xcd % bh;
+        pos = local * (kXcds / bh) + xcd / bh;
+        return pos < npos;
+    }
+    s = bid % bh;
+    pos = bid / bh;
+    return true;
 }
 
+// Ascending list of the non-empty blocks of a set of row lists (offs as built below):
+// ulist[0 .. *count).  All NT threads; ends with a workgroup barrier.
+template <int NT>
+__device__ __forceinline__ void list_nonempty(const uint32_t* offs, int nb, uint16_t* ulist,
+                                              int* count, uint32_t* wsum, int tid)
+{
+    const int lane = tid % kWave, wave = tid / kWave;
+    int base = 0;
+    for (int c = 0; c < nb; c += NT) {
+        const int i = c + tid;
+        const bool some = i < nb && offs[i + 1] > offs[i];
+        const uint64_t b = __ballot(some);
+        if (lane == 0) wsum[wave] = (uint32_t)__popcll(b);
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int wv = 0; wv < NT / kWave; ++wv) {
+            const int n = (int)wsum[wv];
+            if (wv < wave) before += n;
+            total += n;
+        }
+        if (some) ulist[base + before + lanes_below(b)] = (uint16_t)i;
+        base += total;
+        __syncthreads();
+    }
+    if (tid == 0) *count = base;
+    __syncthreads();
+}
+
+// ---- per-tile block lists in LDS --------------------------------------------------------
+// For a tile of TILE consecutive queries and the key blocks [lo, hi): a counting sort of the
+// tile's (row, kept block) pairs by block.  Afterwards offs[j - lo] .. offs[j - lo + 1] is the
+// piece of rows8[] holding the local rows (0 .. TILE-1, one byte each) that kept block j, in no
+// particular order.  Built once per tile and range, by all NT threads; integer atomics only.
+//   cur   [hi - lo + 1] words of scratch (counters, then insertion cursors)
+//   offs  [hi - lo + 1] words
+//   rows8 cap bytes; a routing without repeats has at most min(TILE * (hi - lo), TILE * k)
+//         pairs, and pairs beyond cap are dropped rather than written
+//   wsum  NT / 64 words of scratch
+// `idx_tile` points at the tile's first topk_idx row; entries that are not past blocks of
+// their row are ignored.  Ends with a workgroup barrier.
+template <int TILE, int NT>
+__device__ __forceinline__ void build_block_lists(const int32_t* __restrict__ idx_tile, int t0,
+                                                  int rows_here, int k, int B, int lo, int hi,
+                                                  uint32_t* cur, uint32_t* offs, uint8_t* rows8,
+                                                  uint32_t cap, uint32_t* wsum, int tid)
+{
+    constexpr int TPR = NT / TILE;                 // threads per row
+    const int nb = hi - lo;
+    const int r = tid / TPR, part = tid % TPR;
+    const int past = (t0 + r) / B;
+    const int lane = tid % kWave, wave = tid / kWave;
+    auto for_each_entry = [&](auto f) {
+        if (r >= rows_here) return;
+        const int32_t* row = idx_tile + (int64_t)r * k;
+        auto one = [&](int b) { if (b >= lo && b < hi && b < past) f(b - lo); };
+        if ((k & 3) == 0) {                        // 16-byte loads, several in flight
+            const int4* row4 = reinterpret_cast<const int4*>(row);
+            const int n4 = k >> 2;
+            for (int e0 = part; e0 < n4; e0 += 4 * TPR) {
+                int4 v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    v[j] = e0 + j * TPR < n4 ? row4[e0 + j * TPR] : make_int4(-1, -1, -1, -1);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { one(v[j].x); one(v[j].y); one(v[j].z); one(v[j].w); }
+            }
+        } else {
+            for (int e = part; e < k; e += TPR) one(row[e]);
+        }
+    };
+    for (int i = tid; i <= nb; i += NT) cur[i] = 0u;
+    __syncthreads();
+    for_each_entry([&](int j) { atomicAdd(&cur[j], 1u); });
+    __syncthreads();
+    // exclusive scan of the counts: each thread takes EPT consecutive blocks
+    constexpr int kMaxRange = 1024;
+    constexpr int EPT = (kMaxRange + NT - 1) / NT;
+    uint32_t v[EPT], sum = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const int j = tid * EPT + e;
+        v[e] = j < nb ? cur[j] : 0u;
+        sum += v[e];
+    }
+    uint32_t incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += t;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    uint32_t base = incl - sum;
+    for (int wv = 0; wv < wave; ++wv) base += wsum[wv];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const int j = tid * EPT + e;
+        if (j < nb) { offs[j] = base; cur[j] = base; }
+        base += v[e];
+        if (j == nb - 1) offs[nb] = base;
+    }
+    __syncthreads();
+    for_each_entry([&](int j) {
+        const uint32_t pos = atomicAdd(&cur[j], 1u);
+        if (pos < cap) rows8[pos] = (uint8_t)r;
+    });
+    __syncthreads();
+}
+
+hipError_t launch_operand_copy(const Dims& s, const void* X, void* Xa, hipStream_t st);
 hipError_t launch_absmax(const Dims& s, const void* X, uint32_t* vmax, hipStream_t st);
 hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, const uint32_t* vmax,
                                   hipStream_t st);
