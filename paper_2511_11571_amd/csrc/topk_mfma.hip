@@ -25,18 +25,33 @@ constexpr int kHistWords = 32;            // 64 bins of 16 bits per query
 constexpr int kHistStride = 33;           // odd row stride: queries land on different LDS banks
 constexpr int kTopkMfmaMaxBlocks = 2048;  // bit row of a query: at most 64 words
 
-__global__ void split3_kernel(const float* __restrict__ c, bf16_t* __restrict__ out, int64_t count)
+// c3 <- the three bf16 terms of the fp32 centroids, in MFMA operand order: the 16 bytes lane
+// (m, g) feeds to the MFMA for blocks 16 jt + m, channels 32 ks + 8 g .. + 8, term t, sit at
+// (((slice * ntile + jt) * 3 + t) * (D / 32) + ks) * 1024 + 16 * lane, so that one load
+// instruction of a wave covers 1 KB of consecutive bytes.  Blocks beyond n read as zero.
+template <int D>
+__global__ void split3_kernel(const float* __restrict__ c, bf16_t* __restrict__ out, int n, int ntile,
+                              int64_t chunks)
 {
+    constexpr int KS = D / 32;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count) return;
-    const float x = c[i];
-    const bf16_t hi = f32_to_bf16(x);
-    const float r1 = x - bf16_to_f32(hi);
-    const bf16_t mid = f32_to_bf16(r1);
-    const float r2 = r1 - bf16_to_f32(mid);
-    out[i] = hi;
-    out[count + i] = mid;
-    out[2 * count + i] = f32_to_bf16(r2);
+    if (i >= chunks) return;
+    const int lane = (int)(i % 64), ks = (int)((i / 64) % KS), term = (int)((i / (64 * KS)) % 3);
+    const int64_t tile = i / (64 * KS * 3);
+    const int jt = (int)(tile % ntile);
+    const int64_t s = tile / ntile;
+    const int row = 16 * jt + (lane & 15), g = lane >> 4;
+    bf16_t o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float x = row < n ? c[(s * n + row) * D + 32 * ks + 8 * g + e] : 0.f;
+        const bf16_t hi = f32_to_bf16(x);
+        const float r1 = x - bf16_to_f32(hi);
+        const bf16_t mid = f32_to_bf16(r1);
+        const float r2 = r1 - bf16_to_f32(mid);
+        o[e] = term == 0 ? hi : term == 1 ? mid : f32_to_bf16(r2);
+    }
+    *reinterpret_cast<uint4*>(out + i * 8) = *reinterpret_cast<const uint4*>(o);
 }
 
 // the score whose order_key is `key`; `none` when the key does not belong to a number
@@ -49,19 +64,18 @@ __device__ __forceinline__ float key_score(uint32_t key, float none)
 // One sweep over the centroid tiles of a 64-query strip.  f(qt, sc, j0): sc[i] is the score of
 // query 16*qt + m16 against block j0 + i (j0 = 16*tile + 4*g).
 template <int D, typename F>
-__device__ __forceinline__ void sweep_tiles(const bf16_t* __restrict__ c3, int64_t cstride,
-                                            int64_t cbase, int n, int tile_lo, int tile_hi,
-                                            const Frag (&qb)[4][D / 32], int m16, int g, F f)
+__device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int tile_lo, int tile_hi,
+                                            const Frag (&qb)[4][D / 32], int lane, int g, F f)
 {
     constexpr int KS = D / 32;
     for (int jt = tile_lo; jt < tile_hi; ++jt) {
-        const int row = min(16 * jt + m16, n - 1);
+        const char* tb = c3s + (int64_t)jt * (3 * KS * 1024) + lane * 16;
         Frag a[3][KS];
 #pragma unroll
         for (int term = 0; term < 3; ++term)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                a[term][ks].q = *reinterpret_cast<const uint4*>(c3 + term * cstride + (cbase + row) * D + 8 * g + 32 * ks);
+                a[term][ks].q = *reinterpret_cast<const uint4*>(tb + (term * KS + ks) * 1024);
         // the four 16-query tiles are independent accumulation chains: issue them interleaved so
         // that no MFMA waits for the one before it
         f32x4_t sc[4];
@@ -80,7 +94,7 @@ __device__ __forceinline__ void sweep_tiles(const bf16_t* __restrict__ c3, int64
 
 template <int D>
 __global__ __launch_bounds__(256) void topk_mfma_kernel(
-    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ c3, int64_t cstride,
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ c3, int ntile_all,
     int32_t* __restrict__ idx, int N, int B, int n, int k, int strips_per_slice,
     int64_t total_strips, int Wn)
 {
@@ -102,7 +116,7 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
     const int s = (int)(strip / strips_per_slice);
     const int t0 = (int)(strip % strips_per_slice) * 64;
     const int rows_here = min(64, N - t0);
-    const int64_t cbase = (int64_t)s * n;
+    const char* c3s = reinterpret_cast<const char*>(c3) + (int64_t)s * ntile_all * (3 * KS * 1024);
     int32_t* out = idx + ((int64_t)s * N + t0) * k;
 
     {   // lane = query: initial state
@@ -133,9 +147,9 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
     const int ntile_int = min(ntile, (t0 / B) / 16);
     auto sweep = [&](int tlo, int thi, auto f) {
         const int mid = min(max(ntile_int, tlo), thi);
-        sweep_tiles<D>(c3, cstride, cbase, n, tlo, mid, qb, m16, g,
+        sweep_tiles<D>(c3s, tlo, mid, qb, lane, g,
                        [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::false_type()); });
-        sweep_tiles<D>(c3, cstride, cbase, n, mid, thi, qb, m16, g,
+        sweep_tiles<D>(c3s, mid, thi, qb, lane, g,
                        [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::true_type()); });
     };
 
@@ -266,7 +280,7 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
 
 size_t topk_mfma_ws_bytes(const Dims& s)
 {
-    return 3 * sizeof(bf16_t) * (size_t)s.bh * s.n * s.D;
+    return 3 * sizeof(bf16_t) * (size_t)s.bh * ((s.n + 15) / 16 * 16) * s.D;
 }
 
 bool topk_mfma_supported(const Dims& s)
@@ -287,19 +301,22 @@ static hipError_t topk_launch(const Dims& s, const void* Q, const bf16_t* c3, in
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((topk_mfma_kernel<D>), dim3((unsigned)((strips + 3) / 4)), dim3(256), lds, st,
-                       (const bf16_t*)Q, c3, (int64_t)s.bh * s.n * s.D, idx, s.N, s.B, s.n, s.k, sps,
-                       strips, Wn);
+                       (const bf16_t*)Q, c3, (s.n + 15) / 16, idx, s.N, s.B, s.n, s.k, sps, strips, Wn);
     return hipGetLastError();
 }
 
 hipError_t launch_topk_mfma(const Dims& s, const void* Q, const float* cent, int32_t* idx, void* ws,
                             hipStream_t st)
 {
-    const int64_t count = (int64_t)s.bh * s.n * s.D;
-    if (count == 0) return hipSuccess;
+    const int ntile = (s.n + 15) / 16;
+    const int64_t chunks = (int64_t)s.bh * ntile * 3 * (s.D / 32) * 64;
+    if (chunks == 0) return hipSuccess;
     bf16_t* c3 = (bf16_t*)ws;
-    hipLaunchKernelGGL(split3_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, cent, c3,
-                       count);
+    const unsigned grid = (unsigned)((chunks + 255) / 256);
+    if (s.D == 64)
+        hipLaunchKernelGGL(split3_kernel<64>, dim3(grid), dim3(256), 0, st, cent, c3, s.n, ntile, chunks);
+    else
+        hipLaunchKernelGGL(split3_kernel<128>, dim3(grid), dim3(256), 0, st, cent, c3, s.n, ntile, chunks);
     return s.D == 64 ? topk_launch<64>(s, Q, c3, idx, st) : topk_launch<128>(s, Q, c3, idx, st);
 }
 
