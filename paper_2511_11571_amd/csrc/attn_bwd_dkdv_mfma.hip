@@ -8,50 +8,69 @@
 // through LDS at the end.
 //
 // Per step, with queries as the contraction index of the two accumulating products:
-//   S  = Q_g K^T, dP = dO_g V^T          gathered rows straight from global memory as A
-//                                        operands, K and V rows of the group as B operands;
+//   gather                               the 32 rows of Q and dO come in with 8 (d = 64) lanes
+//                                        per row, whole 128-byte lines per load instruction
+//                                        (the rate of a lane-per-row gather is a quarter of
+//                                        that on this chip), and are parked in LDS;
+//   S  = Q_g K^T, dP = dO_g V^T          A operands read back from LDS row by row, K and V rows
+//                                        of the group as B operands (registers, loaded once);
 //   P, dS                                in the result layout: a lane holds one key column
 //                                        and query rows 4g..4g+3 of both 16-query tiles,
 //                                        which packed to bf16 is already a B operand over
 //                                        the 32 queries (slot order of mfma.h);
-//   dV^T += dO_g^T P, dK^T += Q_g^T dS   the A operands need the gathered rows transposed:
-//                                        they are parked in LDS and read back 16 bits at a
-//                                        time in the same slot order.
+//   dV^T += dO_g^T P, dK^T += Q_g^T dS   the A operands are the parked rows transposed, which
+//                                        the LDS transpose read of gfx950 (ds_read_b64_tr_b16)
+//                                        delivers four query slots per lane at a time.
 #include "mfma.h"
 
 namespace moba {
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 template <int D>
 struct DkvCfg {
     static constexpr int NW = 4;
     static constexpr int NT = NW * kWave;
-    static constexpr int SSTRIDE = D + 4;              // bf16 per staged row: 4 rows shift 8 banks
+    static constexpr int SB = D * 2 + 16;              // bytes per parked row
     static constexpr int MT = D / 16;
     static constexpr int KS = D / 32;
+    static constexpr int CPR = D / 8;                  // 16-byte chunks per row
+    static constexpr int RPI = kWave / CPR;            // rows per gather instruction
+    static constexpr int NI = 32 / RPI;                // gather instructions per tensor and step
     static constexpr int RSTRIDE = D + 4;              // floats per key row of the reduction buffer
-    static constexpr size_t STAGE = (size_t)2 * 32 * SSTRIDE * 2;          // Q and dO, bytes per wave
+    static constexpr size_t STAGE = (size_t)2 * 32 * SB;                   // Q and dO, bytes per wave
     static constexpr size_t LDS = NW * (STAGE + 2 * 32 * 4) + (size_t)2 * 32 * RSTRIDE * 4;
 };
+
+// LDS transpose read: within each group of 16 lanes, lane i receives as element e the 16-bit
+// element (i & 3) of the 8 bytes that lane 4 e + (i >> 2) of the group points at.
+__device__ __forceinline__ uint2 lds_read_tr16(const unsigned char* p)
+{
+    typedef short v4s __attribute__((ext_vector_type(4)));
+    const v4s r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) v4s*)(const_cast<unsigned char*>(p)));
+    return *reinterpret_cast<const uint2*>(&r);
+}
 
 template <int D>
 __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ Dv,
     const int32_t* __restrict__ off, const int32_t* __restrict__ ql, bf16_t* __restrict__ dK,
-    bf16_t* __restrict__ dV, int N, int B, int n, float scale, int64_t R, int groups_per_slice)
+    bf16_t* __restrict__ dV, int N, int B, int n, float scale, int64_t R, int groups_per_slice, int bh)
 {
     using C = DkvCfg<D>;
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int m16 = lane & 15, g = lane >> 4;
-    bf16_t* stQ = reinterpret_cast<bf16_t*>(smem + wave * (C::STAGE + 256));
-    bf16_t* stG = stQ + 32 * C::SSTRIDE;
-    float* ls = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(stQ) + C::STAGE);
+    unsigned char* stQ = smem + wave * (C::STAGE + 256);
+    unsigned char* stG = stQ + 32 * C::SB;
+    float* ls = reinterpret_cast<float*>(stQ + C::STAGE);
     float* Ds = ls + 32;
     float* red = reinterpret_cast<float*>(smem + C::NW * (C::STAGE + 256));    // [2][32][RSTRIDE]
 
-    const int s = blockIdx.x / groups_per_slice;
-    const int kap = blockIdx.x % groups_per_slice;          // 32-key group inside the slice
+    int s, kap;                                             // slice, 32-key group inside the slice
+    if (!schedule(blockIdx.x, bh, groups_per_slice, s, kap)) return;
     const int NG = B / 32;
     const int j = kap / NG;
     const int64_t sbase = (int64_t)s * N;
@@ -61,6 +80,8 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
     const int lo = os[j], nlist = os[j + 1] - lo;
     const int own0 = 32 * kap;                              // first own query that sees this group
     const int total = nlist + (j + 1) * B - own0;
+    const char* Qg = reinterpret_cast<const char*>(Q + sbase * D);
+    const char* Gg = reinterpret_cast<const char*>(dO + sbase * D);
 
     // B operands: the group's keys and values (lane = key m16 of tile nt)
     Frag kb[2][C::KS], vb[2][C::KS];
@@ -81,100 +102,103 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
             dVT[mt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         }
 
+    // position a of the walk -> query: the block's list, then its own queries from this group on
+    auto query_at = [&](int a) { return a >= total ? own0 : (a < nlist ? qs[lo + a] : own0 + (a - nlist)); };
     // The gathers are the long pole (two dependent global loads: list entry, then the row), so
     // they run ahead of the arithmetic: row ids two steps ahead, rows one step ahead.
-    auto ids = [&](int a0, int (&t)[2], bool (&ok)[2]) {
+    const int grow = lane / C::CPR;                          // row of this lane inside a gather instruction
+    const uint32_t gcol = (uint32_t)(lane % C::CPR) * 16u;   // its bytes inside the row
+    auto ids = [&](int a0, int (&t)[C::NI], int& tl) {
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            const int a = a0 + 16 * qt + m16;
-            ok[qt] = a < total;
-            t[qt] = !ok[qt] ? own0 : (a < nlist ? qs[lo + a] : own0 + (a - nlist));
-        }
+        for (int i = 0; i < C::NI; ++i) t[i] = query_at(a0 + C::RPI * i + grow);
+        tl = query_at(a0 + (lane & 31));
     };
-    auto fetch = [&](const int (&t)[2], const bool (&ok)[2], Frag (&qa)[2][C::KS], Frag (&ga)[2][C::KS],
-                     float (&lv)[2], float (&dv)[2]) {
+    auto fetch = [&](int a0, const int (&t)[C::NI], int tl, u32x4_t (&qr)[C::NI], u32x4_t (&gr)[C::NI],
+                     float& lv, float& dv) {
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-#pragma unroll
-            for (int ks = 0; ks < C::KS; ++ks) {
-                const int64_t o = (sbase + t[qt]) * D + 8 * g + 32 * ks;
-                qa[qt][ks].q = *reinterpret_cast<const uint4*>(Q + o);
-                ga[qt][ks].q = *reinterpret_cast<const uint4*>(dO + o);
-            }
-            lv[qt] = INFINITY;                        // rows past the list: P = 0
-            dv[qt] = 0.f;
-            if (g == 0 && ok[qt]) {
-                lv[qt] = lse[sbase + t[qt]] * kLog2e;
-                dv[qt] = Dv[sbase + t[qt]];
-            }
+        for (int i = 0; i < C::NI; ++i) {
+            const uint32_t o = (uint32_t)t[i] * (uint32_t)(2 * D) + gcol;
+            qr[i] = *reinterpret_cast<const u32x4_t*>(Qg + o);
+            gr[i] = *reinterpret_cast<const u32x4_t*>(Gg + o);
+        }
+        lv = INFINITY;                                // rows past the end of the walk: P = 0
+        dv = 0.f;
+        if (a0 + (lane & 31) < total) {
+            lv = lse[sbase + tl] * kLog2e;
+            dv = Dv[sbase + tl];
         }
     };
     const int stride = 32 * C::NW;
-    int tN[2];
-    bool okN[2];
-    Frag qa[2][C::KS], ga[2][C::KS], qaN[2][C::KS], gaN[2][C::KS];
-    float lv[2], dv[2], lvN[2], dvN[2];
+    int tN[C::NI], tlN;
+    u32x4_t qr[C::NI], gr[C::NI];    // plain vectors: a struct type would be copied through scratch
+    float lv, dv;
     {
-        int t0[2];
-        bool ok0[2];
-        ids(32 * wave, t0, ok0);
-        fetch(t0, ok0, qa, ga, lv, dv);
-        ids(32 * wave + stride, tN, okN);
+        int t0[C::NI], tl0;
+        ids(32 * wave, t0, tl0);
+        fetch(32 * wave, t0, tl0, qr, gr, lv, dv);
+        ids(32 * wave + stride, tN, tlN);
     }
+    const uint32_t park = (uint32_t)grow * C::SB + gcol;                       // gather lane -> parked bytes
+    const uint32_t arow = (uint32_t)m16 * C::SB + 16u * g;                     // row-major operand of this lane
+    // transpose read: lanes 4 e + a of a 16-lane group point at query slot e (+4), channels 4 a ..
+    const int te = (lane >> 2) & 3, ta = lane & 3;
+    const uint32_t tr0 = (uint32_t)slot_key(g, te) * C::SB + 8u * ta;
+    const uint32_t tr1 = (uint32_t)slot_key(g, te + 4) * C::SB + 8u * ta;
     for (int a0 = 32 * wave; a0 < total; a0 += stride) {
-        fetch(tN, okN, qaN, gaN, lvN, dvN);
-        ids(a0 + 2 * stride, tN, okN);
-        if (g == 0) {
+        // park this step's rows, then put the next step's loads in flight
 #pragma unroll
-            for (int qt = 0; qt < 2; ++qt) {
-                ls[16 * qt + m16] = lv[qt];
-                Ds[16 * qt + m16] = dv[qt];
-            }
+        for (int i = 0; i < C::NI; ++i) {
+            *reinterpret_cast<u32x4_t*>(stQ + park + i * C::RPI * C::SB) = qr[i];
+            *reinterpret_cast<u32x4_t*>(stG + park + i * C::RPI * C::SB) = gr[i];
         }
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-            for (int ks = 0; ks < C::KS; ++ks) {
-                const int o = (16 * qt + m16) * C::SSTRIDE + 8 * g + 32 * ks;
-                *reinterpret_cast<uint2*>(stQ + o) = make_uint2(qa[qt][ks].u[0], qa[qt][ks].u[1]);
-                *reinterpret_cast<uint2*>(stQ + o + 4) = make_uint2(qa[qt][ks].u[2], qa[qt][ks].u[3]);
-                *reinterpret_cast<uint2*>(stG + o) = make_uint2(ga[qt][ks].u[0], ga[qt][ks].u[1]);
-                *reinterpret_cast<uint2*>(stG + o + 4) = make_uint2(ga[qt][ks].u[2], ga[qt][ks].u[3]);
-            }
+        if (lane < 32) { ls[lane] = lv; Ds[lane] = dv; }
+        fetch(a0 + stride, tN, tlN, qr, gr, lv, dv);
+        ids(a0 + 2 * stride, tN, tlN);
+        __builtin_amdgcn_wave_barrier();
         // S and dP
         f32x4_t sc[2][2], dp[2][2];
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
+        for (int qt = 0; qt < 2; ++qt) {
+            Frag qa[C::KS], ga[C::KS];
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ++ks) {
+                qa[ks].q = *reinterpret_cast<const uint4*>(stQ + arow + qt * 16 * C::SB + 64 * ks);
+                ga[ks].q = *reinterpret_cast<const uint4*>(stG + arow + qt * 16 * C::SB + 64 * ks);
+            }
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) {
                 sc[qt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
                 dp[qt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < C::KS; ++ks) {
-                    sc[qt][nt] = mfma16(qa[qt][ks], kb[nt][ks], sc[qt][nt]);
-                    dp[qt][nt] = mfma16(ga[qt][ks], vb[nt][ks], dp[qt][nt]);
+                    sc[qt][nt] = mfma16(qa[ks], kb[nt][ks], sc[qt][nt]);
+                    dp[qt][nt] = mfma16(ga[ks], vb[nt][ks], dp[qt][nt]);
                 }
             }
-        __builtin_amdgcn_wave_barrier();
+        }
         // own queries of this very group are causal: key (16 nt + m16) must not exceed the query
         const bool causal = a0 + 32 > nlist && a0 < nlist + 32;    // the step touches own rows 0..31
         Frag pb[2], sb[2];
+        f32x4_t l4[2], d4[2];
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            l4[qt] = *reinterpret_cast<const f32x4_t*>(ls + 16 * qt + 4 * g);
+            d4[qt] = *reinterpret_cast<const f32x4_t*>(Ds + 16 * qt + 4 * g);
+        }
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
             float p[8], d[8];
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt) {
-                const f32x4_t l4 = *reinterpret_cast<const f32x4_t*>(ls + 16 * qt + 4 * g);
-                const f32x4_t d4 = *reinterpret_cast<const f32x4_t*>(Ds + 16 * qt + 4 * g);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float pv = fast_exp2(fmaf(sc[qt][nt][i], c2, -l4[i]));
+                    float pv = fast_exp2(fmaf(sc[qt][nt][i], c2, -l4[qt][i]));
                     if (causal) {
                         const int a = a0 + 16 * qt + 4 * g + i - nlist;     // own row index, if >= 0
                         if (a >= 0 && a < 32 && 16 * nt + m16 > a) pv = 0.f;
                     }
                     p[4 * qt + i] = pv;
-                    d[4 * qt + i] = pv * (dp[qt][nt][i] - d4[i]);
+                    d[4 * qt + i] = pv * (dp[qt][nt][i] - d4[qt][i]);
                 }
             }
 #pragma unroll
@@ -183,17 +207,14 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
                 sb[nt].u[e] = pack2(d[2 * e], d[2 * e + 1]);
             }
         }
-        // transposed A operands from the staged rows, then the two accumulating products
+        // transposed A operands from the parked rows, then the two accumulating products
 #pragma unroll
         for (int mt = 0; mt < C::MT; ++mt) {
             Frag qT, gT;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int r0 = slot_key(g, 2 * e) * C::SSTRIDE + 16 * mt + m16;
-                const int r1 = slot_key(g, 2 * e + 1) * C::SSTRIDE + 16 * mt + m16;
-                qT.u[e] = (uint32_t)stQ[r0] | ((uint32_t)stQ[r1] << 16);
-                gT.u[e] = (uint32_t)stG[r0] | ((uint32_t)stG[r1] << 16);
-            }
+            const uint2 q0 = lds_read_tr16(stQ + tr0 + 32 * mt), q1 = lds_read_tr16(stQ + tr1 + 32 * mt);
+            const uint2 g0 = lds_read_tr16(stG + tr0 + 32 * mt), g1 = lds_read_tr16(stG + tr1 + 32 * mt);
+            qT.u[0] = q0.x; qT.u[1] = q0.y; qT.u[2] = q1.x; qT.u[3] = q1.y;
+            gT.u[0] = g0.x; gT.u[1] = g0.y; gT.u[2] = g1.x; gT.u[3] = g1.y;
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) {
                 dVT[mt][nt] = mfma16(gT, pb[nt], dVT[mt][nt]);
@@ -201,13 +222,6 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
             }
         }
         __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-#pragma unroll
-            for (int ks = 0; ks < C::KS; ++ks) { qa[qt][ks] = qaN[qt][ks]; ga[qt][ks] = gaN[qt][ks]; }
-            lv[qt] = lvN[qt];
-            dv[qt] = dvN[qt];
-        }
     }
 
     // sum the four waves' accumulators through LDS: red[tensor][key][channel]
@@ -254,9 +268,9 @@ static hipError_t dkdv_launch(const Dims& s, const void* Q, const void* K, const
     hipError_t e = hipFuncSetAttribute((const void*)dkdv_mfma_kernel<D>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((dkdv_mfma_kernel<D>), dim3((unsigned)(gps * s.bh)), dim3(C::NT), C::LDS, st,
+    hipLaunchKernelGGL((dkdv_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, gps)), dim3(C::NT), C::LDS, st,
                        (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, Dv,
-                       off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, gps);
+                       off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, gps, s.bh);
     return hipGetLastError();
 }
 
