@@ -68,14 +68,15 @@ __device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int ti
                                             const Frag (&qb)[4][D / 32], int lane, int g, F f)
 {
     constexpr int KS = D / 32;
-    for (int jt = tile_lo; jt < tile_hi; ++jt) {
+    auto load = [&](int jt, Frag (&a)[3][KS]) {
         const char* tb = c3s + (int64_t)jt * (3 * KS * 1024) + lane * 16;
-        Frag a[3][KS];
 #pragma unroll
         for (int term = 0; term < 3; ++term)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
                 a[term][ks].q = *reinterpret_cast<const uint4*>(tb + (term * KS + ks) * 1024);
+    };
+    auto run = [&](int jt, const Frag (&a)[3][KS]) {
         // the four 16-query tiles are independent accumulation chains: issue them interleaved so
         // that no MFMA waits for the one before it
         f32x4_t sc[4];
@@ -89,6 +90,18 @@ __device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int ti
                 for (int qt = 0; qt < 4; ++qt) sc[qt] = mfma16(a[term][ks], qb[qt][ks], sc[qt]);
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) f(qt, sc[qt], 16 * jt + 4 * g);
+    };
+    // the operands of the next tile are in flight while the current one is worked on
+    Frag a0[3][KS], a1[3][KS];
+    int jt = tile_lo;
+    if (jt < tile_hi) load(jt, a0);
+    while (jt < tile_hi) {
+        if (jt + 1 < tile_hi) load(jt + 1, a1);
+        run(jt, a0);
+        if (++jt >= tile_hi) break;
+        if (jt + 1 < tile_hi) load(jt + 1, a0);
+        run(jt, a1);
+        ++jt;
     }
 }
 
