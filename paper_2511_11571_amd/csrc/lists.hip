@@ -9,29 +9,57 @@
 //      inside the block's list; kept as the blk_chunk output, which lets a query-tile kernel
 //      find "its" rows of any block's list directly), then an exclusive scan of the block
 //      totals (blk_off).
-//   3. fill: the bit matrix is rebuilt and each row's set bits are written out in
-//      ascending order at blk_off[j] + chunk start.
-// The bit matrix lives in LDS only and covers 2048 key blocks at a time.
+//   3. fill: the bit matrix is rebuilt; the place of query q in block j's list is
+//      blk_off[j] + chunk start + (number of set bits of row j below q), so every (query, kept
+//      block) pair writes its own entry and the lists come out ascending.
+// The bit matrix lives in LDS only and covers 1024 key blocks at a time.
 #include "common.h"
 
 namespace moba {
 
-constexpr int kRange = 2048;                    // key blocks per LDS bit matrix (64 KB)
+constexpr int kRange = 1024;                    // key blocks per LDS bit matrix (32 KB)
 constexpr int kListQ = 2 * kChunkQ;              // queries per workgroup: two chunks of 128
 constexpr int kWords = kListQ / 32;             // 8 words of 32 query bits per block
 
+// f(r, b) for every entry b of the routing rows r = 0 .. rows-1 of this workgroup (k entries per
+// row, rows contiguous in memory), all 256 threads, 16-byte loads when the row length allows
+template <typename F>
+__device__ __forceinline__ void for_each_entry(const int32_t* __restrict__ rows0, int rows, int k,
+                                               int tid, F f)
+{
+    const int total = rows * k;
+    if ((k & 3) == 0) {
+        const int4* p4 = reinterpret_cast<const int4*>(rows0);
+        const int n4 = total >> 2;
+        for (int i0 = tid; i0 < n4; i0 += 4 * 256) {
+            int4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[u] = i0 + u * 256 < n4 ? p4[i0 + u * 256] : make_int4(-1, -1, -1, -1);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = ((i0 + u * 256) << 2) / k;     // a 16-byte piece never straddles rows
+                f(r, v[u].x); f(r, v[u].y); f(r, v[u].z); f(r, v[u].w);
+            }
+        }
+    } else {
+        for (int i = tid; i < total; i += 256) f(i / k, rows0[i]);
+    }
+}
 
 template <bool FILL>
 __global__ __launch_bounds__(256) void lists_chunk_kernel(
     const int32_t* __restrict__ idx, int32_t* __restrict__ cnt2, const int32_t* __restrict__ off,
     int32_t* __restrict__ ql, int N, int B, int n, int k, int nchunk, int64_t R)
 {
-    __shared__ uint32_t mask[kRange * kWords];
+    __shared__ __align__(16) uint32_t mask[kRange * kWords];
+    __shared__ int32_t start[FILL ? 2 * kRange : 2];     // first list position of each half's queries
     const int c = blockIdx.x, s = blockIdx.z;
     const int lo = blockIdx.y * kRange;
     const int hi = min(n, lo + kRange);
-    const int t_last = min(N, (c + 1) * kListQ) - 1;
-    const int nblk = min(hi, t_last / B) - lo;          // kept blocks are < own block of t_last
+    const int t0 = c * kListQ;
+    const int rows = min(N - t0, kListQ);
+    const int nblk = min(hi, (t0 + rows - 1) / B) - lo;   // kept blocks are < own block of the last query
     const int tid = threadIdx.x;
     // this workgroup covers chunks 2c and 2c+1 (the second may not exist)
     int32_t* crow = cnt2 + ((int64_t)s * (nchunk + 1) + 2 * c) * n + lo;
@@ -45,18 +73,20 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
         return;
     }
     for (int i = tid; i < nblk * kWords; i += 256) mask[i] = 0u;
-    __syncthreads();
-    const int t = c * kListQ + tid;
-    if (t < N) {
-        const int32_t* row = idx + ((int64_t)s * N + t) * k;
-        const uint32_t bit = 1u << (tid & 31);
-        const int word = tid >> 5;
-        const int past = t / B;            // only past blocks count: lists never exceed R
-        for (int e = 0; e < k; ++e) {
-            const int b = row[e] - lo;
-            if (b >= 0 && b < nblk && b + lo < past) atomicOr(&mask[b * kWords + word], bit);
+    if (FILL) {
+        const int32_t* orow = off + (int64_t)s * (n + 1) + lo;
+        for (int j = tid; j < nblk; j += 256) {
+            start[j] = orow[j] + crow[j];
+            start[kRange + j] = orow[j] + (two ? crow[n + j] : 0);
         }
     }
+    __syncthreads();
+    const int32_t* rows0 = idx + ((int64_t)s * N + t0) * k;
+    // only past blocks count: lists never exceed R
+    for_each_entry(rows0, rows, k, tid, [&](int r, int b) {
+        b -= lo;
+        if (b >= 0 && b < nblk && b + lo < (t0 + r) / B) atomicOr(&mask[b * kWords + (r >> 5)], 1u << (r & 31));
+    });
     __syncthreads();
     if (!FILL) {
         for (int j = tid; j < hi - lo; j += 256) {
@@ -72,43 +102,69 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
             if (two) crow[n + j] = c1;
         }
     } else {
-        const int wave = tid / kWave, lane = tid % kWave;
-        const int32_t* orow = off + (int64_t)s * (n + 1) + lo;
         int32_t* qs = ql + (int64_t)s * R;
-        for (int j = wave; j < nblk; j += 4) {
-            int base = orow[j] + crow[j];
-#pragma unroll
-            for (int r = 0; r < kListQ / kWave; ++r) {
-                const int q = r * kWave + lane;
-                const bool on = (mask[j * kWords + (q >> 5)] >> (q & 31)) & 1u;
-                const uint64_t m = __ballot(on);
-                if (on) qs[base + lanes_below(m)] = c * kListQ + q;
-                base += __popcll(m);
-            }
-        }
+        for_each_entry(rows0, rows, k, tid, [&](int r, int b) {
+            b -= lo;
+            if (!(b >= 0 && b < nblk && b + lo < (t0 + r) / B)) return;
+            const int half = r >> 7, w = (r >> 5) & 3;
+            const uint4 m = *reinterpret_cast<const uint4*>(&mask[b * kWords + 4 * half]);
+            const uint32_t below = (1u << (r & 31)) - 1u;
+            const int rank = __popc(m.x & (w > 0 ? ~0u : below)) +
+                             (w >= 1 ? __popc(m.y & (w > 1 ? ~0u : below)) : 0) +
+                             (w >= 2 ? __popc(m.z & (w > 2 ? ~0u : below)) : 0) +
+                             (w >= 3 ? __popc(m.w & below) : 0);
+            const int pos = start[half * kRange + b] + rank;
+            // a routing that breaks the contract (repeats, too many kept blocks) must not write
+            // outside the slice's lists
+            if ((int64_t)pos < R) qs[pos] = t0 + r;
+        });
     }
 }
 
-// per slice: cnt2[c][j] <- sum_{c' < c} cnt2[c'][j] (row nchunk: the total);  off[j] <- sum_{j' < j} total[j']
+// per slice and key block: blk_chunk[c][j] <- sum_{c' < c} count[c'][j] (row nchunk: the total).
+// A workgroup takes 32 key blocks; 8 threads per block share the chunks.
 __global__ __launch_bounds__(256) void lists_scan_kernel(int32_t* __restrict__ cnt2,
                                                          int32_t* __restrict__ off, int n,
                                                          int nchunk)
 {
-    __shared__ int part[256];
-    const int s = blockIdx.x, tid = threadIdx.x;
+    __shared__ int part[8][33];
+    const int s = blockIdx.y, tid = threadIdx.x;
+    const int jj = tid & 31, seg = tid >> 5;
+    const int j = blockIdx.x * 32 + jj;
     int32_t* cs = cnt2 + (int64_t)s * (nchunk + 1) * n;
-    int32_t* os = off + (int64_t)s * (n + 1);
-    for (int j = tid; j < n; j += 256) {
-        int run = 0;
-        for (int c = 0; c < nchunk; ++c) {
+    const int per = (nchunk + 7) / 8;
+    const int c0 = min(nchunk, seg * per), c1 = min(nchunk, c0 + per);
+    int sum = 0;
+    if (j < n)
+        for (int c = c0; c < c1; ++c) sum += cs[(int64_t)c * n + j];
+    part[seg][jj] = sum;
+    __syncthreads();
+    int run = 0, total = 0;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+        const int v = part[g][jj];
+        if (g < seg) run += v;
+        total += v;
+    }
+    if (j < n) {
+        for (int c = c0; c < c1; ++c) {
             const int v = cs[(int64_t)c * n + j];
             cs[(int64_t)c * n + j] = run;
             run += v;
         }
-        cs[(int64_t)nchunk * n + j] = run;
-        os[j + 1] = run;
+        if (seg == 0) {
+            cs[(int64_t)nchunk * n + j] = total;
+            off[(int64_t)s * (n + 1) + j + 1] = total;
+        }
     }
-    __syncthreads();
+}
+
+// per slice: off[j] <- sum_{j' < j} total[j'] (off[j + 1] holds total[j] on entry)
+__global__ __launch_bounds__(256) void lists_offsets_kernel(int32_t* __restrict__ off, int n)
+{
+    __shared__ int part[256];
+    const int s = blockIdx.x, tid = threadIdx.x;
+    int32_t* os = off + (int64_t)s * (n + 1);
     const int seg = (n + 255) / 256;
     const int a = min(n, tid * seg), b = min(n, a + seg);
     int sum = 0;
@@ -132,7 +188,9 @@ hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, i
     dim3 grid((s.nchunk + 1) / 2, nranges, s.bh), block(256);
     hipLaunchKernelGGL((lists_chunk_kernel<false>), grid, block, 0, st, idx, cnt2,
                        (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R);
-    hipLaunchKernelGGL(lists_scan_kernel, dim3(s.bh), block, 0, st, cnt2, off, s.n, s.nchunk);
+    hipLaunchKernelGGL(lists_scan_kernel, dim3((s.n + 31) / 32, s.bh), block, 0, st, cnt2, off, s.n,
+                       s.nchunk);
+    hipLaunchKernelGGL(lists_offsets_kernel, dim3(s.bh), block, 0, st, off, s.n);
     if (s.R > 0)
         hipLaunchKernelGGL((lists_chunk_kernel<true>), grid, block, 0, st, idx, cnt2,
                            (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R);
