@@ -35,7 +35,7 @@ struct DqCfg {
     static constexpr int RANGE = 1024;                 // key blocks per set of row lists (at most)
     static constexpr int LCAP = 16384;                 // (row, block) pairs per set of row lists
     static constexpr size_t LDS = (size_t)2 * TILE * ROWB + 4 * TILE * OSTRIDE + 4 * 3 * TILE +
-                                  4 * 2 * (RANGE + 1) + 4 * NW + 4 + LCAP + 64;
+                                  4 * 2 * (RANGE + 1) + 4 * NW + 8 + LCAP + 64;
 };
 
 constexpr float kDqBits = 30.f;
@@ -60,7 +60,8 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
     uint32_t* offs = cur + C::RANGE + 1;
     uint32_t* wsum = offs + C::RANGE + 1;
     int* next = reinterpret_cast<int*>(wsum + C::NW);
-    uint8_t* rows8 = reinterpret_cast<uint8_t*>(next + 1);
+    int* take = next + 1;                                 // next unit of the list to hand to a wave
+    uint8_t* rows8 = reinterpret_cast<uint8_t*>(take + 1);
     uint16_t* ulist = reinterpret_cast<uint16_t*>(cur);   // non-empty blocks of a range (over the builder's scratch)
 
     const int tid = threadIdx.x, lane = tid % kWave;
@@ -205,11 +206,14 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
         __syncthreads();
         build_block_lists<C::TILE, C::NT>(idx + (sbase + t0) * k, t0, rows_here, k, B, lo, hi, cur, offs,
                                           rows8, C::LCAP, wsum, tid);
+        if (tid == 0) *take = 0;
         list_nonempty<C::NT>(offs, hi - lo, ulist, next, wsum, tid);
         const int nblk = *next;
 
-        // waves take the listed blocks round robin; one unit = one 32-key group of a block
-        for (int e = wave; e < nblk; e += C::NW) {
+        // waves take the listed blocks as they get free; one unit = one 32-key group of a block
+        int e = take_unit(take, lane);
+        while (e < nblk) {
+            const int en = take_unit(take, lane);     // asked for early: its latency hides behind this unit
             const int j = __builtin_amdgcn_readfirstlane((int)ulist[e]);
             const int beg = __builtin_amdgcn_readfirstlane((int)offs[j]);
             const int end = min(__builtin_amdgcn_readfirstlane((int)offs[j + 1]), (int)C::LCAP);
@@ -245,6 +249,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
                     accumulate(row, x, kt, valid);
                 }
             }
+            e = en;
         }
     }
     __syncthreads();

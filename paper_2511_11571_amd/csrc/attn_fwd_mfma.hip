@@ -55,7 +55,7 @@ struct FwdCfg {
     static constexpr bool PREV = D == 64;              // ... and the V operands too (registers allow)
     static constexpr bool SPIPE = D == 64 ? MOBA_FWD_SPIPE64 : true; // Q gather one sub-tile ahead
     static constexpr size_t LDS = (size_t)TILE * QSTRIDE + 4 * TILE * OSTRIDE + 4 * 2 * TILE +
-                                  4 * 2 * (RANGE + 1) + 4 * NW + 4 + LCAP + 64;
+                                  4 * 2 * (RANGE + 1) + 4 * NW + 8 + LCAP + 64;
 };
 
 // ---- per-channel scale of V and the slot-ordered transposed copy (see mfma.h) -----------
@@ -223,7 +223,8 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
     uint32_t* offs = cur + C::RANGE + 1;
     uint32_t* wsum = offs + C::RANGE + 1;
     int* next = reinterpret_cast<int*>(wsum + C::NW);
-    uint8_t* rows8 = reinterpret_cast<uint8_t*>(next + 1);
+    int* take = next + 1;                                 // next unit of the list to hand to a wave
+    uint8_t* rows8 = reinterpret_cast<uint8_t*>(take + 1);
     uint16_t* ulist = reinterpret_cast<uint16_t*>(cur);   // non-empty blocks of a range (over the builder's scratch)
 
     const int tid = threadIdx.x, lane = tid % kWave;
@@ -360,6 +361,7 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                                                   cur, offs, rows8, C::LCAP, wsum, tid);
                 // Non-empty blocks of this range, ascending: the workgroups of an XCD then walk
                 // K and V in the same order and find each other's blocks in the L2.
+                if (tid == 0) *take = 0;
                 list_nonempty<C::NT>(offs, hi - lo, ulist, next, wsum, tid);
             }
             const int nblk = *next;
@@ -468,18 +470,23 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                     e = en; gi = gn;
                 }
             } else {
-                for (int e = wave; e < nblk; e += C::NW)
+                int e = take_unit(take, lane);
+                while (e < nblk) {
+                    const int en = take_unit(take, lane);     // asked for early: its latency hides behind this unit
                     for (int gi = 0; gi < NG; ++gi) {
                         Frag ka[2][C::KS], va[C::MT];
                         int beg, end;
                         const int kap = load_unit(e, gi, ka, va, beg, end);
                         run_unit(kap, beg, end, ka, va);
                     }
+                    e = en;
+                }
             }
         }
         __syncthreads();
         if (pass == 0) {      // keys -> reference values minus F (log2 units), in place
             for (int i = tid; i < C::TILE; i += C::NT) mkey[i] = __float_as_int(key_float(mkey[i]) - Fbits);
+            if (tid == 0) *take = 0;
             __syncthreads();
         }
     }

@@ -139,6 +139,16 @@ __device__ __forceinline__ void list_nonempty(const uint32_t* offs, int nb, uint
     __syncthreads();
 }
 
+// Next entry of a work list shared by the waves of a workgroup (the same value in all lanes).
+// Units differ in length and the memory system does not serve all waves alike, so a static
+// deal leaves waves idle at the barrier that ends the list.
+__device__ __forceinline__ int take_unit(int* counter, int lane)
+{
+    int e = 0;
+    if (lane == 0) e = atomicAdd(counter, 1);
+    return __builtin_amdgcn_readfirstlane(e);
+}
+
 // ---- per-tile block lists in LDS --------------------------------------------------------
 // For a tile of TILE consecutive queries and the key blocks [lo, hi): a counting sort of the
 // tile's (row, kept block) pairs by block.  Afterwards offs[j - lo] .. offs[j - lo + 1] is the
