@@ -25,6 +25,12 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3      # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch (fetch + write) of a kernel, from the rocprofv3 --pmc runs summarised
+# under profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a
+# plain copy kernel of known size).  Keyed by (benchmark configuration, kernel); not measured
+# for the others.
+MEASURED_TRAFFIC = {}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -151,11 +157,13 @@ def main():
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)]
           for _ in range(a.steps)]
     torch.cuda.synchronize()
+    moba.profile_begin()          # HIP events around every main kernel, on its launch stream
     t0 = time.perf_counter()
     for s in range(a.steps):
         step(ev[s])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    kernel_ms = {name: (tot / max(n, 1)) for name, (tot, n) in moba.profile_end().items() if n}
     ms_step = 1e3 * wall / a.steps
     stage_ms = {name: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(a.steps)) / a.steps
                 for i, name in enumerate(stages)}
@@ -165,19 +173,37 @@ def main():
     bwd_flop = 10.0 * w.d * pairs if w.backward else 0.0
     value = (fwd_flop + bwd_flop) / (ms_step * 1e-3) / 1e12
 
-    # Roofline of the dominant kernel.  The dK/dV kernel executes 4 of the backward's
-    # matrix products (S, dP, dV, dK = 8d flop per pair), the dQ kernel 3 (S, dP, dQ = 6d),
-    # the forward 2 (4d).
-    kernel_flop = {"forward": fwd_flop, "bwd_dq": 6.0 * w.d * pairs, "bwd_dkdv": 8.0 * w.d * pairs}
-    dom = max((s for s in stages if s in kernel_flop), key=lambda s: stage_ms[s])
-    mfma = (w.dtype == "bf16") and not a.reference_kernels
-    peak = PEAK_BF16_TFLOPS if mfma else PEAK_FP32_TFLOPS
-    ach = kernel_flop[dom] / (stage_ms[dom] * 1e-3) / 1e12
-    roofline = {"kernel": dom, "bound": "mfma" if mfma else "alu", "achieved": ach, "peak": peak,
-                "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
-                "ms_per_launch": stage_ms[dom], "flop_per_launch": kernel_flop[dom]}
-    # HBM-bound stages, for the record: algorithmic bytes / measured time
+    # Roofline of the dominant kernel = the one with the longest launch among the four main
+    # kernels, timed by the library with HIP events around each launch (kernel_ms; the stage
+    # times above also hold the small preparation kernels of a stage).  The dK/dV kernel
+    # executes 4 of the backward's matrix products (S, dP, dV, dK = 8d flop per attended pair),
+    # the dQ kernel 3 (S, dP, dQ = 6d), the forward 2 (4d): bf16 MFMA work.  The gate/top-k
+    # kernel is priced against HBM: it has to read Q and the centroids and write the routing.
     es = 2 if w.dtype == "bf16" else 4
+    mfma = (w.dtype == "bf16") and not a.reference_kernels
+    work = {"forward": ("flop", fwd_flop), "bwd_dq": ("flop", 6.0 * w.d * pairs),
+            "bwd_dkdv": ("flop", 8.0 * w.d * pairs),
+            "topk": ("byte", float(w.bh * (w.N * w.d * es + w.n * w.d * 4 + w.N * w.k * 4)))}
+    timed = {k: v for k, v in kernel_ms.items() if k in work and (w.backward or not k.startswith("bwd"))}
+    if timed:
+        dom = max(timed, key=timed.get)
+        dom_ms = timed[dom]
+    else:                               # plain kernels: no event hooks, fall back to stage times
+        dom = max((s for s in stages if s in work), key=lambda s: stage_ms[s])
+        dom_ms = stage_ms[dom]
+    kind, amount = work[dom]
+    if kind == "flop":
+        peak = PEAK_BF16_TFLOPS if mfma else PEAK_FP32_TFLOPS
+        ach = amount / (dom_ms * 1e-3) / 1e12
+        roofline = {"kernel": dom, "bound": "mfma" if mfma else "alu", "achieved": ach, "peak": peak,
+                    "unit": "TFLOP/s", "frac": ach / peak, "flop_per_launch": amount}
+    else:
+        ach = amount / (dom_ms * 1e-3) / 1e9
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "bytes_per_launch": amount}
+    roofline["ms_per_launch"] = dom_ms
+    roofline["traffic"] = MEASURED_TRAFFIC.get((a.config, dom)) if not a.reference_kernels else None
+    # HBM-bound stages, for the record: algorithmic bytes / measured time
     cent_bytes = w.bh * (w.N * w.d * es * (2 if w.conv_width else 1) + w.n * w.d * 4)
     topk_bytes = w.bh * (w.N * w.d * es + w.n * w.d * 4 + w.N * w.k * 4 + R * 4 + (w.n + 1) * 4)
     hbm = {"centroids_GBs": cent_bytes / (stage_ms["centroids"] * 1e-3) / 1e9,
@@ -196,6 +222,7 @@ def main():
             "kernels": "plain" if a.reference_kernels else "default",
             "attended_pairs": pairs, "fwd_gflop": fwd_flop / 1e9, "bwd_gflop": bwd_flop / 1e9},
         "stage_ms": stage_ms,
+        "kernel_ms": kernel_ms,
         "roofline": roofline,
         "hbm_stages": hbm,
     }

@@ -165,6 +165,24 @@ const char* moba_strerror(int status);
 /* hipError_t value of the most recent failed HIP call on the calling thread (0 if none). */
 int moba_last_hip_error(void);
 
+/*
+ * Kernel timing for benchmarks (no part of the method).  Between moba_profile_begin and
+ * moba_profile_end every launch of one of the main kernels is bracketed by a pair of HIP
+ * events on the stream it is launched on.  moba_profile_end waits for those events and adds,
+ * per kernel, the elapsed milliseconds to ms[kernel] and the launches to calls[kernel] (both
+ * host arrays of MOBA_PROFILE_KERNELS entries, overwritten), then drops the events.  At most
+ * 4096 launches are recorded per session; further ones go untimed.  Not thread-safe.
+ */
+enum {
+    MOBA_PROFILE_TOPK = 0,    /* gate scores + top-k selection                    */
+    MOBA_PROFILE_FORWARD = 1, /* forward attention tile kernel                    */
+    MOBA_PROFILE_DQ = 2,      /* backward dQ tile kernel                          */
+    MOBA_PROFILE_DKDV = 3,    /* backward dK / dV kernel                          */
+    MOBA_PROFILE_KERNELS = 4
+};
+int moba_profile_begin(void);
+int moba_profile_end(float* ms, int32_t* calls);
+
 #ifdef __cplusplus
 }
 #endif

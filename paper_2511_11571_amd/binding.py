@@ -73,7 +73,8 @@ def lib():
         L.moba_strerror.argtypes = [ctypes.c_int]
         L.moba_last_hip_error.restype = ctypes.c_int
         for name in ("moba_routes_per_slice", "moba_workspace_bytes", "moba_centroids", "moba_topk",
-                     "moba_build_lists", "moba_forward", "moba_backward", "moba_backward_parts"):
+                     "moba_build_lists", "moba_forward", "moba_backward", "moba_backward_parts",
+                     "moba_profile_begin", "moba_profile_end"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -201,3 +202,19 @@ def backward(shape: Shape, Q, K_eff, V, O, lse, dO, idx, lists, ws=None, out=Non
                                          _p(dK), _p(dV), _p(ws), ctypes.c_size_t(ws.numel()), _stream(),
                                          ctypes.c_uint32(parts)), "moba_backward_parts")
     return dQ, dK, dV
+
+
+PROFILE_KERNELS = ("topk", "forward", "bwd_dq", "bwd_dkdv")
+
+
+def profile_begin():
+    """Starts timing the main kernels with HIP events on their launch stream."""
+    _check(lib().moba_profile_begin(), "moba_profile_begin")
+
+
+def profile_end():
+    """Ends the timing session: {kernel: (total milliseconds, launches)}."""
+    ms = (ctypes.c_float * len(PROFILE_KERNELS))()
+    calls = (ctypes.c_int32 * len(PROFILE_KERNELS))()
+    _check(lib().moba_profile_end(ms, calls), "moba_profile_end")
+    return {name: (float(ms[i]), int(calls[i])) for i, name in enumerate(PROFILE_KERNELS)}

@@ -268,6 +268,7 @@ static hipError_t dkdv_launch(const Dims& s, const void* Q, const void* K, const
     hipError_t e = hipFuncSetAttribute((const void*)dkdv_mfma_kernel<D>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
     if (e != hipSuccess) return e;
+    ProfileScope timing(MOBA_PROFILE_DKDV, st);
     hipLaunchKernelGGL((dkdv_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, gps)), dim3(C::NT), C::LDS, st,
                        (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, Dv,
                        off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, gps, s.bh);

@@ -278,6 +278,7 @@ static hipError_t dq_launch(const Dims& s, const void* Q, const void* Ka, const 
     hipError_t e = hipFuncSetAttribute((const void*)dq_mfma_kernel<D>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
     if (e != hipSuccess) return e;
+    ProfileScope timing(MOBA_PROFILE_DQ, st);
     hipLaunchKernelGGL((dq_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, ntiles)), dim3(C::NT), C::LDS, st,
                        (const bf16_t*)Q, (const bf16_t*)Ka, (const bf16_t*)Va, (const bf16_t*)Kt, kmax,
                        vmax, (const bf16_t*)dO, lse, Dv, idx, (bf16_t*)dQ, s.N, s.B, s.k, s.scale,

@@ -516,6 +516,7 @@ static hipError_t fwd_launch(const Dims& s, const void* Q, const void* K, const 
     hipError_t e = hipFuncSetAttribute((const void*)forward_mfma_kernel<D>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
     if (e != hipSuccess) return e;
+    ProfileScope timing(MOBA_PROFILE_FORWARD, st);
     hipLaunchKernelGGL((forward_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, ntiles)), dim3(C::NT), C::LDS,
                        st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)Vt, vmax, idx,
                        (bf16_t*)O, lse, s.N, s.B, s.k, s.scale, ntiles, s.bh);

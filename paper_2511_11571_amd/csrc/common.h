@@ -127,6 +127,15 @@ struct Dims {
     int nchunk;         // ceil(N / kChunkQ)
 };
 
+// kernel timing hooks (see moba_profile_begin): no-ops unless a session is open
+void profile_mark(int kernel, bool start, hipStream_t st);
+struct ProfileScope {
+    int kernel;
+    hipStream_t st;
+    ProfileScope(int k, hipStream_t s) : kernel(k), st(s) { profile_mark(kernel, true, st); }
+    ~ProfileScope() { profile_mark(kernel, false, st); }
+};
+
 // launchers (one translation unit each); every one returns a hipError_t
 hipError_t launch_centroids(const Dims& s, const void* K, const float* w, void* Keff,
                             float* cent, hipStream_t st);

@@ -71,7 +71,67 @@ size_t bwd_ws_bytes(const Dims& d)
 
 }  // namespace
 
+// ---- kernel timing (benchmarks only) -------------------------------------------------------
+namespace {
+struct ProfileRec { int kernel; hipEvent_t a, b; };
+constexpr int kProfileMax = 4096;
+bool g_profile_on = false;
+int g_profile_n = 0;
+ProfileRec g_profile[kProfileMax];
+}  // namespace
+
+namespace moba {
+void profile_mark(int kernel, bool start, hipStream_t st)
+{
+    if (!g_profile_on) return;
+    if (start) {
+        if (g_profile_n >= kProfileMax) return;
+        ProfileRec& r = g_profile[g_profile_n];
+        r.kernel = kernel;
+        if (hipEventCreate(&r.a) != hipSuccess) return;
+        if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
+        (void)hipEventRecord(r.a, st);
+        ++g_profile_n;
+    } else if (g_profile_n > 0 && g_profile[g_profile_n - 1].kernel == kernel) {
+        (void)hipEventRecord(g_profile[g_profile_n - 1].b, st);
+    }
+}
+
+}  // namespace moba
+
 extern "C" {
+
+int moba_profile_begin(void)
+{
+    if (g_profile_on) return MOBA_EINVAL;
+    g_profile_n = 0;
+    g_profile_on = true;
+    return MOBA_OK;
+}
+
+int moba_profile_end(float* ms, int32_t* calls)
+{
+    if (!g_profile_on || !ms || !calls) return MOBA_EINVAL;
+    g_profile_on = false;
+    for (int i = 0; i < MOBA_PROFILE_KERNELS; ++i) { ms[i] = 0.f; calls[i] = 0; }
+    int status = MOBA_OK;
+    for (int i = 0; i < g_profile_n; ++i) {
+        ProfileRec& r = g_profile[i];
+        float t = 0.f;
+        hipError_t e = hipEventSynchronize(r.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, r.a, r.b);
+        if (e == hipSuccess && r.kernel >= 0 && r.kernel < MOBA_PROFILE_KERNELS) {
+            ms[r.kernel] += t;
+            ++calls[r.kernel];
+        } else if (e != hipSuccess) {
+            status = MOBA_EHIP;
+        }
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    g_profile_n = 0;
+    return status;
+}
 
 const char* moba_strerror(int status)
 {

@@ -4,8 +4,9 @@
 // Scores must be fp32-accurate (the routing is compared with a 1e-4 score gap), so the
 // fp32 centroids are split into three bf16 terms hi + mid + lo (24 mantissa bits); the
 // queries are bf16 already, every product is exact in fp32 and only the fp32 accumulation
-// rounds.  One wave owns 64 consecutive queries and sweeps the centroid tiles of their
-// past blocks: 16 blocks x 64 queries per step, 3 terms x d/32 MFMAs per 16 queries.
+// rounds.  A workgroup of two waves owns 64 consecutive queries; the waves take alternate
+// centroid tiles of the queries' past blocks: 16 blocks x 64 queries per step, 3 terms x d/32
+// MFMAs per 16 queries.
 //
 // Selection replaces the paper's per-row insertion sort (k = 64 of ~1000 candidates makes
 // insertion far too long) by an exact radix search that recomputes the cheap scores instead
@@ -61,11 +62,12 @@ __device__ __forceinline__ float key_score(uint32_t key, float none)
     return (bits & 0x7fffffffu) > 0x7f800000u ? none : __uint_as_float(bits);
 }
 
-// One sweep over the centroid tiles of a 64-query strip.  f(qt, sc, j0): sc[i] is the score of
+// One wave's share (tiles tile_lo, tile_lo + step, ...) of a sweep over the centroid tiles of a
+// 64-query strip.  f(qt, sc, j0): sc[i] is the score of
 // query 16*qt + m16 against block j0 + i (j0 = 16*tile + 4*g).
 template <int D, typename F>
 __device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int tile_lo, int tile_hi,
-                                            const Frag (&qb)[4][D / 32], int lane, int g, F f)
+                                            int step, const Frag (&qb)[4][D / 32], int lane, int g, F f)
 {
     constexpr int KS = D / 32;
     auto load = [&](int jt, Frag (&a)[3][KS]) {
@@ -96,28 +98,30 @@ __device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int ti
     int jt = tile_lo;
     if (jt < tile_hi) load(jt, a0);
     while (jt < tile_hi) {
-        if (jt + 1 < tile_hi) load(jt + 1, a1);
+        if (jt + step < tile_hi) load(jt + step, a1);
         run(jt, a0);
-        if (++jt >= tile_hi) break;
-        if (jt + 1 < tile_hi) load(jt + 1, a0);
+        jt += step;
+        if (jt >= tile_hi) break;
+        if (jt + step < tile_hi) load(jt + step, a0);
         run(jt, a1);
-        ++jt;
+        jt += step;
     }
 }
 
+constexpr int kTopkWaves = 2;             // waves per 64-query strip (= per workgroup)
+
 template <int D>
-__global__ __launch_bounds__(256) void topk_mfma_kernel(
+__global__ __launch_bounds__(kTopkWaves * kWave) void topk_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ c3, int ntile_all,
-    int32_t* __restrict__ idx, int N, int B, int n, int k, int strips_per_slice,
-    int64_t total_strips, int Wn)
+    int32_t* __restrict__ idx, int N, int B, int n, int k, int strips_per_slice, int Wn)
 {
     extern __shared__ uint32_t smem[];
     constexpr int KS = D / 32;
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int m16 = lane & 15, g = lane >> 4;
-    const int64_t strip = (int64_t)blockIdx.x * 4 + wave;
-    if (strip >= total_strips) return;             // waves are independent: no workgroup barrier below
-    uint32_t* hist = smem + (size_t)wave * (64 * kHistStride + 6 * 64 + 64 * Wn);
+    const int strip = blockIdx.x;
+    uint32_t* hist = smem;
     uint32_t* st_lo = hist + 64 * kHistStride;
     uint32_t* st_sh = st_lo + 64;
     uint32_t* st_need = st_sh + 64;
@@ -126,13 +130,13 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
     uint32_t* st_nb = st_past + 64;                // bins of the current interval (64, fewer at the end)
     uint32_t* selm = st_nb + 64;                   // [64][Wn] kept-block bits
 
-    const int s = (int)(strip / strips_per_slice);
-    const int t0 = (int)(strip % strips_per_slice) * 64;
+    const int s = strip / strips_per_slice;
+    const int t0 = (strip % strips_per_slice) * 64;
     const int rows_here = min(64, N - t0);
     const char* c3s = reinterpret_cast<const char*>(c3) + (int64_t)s * ntile_all * (3 * KS * 1024);
     int32_t* out = idx + ((int64_t)s * N + t0) * k;
 
-    {   // lane = query: initial state
+    if (wave == 0) {   // lane = query: initial state
         const int past = lane < rows_here ? (t0 + lane) / B : 0;
         st_past[lane] = past;
         st_lo[lane] = 0u;
@@ -141,7 +145,7 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
         st_need[lane] = (uint32_t)min(k, past);
         st_state[lane] = past <= k ? 1u : 0u;      // few candidates: keep them all (every key >= 0)
     }
-    for (int i = lane; i < 64 * Wn; i += kWave) selm[i] = 0u;
+    for (int i = tid; i < 64 * Wn; i += kTopkWaves * kWave) selm[i] = 0u;
     const int pmax = (t0 + rows_here - 1) / B;
     const int ntile = (pmax + 15) / 16;
 
@@ -153,24 +157,26 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
             const int64_t r = min(t0 + 16 * qt + m16, N - 1);
             qb[qt][ks].q = *reinterpret_cast<const uint4*>(Q + ((int64_t)s * N + r) * D + 8 * g + 32 * ks);
         }
-    __builtin_amdgcn_wave_barrier();
+    __syncthreads();
 
     // Interior tiles hold only blocks that are past blocks of every query of the strip; the
-    // tail tiles need the per-query causal test.
+    // tail tiles need the per-query causal test.  The waves of the strip take alternate tiles.
     const int ntile_int = min(ntile, (t0 / B) / 16);
     auto sweep = [&](int tlo, int thi, auto f) {
         const int mid = min(max(ntile_int, tlo), thi);
-        sweep_tiles<D>(c3s, tlo, mid, qb, lane, g,
+        sweep_tiles<D>(c3s, tlo + wave, mid, kTopkWaves, qb, lane, g,
                        [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::false_type()); });
-        sweep_tiles<D>(c3s, mid, thi, qb, lane, g,
+        // first tail tile of this wave: same parity as its interior tiles
+        const int tail0 = mid + ((wave - (mid - tlo)) & (kTopkWaves - 1));
+        sweep_tiles<D>(c3s, tail0, thi, kTopkWaves, qb, lane, g,
                        [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::true_type()); });
     };
 
     // ---- radix search for the k-th largest key of every undecided query.  Membership of a
     // score in the query's current key interval is tested on the float itself (two compares);
     // only members pay for the key, the bin and the atomic.
-    while (__any(st_state[lane] == 0u)) {
-        for (int i = 0; i < kHistWords; ++i) hist[lane * kHistStride + i] = 0u;
+    while (__syncthreads_or(st_state[lane] == 0u)) {
+        for (int i = tid; i < 64 * kHistStride; i += kTopkWaves * kWave) hist[i] = 0u;
         uint32_t lo4[4], sh4[4], past4[4];
         float flo4[4], fhi4[4];
         bool act4[4];
@@ -183,7 +189,7 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
             const uint64_t hi = (uint64_t)lo4[qt] + ((uint64_t)st_nb[q] << sh4[qt]);
             fhi4[qt] = hi > 0xff800000ull ? NAN : key_score((uint32_t)hi, NAN);   // NaN: no upper end
         }
-        __builtin_amdgcn_wave_barrier();
+        __syncthreads();
         sweep(0, ntile, [&](int qt, const f32x4_t& sc, int j0, auto tail) {
             if (!act4[qt]) return;
             uint32_t* row = hist + (16 * qt + m16) * kHistStride;
@@ -197,8 +203,8 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
                 }
             }
         });
-        __builtin_amdgcn_wave_barrier();
-        if (st_state[lane] == 0u) {                  // lane = query: walk the bins from the top
+        __syncthreads();
+        if (wave == 0 && st_state[lane] == 0u) {     // lane = query: walk the bins from the top
             const uint32_t need = st_need[lane], lo = st_lo[lane], sh = st_sh[lane];
             uint32_t cum = 0, c = 0;
             int b = 63;
@@ -216,7 +222,7 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
             else if (sh >= 6u) { st_sh[lane] = sh - 6u; st_nb[lane] = 64u; }   // 64 bins again
             else { st_sh[lane] = 0u; st_nb[lane] = 1u << sh; }               // last step: one key per bin
         }
-        __builtin_amdgcn_wave_barrier();
+        __syncthreads();
     }
 
     // ---- mark the kept blocks: score >= threshold (state 1) or > threshold plus ties (state 2)
@@ -241,12 +247,11 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
             }
             if (bits) atomicOr(&selm[(16 * qt + m16) * Wn + (j0 >> 5)], bits << (j0 & 31));
         });
-        __builtin_amdgcn_wave_barrier();
         // ties at the threshold: the lowest block indices among the equal scores, 1024 blocks at a time
-        if (__any(st_state[lane] == 2u)) {
+        if (__syncthreads_or(st_state[lane] == 2u)) {
             for (int r0 = 0; r0 < 16 * ntile; r0 += 1024) {
-                for (int i = 0; i < kHistWords; ++i) hist[lane * kHistStride + i] = 0u;
-                __builtin_amdgcn_wave_barrier();
+                for (int i = tid; i < 64 * kHistStride; i += kTopkWaves * kWave) hist[i] = 0u;
+                __syncthreads();
                 sweep(r0 / 16, min(ntile, (r0 + 1024) / 16), [&](int qt, const f32x4_t& sc, int j0, auto tail) {
                     if (!strict4[qt]) return;
                     uint32_t bits = 0;
@@ -255,8 +260,8 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
                         if ((uint32_t)(j0 + i) < past4[qt] && sc[i] == thr4[qt]) bits |= 1u << i;
                     if (bits) atomicOr(&hist[(16 * qt + m16) * kHistStride + ((j0 - r0) >> 5)], bits << (j0 & 31));
                 });
-                __builtin_amdgcn_wave_barrier();
-                if (st_state[lane] == 2u) {
+                __syncthreads();
+                if (wave == 0 && st_state[lane] == 2u) {
                     uint32_t need = st_need[lane];
                     for (int w = 0; w < kHistWords && need > 0; ++w) {
                         uint32_t word = hist[lane * kHistStride + w];
@@ -269,13 +274,13 @@ __global__ __launch_bounds__(256) void topk_mfma_kernel(
                     }
                     st_need[lane] = need;
                 }
-                __builtin_amdgcn_wave_barrier();
+                __syncthreads();
             }
         }
     }
 
     // ---- write the rows (lane = query): kept blocks ascending, then -1
-    if (lane < rows_here) {
+    if (wave == 0 && lane < rows_here) {
         int32_t* row = out + (int64_t)lane * k;
         int pos = 0;
         for (int w = 0; w < Wn; ++w) {
@@ -309,12 +314,13 @@ static hipError_t topk_launch(const Dims& s, const void* Q, const bf16_t* c3, in
     const int sps = (s.N + 63) / 64;
     const int64_t strips = (int64_t)sps * s.bh;
     const int Wn = ((s.n + 31) / 32) | 1;      // words per bit row, odd for the same reason
-    const size_t lds = sizeof(uint32_t) * 4 * (size_t)(64 * kHistStride + 6 * 64 + 64 * Wn);
+    const size_t lds = sizeof(uint32_t) * (size_t)(64 * kHistStride + 6 * 64 + 64 * Wn);
     hipError_t e = hipFuncSetAttribute((const void*)topk_mfma_kernel<D>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((topk_mfma_kernel<D>), dim3((unsigned)((strips + 3) / 4)), dim3(256), lds, st,
-                       (const bf16_t*)Q, c3, (s.n + 15) / 16, idx, s.N, s.B, s.n, s.k, sps, strips, Wn);
+    ProfileScope timing(MOBA_PROFILE_TOPK, st);
+    hipLaunchKernelGGL((topk_mfma_kernel<D>), dim3((unsigned)strips), dim3(kTopkWaves * kWave), lds, st,
+                       (const bf16_t*)Q, c3, (s.n + 15) / 16, idx, s.N, s.B, s.n, s.k, sps, Wn);
     return hipGetLastError();
 }
 
