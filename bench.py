@@ -29,7 +29,9 @@ PEAK_HBM_GBS = 8000.0
 # under profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a
 # plain copy kernel of known size).  Keyed by (benchmark configuration, kernel); not measured
 # for the others.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    (3, "bwd_dkdv"): 2.0 * 766675.4 * 1024 + 1.0 * 131072.0 * 1024,   # profiles/config3_hbm_traffic.txt
+}
 
 
 def parse():
@@ -41,6 +43,9 @@ def parse():
     ap.add_argument("--reference-kernels", action="store_true",
                     help="force the plain (non-MFMA) kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed steps, copy 1 GiB device to device once (a kernel of "
+                         "known HBM traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-max-slices", type=int, default=0,
                     help="cap on the (batch, head) slices of the CPU-baseline sample")
     return ap.parse_args()
@@ -226,6 +231,12 @@ def main():
         "roofline": roofline,
         "hbm_stages": hbm,
     }
+    if a.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, t, max_slices=a.cpu_max_slices)
     print(json.dumps(out))
