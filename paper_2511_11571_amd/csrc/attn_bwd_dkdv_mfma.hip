@@ -122,10 +122,10 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
             gr[i] = *reinterpret_cast<const u32x4_t*>(Gg + o);
         }
         lv = INFINITY;                                // rows past the end of the walk: P = 0
-        dv = 0.f;
+        dv = 0.f;                                     // -D, the start value of the dP product
         if (a0 + (lane & 31) < total) {
             lv = lse[sbase + tl] * kLog2e;
-            dv = Dv[sbase + tl];
+            dv = -Dv[sbase + tl];
         }
     };
     const int stride = 32 * C::NW;
@@ -165,10 +165,11 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
                 qa[ks].q = *reinterpret_cast<const uint4*>(stQ + arow + qt * 16 * C::SB + 64 * ks);
                 ga[ks].q = *reinterpret_cast<const uint4*>(stG + arow + qt * 16 * C::SB + 64 * ks);
             }
+            const f32x4_t nd = *reinterpret_cast<const f32x4_t*>(Ds + 16 * qt + 4 * g);   // -D of the rows
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) {
                 sc[qt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                dp[qt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                dp[qt][nt] = nd;                              // dP - D comes out of the MFMA
 #pragma unroll
                 for (int ks = 0; ks < C::KS; ++ks) {
                     sc[qt][nt] = mfma16(qa[ks], kb[nt][ks], sc[qt][nt]);
@@ -179,12 +180,9 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
         // own queries of this very group are causal: key (16 nt + m16) must not exceed the query
         const bool causal = a0 + 32 > nlist && a0 < nlist + 32;    // the step touches own rows 0..31
         Frag pb[2], sb[2];
-        f32x4_t l4[2], d4[2];
+        f32x4_t l4[2];
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            l4[qt] = *reinterpret_cast<const f32x4_t*>(ls + 16 * qt + 4 * g);
-            d4[qt] = *reinterpret_cast<const f32x4_t*>(Ds + 16 * qt + 4 * g);
-        }
+        for (int qt = 0; qt < 2; ++qt) l4[qt] = *reinterpret_cast<const f32x4_t*>(ls + 16 * qt + 4 * g);
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
             float p[8], d[8];
@@ -198,7 +196,7 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
                         if (a >= 0 && a < 32 && 16 * nt + m16 > a) pv = 0.f;
                     }
                     p[4 * qt + i] = pv;
-                    d[4 * qt + i] = pv * (dp[qt][nt][i] - d4[qt][i]);
+                    d[4 * qt + i] = pv * dp[qt][nt][i];
                 }
             }
 #pragma unroll

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
     unsigned char* Gs = Qs + (size_t)C::TILE * C::ROWB;
     int* acc = reinterpret_cast<int*>(Gs + (size_t)C::TILE * C::ROWB);
     float* pexp = reinterpret_cast<float*>(acc + C::TILE * C::OSTRIDE);   // lse*log2e - 30 + e_t
-    float* Dr = pexp + C::TILE;
+    float* Dr = pexp + C::TILE;                // -D_t
     int* esc = reinterpret_cast<int*>(Dr + C::TILE);
     uint32_t* cur = reinterpret_cast<uint32_t*>(esc + C::TILE);
     uint32_t* offs = cur + C::RANGE + 1;
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
         }
         const int e = max(scale_exponent(__float_as_uint(bound)), -60);   // keeps 2^(30-e) finite
         esc[r] = e;
-        Dr[r] = Dt;
+        Dr[r] = -Dt;                   // start value of the dP product: dP - D comes out of the MFMA
         pexp[r] = L * kLog2e - kDqBits + (float)e;
     }
     __syncthreads();
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
         const int kfirst = NG == 1 ? kown : kown - kown % NG;
         Frag qb[C::KS], gb[C::KS];
         gather(row, qb, gb);
-        const float pe = pexp[row], Dt = Dr[row];
+        const float pe = pexp[row], nD = Dr[row];
         for (int kap = kfirst; kap <= kown; ++kap) {
             const bool own = kap == kown;
             Frag ka[2][C::KS], va[2][C::KS], kt[C::MT];
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
                 sc[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                dp[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                dp[mt] = f32x4_t{nD, nD, nD, nD};
                 if (!own || mt <= st) {
 #pragma unroll
                     for (int ks = 0; ks < C::KS; ++ks) {
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const bool vis = !own || 16 * (e >> 2) + 4 * g + (e & 3) <= 16 * st + m16;
-                x[e] = vis ? fast_exp2(fmaf(sc[e >> 2][e & 3], c2, -pe)) * (dp[e >> 2][e & 3] - Dt) : 0.f;
+                x[e] = vis ? fast_exp2(fmaf(sc[e >> 2][e & 3], c2, -pe)) * dp[e >> 2][e & 3] : 0.f;
             }
             accumulate(row, x, kt, true);
         }
@@ -230,12 +230,12 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
                     const int row = rows8[c0 + m16] & (C::TILE - 1);
                     Frag qb[C::KS], gb[C::KS];
                     gather(row, qb, gb);
-                    const float pe = pexp[row], Dt = Dr[row];
+                    const float pe = pexp[row], nD = Dr[row];
                     f32x4_t sc[2], dp[2];
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt) {
                         sc[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                        dp[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                        dp[mt] = f32x4_t{nD, nD, nD, nD};
 #pragma unroll
                         for (int ks = 0; ks < C::KS; ++ks) {
                             sc[mt] = mfma16(ka[mt][ks], qb[ks], sc[mt]);
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
                     float x[8];
 #pragma unroll
                     for (int e2 = 0; e2 < 8; ++e2)
-                        x[e2] = fast_exp2(fmaf(sc[e2 >> 2][e2 & 3], c2, -pe)) * (dp[e2 >> 2][e2 & 3] - Dt);
+                        x[e2] = fast_exp2(fmaf(sc[e2 >> 2][e2 & 3], c2, -pe)) * dp[e2 >> 2][e2 & 3];
                     accumulate(row, x, kt, valid);
                 }
             }
