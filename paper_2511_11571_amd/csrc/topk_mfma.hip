@@ -24,6 +24,7 @@ namespace moba {
 
 constexpr int kHistWords = 32;            // 64 bins of 16 bits per query
 constexpr int kHistStride = 33;           // odd row stride: queries land on different LDS banks
+constexpr int kCand = 16;                 // a final bin this small is resolved from a candidate list
 constexpr int kTopkMfmaMaxBlocks = 2048;  // bit row of a query: at most 64 words
 
 // c3 <- the three bf16 terms of the fp32 centroids, in MFMA operand order: the 16 bytes lane
@@ -125,10 +126,12 @@ __global__ __launch_bounds__(kTopkWaves * kWave) void topk_mfma_kernel(
     uint32_t* st_lo = hist + 64 * kHistStride;
     uint32_t* st_sh = st_lo + 64;
     uint32_t* st_need = st_sh + 64;
-    uint32_t* st_state = st_need + 64;             // 0 undecided, 1 keep key >= lo, 2 keep key > lo + ties
+    // 0 undecided, 1 keep key >= lo, 2 keep key > lo + ties at lo, 3 keep key >= lo + 2^sh and
+    // the best `need` of the (at most kCand) keys inside [lo, lo + 2^sh)
+    uint32_t* st_state = st_need + 64;
     uint32_t* st_past = st_state + 64;
-    uint32_t* st_nb = st_past + 64;                // bins of the current interval (64, fewer at the end)
-    uint32_t* selm = st_nb + 64;                   // [64][Wn] kept-block bits
+    uint32_t* st_hi = st_past + 64;                // the current interval is [lo, hi): at most 64 bins of 2^sh keys
+    uint32_t* selm = st_hi + 64;                   // [64][Wn] kept-block bits
 
     const int s = strip / strips_per_slice;
     const int t0 = (strip % strips_per_slice) * 64;
@@ -141,7 +144,7 @@ __global__ __launch_bounds__(kTopkWaves * kWave) void topk_mfma_kernel(
         st_past[lane] = past;
         st_lo[lane] = 0u;
         st_sh[lane] = 26u;
-        st_nb[lane] = 64u;
+        st_hi[lane] = 0xffffffffu;
         st_need[lane] = (uint32_t)min(k, past);
         st_state[lane] = past <= k ? 1u : 0u;      // few candidates: keep them all (every key >= 0)
     }
@@ -172,6 +175,35 @@ __global__ __launch_bounds__(kTopkWaves * kWave) void topk_mfma_kernel(
                        [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::true_type()); });
     };
 
+    // ---- the largest key of every undecided query: the first interval of the search is the
+    // 2^24 keys (two binades of the score) that end there, 64 bins of 2^18 keys
+    if (__syncthreads_or(st_state[lane] == 0u)) {
+        for (int i = tid; i < 64; i += kTopkWaves * kWave) hist[i * kHistStride] = 0u;
+        uint32_t past4[4];
+        float mx4[4];
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt) { past4[qt] = st_past[16 * qt + m16]; mx4[qt] = -INFINITY; }
+        __syncthreads();
+        sweep(0, ntile, [&](int qt, const f32x4_t& sc, int j0, auto tail) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                bool ok = true;
+                if (decltype(tail)::value) ok = (uint32_t)(j0 + i) < past4[qt];
+                if (ok) mx4[qt] = fmaxf(mx4[qt], sc[i]);      // NaN scores are ignored here as in the counts
+            }
+        });
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt) atomicMax(&hist[(16 * qt + m16) * kHistStride], order_key(mx4[qt]));
+        __syncthreads();
+        if (wave == 0 && st_state[lane] == 0u) {
+            const uint32_t kmax = hist[lane * kHistStride];
+            const uint32_t top = kmax == 0xffffffffu ? kmax : kmax + 1u;            // one past the largest key
+            st_lo[lane] = top > (1u << 24) ? top - (1u << 24) : 0u;
+            st_hi[lane] = top;
+            st_sh[lane] = 18u;
+        }
+    }
+
     // ---- radix search for the k-th largest key of every undecided query.  Membership of a
     // score in the query's current key interval is tested on the float itself (two compares);
     // only members pay for the key, the bin and the atomic.
@@ -186,8 +218,8 @@ __global__ __launch_bounds__(kTopkWaves * kWave) void topk_mfma_kernel(
             lo4[qt] = st_lo[q]; sh4[qt] = st_sh[q]; past4[qt] = st_past[q];
             act4[qt] = st_state[q] == 0u;
             flo4[qt] = key_score(lo4[qt], -INFINITY);
-            const uint64_t hi = (uint64_t)lo4[qt] + ((uint64_t)st_nb[q] << sh4[qt]);
-            fhi4[qt] = hi > 0xff800000ull ? NAN : key_score((uint32_t)hi, NAN);   // NaN: no upper end
+            const uint32_t hi = st_hi[q];
+            fhi4[qt] = hi > 0xff800000u ? NAN : key_score(hi, NAN);   // NaN: no upper end
         }
         __syncthreads();
         sweep(0, ntile, [&](int qt, const f32x4_t& sc, int j0, auto tail) {
@@ -205,7 +237,7 @@ __global__ __launch_bounds__(kTopkWaves * kWave) void topk_mfma_kernel(
         });
         __syncthreads();
         if (wave == 0 && st_state[lane] == 0u) {     // lane = query: walk the bins from the top
-            const uint32_t need = st_need[lane], lo = st_lo[lane], sh = st_sh[lane];
+            const uint32_t need = st_need[lane], lo = st_lo[lane], sh = st_sh[lane], hi = st_hi[lane];
             uint32_t cum = 0, c = 0;
             int b = 63;
             for (; b >= 0; --b) {
@@ -213,40 +245,88 @@ __global__ __launch_bounds__(kTopkWaves * kWave) void topk_mfma_kernel(
                 if (cum + c >= need) break;
                 cum += c;
             }
-            b = max(b, 0);
-            const uint32_t need2 = need - cum;
-            st_lo[lane] = lo + ((uint32_t)b << sh);
-            st_need[lane] = need2;
-            if (c == need2) st_state[lane] = 1u;
-            else if (sh == 0u) st_state[lane] = 2u;
-            else if (sh >= 6u) { st_sh[lane] = sh - 6u; st_nb[lane] = 64u; }   // 64 bins again
-            else { st_sh[lane] = 0u; st_nb[lane] = 1u << sh; }               // last step: one key per bin
+            if (b < 0 && lo > 0u) {
+                // fewer keys in the interval than needed (only the first, guessed interval can
+                // miss): keep them all and go on below it, [0, lo) in at most 64 bins
+                const int width = 32 - __clz((int)(lo - 1u));                 // lo > 0 here
+                const uint32_t sh2 = (uint32_t)max(width - 6, 0);
+                st_lo[lane] = 0u;
+                st_need[lane] = need - cum;
+                st_sh[lane] = sh2;
+                st_hi[lane] = lo;
+            } else {
+                b = max(b, 0);                 // (only NaN scores can leave [0, ..) short: keep all)
+                const uint32_t need2 = need - cum;
+                const uint32_t lo2 = lo + ((uint32_t)b << sh);
+                st_lo[lane] = lo2;
+                st_hi[lane] = (uint32_t)min((uint64_t)lo2 + (1ull << sh), (uint64_t)hi);   // the chosen bin
+                st_need[lane] = need2;
+                if (c == need2) st_state[lane] = 1u;
+                else if (sh == 0u) st_state[lane] = 2u;
+                else if (c <= (uint32_t)kCand) st_state[lane] = 3u;
+                else st_sh[lane] = sh >= 6u ? sh - 6u : 0u;                     // cut the bin into 64 again
+            }
         }
         __syncthreads();
     }
 
-    // ---- mark the kept blocks: score >= threshold (state 1) or > threshold plus ties (state 2)
+    // ---- mark the kept blocks: score >= threshold (state 1), > threshold plus ties (state 2), or
+    // above the last bin plus the best of the few scores inside it (state 3; those are collected
+    // as (key, block) pairs in the query's histogram row, whose word 32 counts them)
     {
-        uint32_t past4[4];
-        float thr4[4];
-        bool strict4[4];
+        uint32_t past4[4], st4[4];
+        float thr4[4], top4[4];
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) {
             const int q = 16 * qt + m16;
             past4[qt] = st_past[q];
-            strict4[qt] = st_state[q] == 2u;
+            st4[qt] = st_state[q];
             thr4[qt] = key_score(st_lo[q], -INFINITY);
+            const uint32_t top = st_hi[q];
+            top4[qt] = top > 0xff800000u ? NAN : key_score(top, NAN);               // NaN: nothing above
         }
+        bool strict4[4];
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt) strict4[qt] = st4[qt] == 2u;
         sweep(0, ntile, [&](int qt, const f32x4_t& sc, int j0, auto tail) {
             uint32_t bits = 0;
+            uint32_t* row = hist + (16 * qt + m16) * kHistStride;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                bool keep = strict4[qt] ? sc[i] > thr4[qt] : sc[i] >= thr4[qt];
-                if (decltype(tail)::value) keep = keep && (uint32_t)(j0 + i) < past4[qt];
-                if (keep) bits |= 1u << i;
+                bool ok = true;
+                if (decltype(tail)::value) ok = (uint32_t)(j0 + i) < past4[qt];
+                bool keep;
+                if (st4[qt] == 3u) {
+                    keep = sc[i] >= top4[qt];
+                    if (ok && !keep && sc[i] >= thr4[qt]) {
+                        const uint32_t slot = atomicAdd(&row[32], 1u);
+                        if (slot < (uint32_t)kCand) { row[2 * slot] = order_key(sc[i]); row[2 * slot + 1] = (uint32_t)(j0 + i); }
+                    }
+                } else {
+                    keep = strict4[qt] ? sc[i] > thr4[qt] : sc[i] >= thr4[qt];
+                }
+                if (keep && ok) bits |= 1u << i;
             }
             if (bits) atomicOr(&selm[(16 * qt + m16) * Wn + (j0 >> 5)], bits << (j0 & 31));
         });
+        __syncthreads();
+        if (wave == 0 && st_state[lane] == 3u) {     // lane = query: the best `need` candidates
+            uint32_t* row = hist + lane * kHistStride;
+            const int c = (int)min(row[32], (uint32_t)kCand);
+            uint32_t used = 0;
+            for (uint32_t need = st_need[lane]; need > 0; --need) {
+                int best = -1;
+                uint32_t bkey = 0, bj = 0;
+                for (int i = 0; i < c; ++i) {
+                    if ((used >> i) & 1u) continue;
+                    const uint32_t ky = row[2 * i], jj = row[2 * i + 1];
+                    if (best < 0 || ky > bkey || (ky == bkey && jj < bj)) { best = i; bkey = ky; bj = jj; }
+                }
+                if (best < 0) break;
+                used |= 1u << best;
+                selm[lane * Wn + (bj >> 5)] |= 1u << (bj & 31);
+            }
+        }
         // ties at the threshold: the lowest block indices among the equal scores, 1024 blocks at a time
         if (__syncthreads_or(st_state[lane] == 2u)) {
             for (int r0 = 0; r0 < 16 * ntile; r0 += 1024) {

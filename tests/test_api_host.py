@@ -87,3 +87,15 @@ def test_null_pointers_and_short_workspace(lib):
 def test_binding_raises(lib):
     with pytest.raises(moba.MobaError):
         moba.routes_per_slice(_shape(head_dim=80))
+
+
+def test_profile_session_misuse_is_rejected(lib):
+    import ctypes
+    ms = (ctypes.c_float * 4)()
+    calls = (ctypes.c_int32 * 4)()
+    assert lib.moba_profile_end(ms, calls) == -1            # no session open
+    assert lib.moba_profile_begin() == 0
+    assert lib.moba_profile_begin() == -1                   # already open
+    assert lib.moba_profile_end(None, calls) == -1          # null array: the session stays open
+    assert lib.moba_profile_end(ms, calls) == 0             # no launches: all zero, no HIP call
+    assert list(calls) == [0, 0, 0, 0] and list(ms) == [0.0] * 4

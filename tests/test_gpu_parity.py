@@ -291,3 +291,35 @@ def test_logit_far_above_the_own_block(oracle, flags):
     rQ, rK, rV = oracle.attn_bwd(Q, K, V, ref_idx, dO, w.B, w.scale)
     for a, b in ((dQ, rQ), (dK, rK), (dV, rV)):
         assert parity.rel_l2(np64(a), b) < parity.GRAD_TOL[w.dtype]
+
+
+def test_kernel_timing_session():
+    """moba_profile_begin/_end: one event pair per launch of a main kernel, results unchanged."""
+    w = W("timing", 1, 2, 2048, 64, 32, 8, backward=True, seed=72)
+    d = dev(workloads.generate(w))
+    sh = shape_of(w)
+    Ke, c = moba.centroids(sh, d["K"])
+
+    def chain():
+        idx, lists = moba.topk(sh, d["Q"], c)
+        O, lse = moba.forward(sh, d["Q"], Ke, d["V"], idx, lists)
+        g = moba.backward(sh, d["Q"], Ke, d["V"], O, lse, d["dO"], idx, lists)
+        torch.cuda.synchronize()
+        return [x.clone() for x in (idx, O, lse, *g)]
+
+    plain = chain()
+    moba.profile_begin()
+    timed = [chain() for _ in range(2)]
+    times = moba.profile_end()
+    assert set(times) == {"topk", "forward", "bwd_dq", "bwd_dkdv"}
+    for name, (ms, calls) in times.items():
+        assert calls == 2 and 0.0 < ms < 1e3, (name, ms, calls)
+    for run in timed:
+        for a, b in zip(plain, run):
+            assert torch.equal(a, b)
+    assert moba.profile_end.__doc__ and all(v == (0.0, 0) for v in _closed_session().values())
+
+
+def _closed_session():
+    moba.profile_begin()
+    return moba.profile_end()
