@@ -27,8 +27,6 @@
  *   - R below is the number of (query, kept past block) pairs of one [N, d]
  *     slice, R = B * sum_{c<n} min(c, topk); it depends on the shape only
  *     (moba_routes_per_slice).
- *   - Queries are also grouped in chunks of MOBA_CHUNK_QUERIES consecutive queries;
- *     C = ceil(N / MOBA_CHUNK_QUERIES) is the number of chunks of one slice.
  */
 #ifndef MOBA_H_
 #define MOBA_H_
@@ -39,8 +37,6 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
-
-#define MOBA_CHUNK_QUERIES 128
 
 typedef enum moba_status {
     MOBA_OK = 0,
@@ -94,14 +90,10 @@ int moba_centroids(const moba_shape* shape, const void* K, const float* conv_w,
  *   blk_q     out  [b,h,R] int32: for each key block the ids of the queries that kept
  *                  it, ascending (deterministic); block j's list is
  *                  blk_q[blk_off[j] .. blk_off[j+1])
- *   blk_chunk out  [b,h,C+1,n] int32: blk_chunk[c][j] = number of entries of block j's list
- *                  that belong to query chunks before c (so chunk c's queries sit at
- *                  blk_off[j] + blk_chunk[c][j] .. blk_off[j] + blk_chunk[c+1][j]); row C holds
- *                  the list lengths
  *   ws             at least topk_ws bytes from moba_workspace_bytes
  */
 int moba_topk(const moba_shape* shape, const void* Q, const float* centroids,
-              int32_t* topk_idx, int32_t* blk_off, int32_t* blk_q, int32_t* blk_chunk,
+              int32_t* topk_idx, int32_t* blk_off, int32_t* blk_q,
               void* ws, size_t ws_bytes, void* stream);
 
 /*
@@ -111,21 +103,21 @@ int moba_topk(const moba_shape* shape, const void* Q, const float* centroids,
  * block c must keep exactly min(c, topk) blocks (not checked on the device).
  */
 int moba_build_lists(const moba_shape* shape, const int32_t* topk_idx,
-                     int32_t* blk_off, int32_t* blk_q, int32_t* blk_chunk,
+                     int32_t* blk_off, int32_t* blk_q,
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Attention over the kept blocks plus the causally masked own block
  * (Section 2; Section 4.2 forward algorithm).  Routing is an input.
  *   Q, K_eff, V   in   [b,h,N,d] dtype (K_eff = K when there is no convolution)
- *   topk_idx, blk_off, blk_q, blk_chunk   in   as produced by moba_topk / moba_build_lists
+ *   topk_idx, blk_off, blk_q   in   as produced by moba_topk / moba_build_lists
  *   O         out  [b,h,N,d] dtype
  *   lse       out  [b,h,N] fp32: natural log of sum_u exp(scale * q.k_u) over the kept keys
  *   ws             at least fwd_ws bytes
  */
 int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
                  const int32_t* topk_idx, const int32_t* blk_off, const int32_t* blk_q,
-                 const int32_t* blk_chunk, void* O, float* lse, void* ws, size_t ws_bytes,
+                 void* O, float* lse, void* ws, size_t ws_bytes,
                  void* stream);
 
 /*
@@ -140,7 +132,7 @@ int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, cons
 int moba_backward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
                   const void* O, const float* lse, const void* dO,
                   const int32_t* topk_idx, const int32_t* blk_off, const int32_t* blk_q,
-                  const int32_t* blk_chunk, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes,
+                  void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes,
                   void* stream);
 
 /*
@@ -157,7 +149,7 @@ int moba_backward(const moba_shape* shape, const void* Q, const void* K_eff, con
 int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
                         const void* O, const float* lse, const void* dO,
                         const int32_t* topk_idx, const int32_t* blk_off, const int32_t* blk_q,
-                        const int32_t* blk_chunk, void* dQ, void* dK, void* dV, void* ws,
+                        void* dQ, void* dK, void* dV, void* ws,
                         size_t ws_bytes, void* stream, uint32_t parts);
 
 /* Static, NUL-terminated description of a status code. */

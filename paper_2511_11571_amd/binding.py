@@ -123,47 +123,43 @@ def centroids(shape: Shape, K, conv_w=None, K_eff=None, out=None):
     return (K_eff if K_eff is not None else K), out
 
 
-CHUNK_QUERIES = 128
 
 
 def _list_buffers(shape, like):
     R = routes_per_slice(shape)
     off = torch.empty((shape.batch, shape.heads, shape.n + 1), dtype=torch.int32, device=like.device)
     ql = torch.empty((shape.batch, shape.heads, max(R, 1)), dtype=torch.int32, device=like.device)
-    nchunk = (shape.seqlen + CHUNK_QUERIES - 1) // CHUNK_QUERIES
-    chunk = torch.empty((shape.batch, shape.heads, nchunk + 1, shape.n), dtype=torch.int32,
-                        device=like.device)
-    return off, (ql[..., :R] if R > 0 else ql[..., :0]), chunk
+    return off, (ql[..., :R] if R > 0 else ql[..., :0])
 
 
 def topk(shape: Shape, Q, cent, ws=None):
-    """-> (topk_idx [b,h,N,k] int32, lists) with lists = (blk_off [b,h,n+1], blk_q [b,h,R],
-    blk_chunk [b,h,C+1,n]), all int32."""
+    """-> (topk_idx [b,h,N,k] int32, lists) with lists = (blk_off [b,h,n+1], blk_q [b,h,R]),
+    all int32."""
     assert Q.is_contiguous() and cent.is_contiguous()
     idx = torch.empty((shape.batch, shape.heads, shape.seqlen, shape.topk), dtype=torch.int32,
                       device=Q.device)
-    off, ql, chunk = _list_buffers(shape, Q)
+    off, ql = _list_buffers(shape, Q)
     if ws is None:
         ws = _ws(workspace_bytes(shape)[0], Q)
     _check(lib().moba_topk(ctypes.byref(shape.c()), _p(Q), _p(cent), _p(idx), _p(off), _p(ql),
-                           _p(chunk), _p(ws), ctypes.c_size_t(ws.numel()), _stream()), "moba_topk")
-    return idx, (off, ql, chunk)
+                           _p(ws), ctypes.c_size_t(ws.numel()), _stream()), "moba_topk")
+    return idx, (off, ql)
 
 
 def build_lists(shape: Shape, idx, ws=None):
-    """-> lists = (blk_off, blk_q, blk_chunk) for a routing given by the caller."""
+    """-> lists = (blk_off, blk_q) for a routing given by the caller."""
     assert idx.is_contiguous() and idx.dtype == torch.int32
-    off, ql, chunk = _list_buffers(shape, idx)
+    off, ql = _list_buffers(shape, idx)
     if ws is None:
         ws = _ws(workspace_bytes(shape)[0], idx)
-    _check(lib().moba_build_lists(ctypes.byref(shape.c()), _p(idx), _p(off), _p(ql), _p(chunk),
+    _check(lib().moba_build_lists(ctypes.byref(shape.c()), _p(idx), _p(off), _p(ql),
                                   _p(ws), ctypes.c_size_t(ws.numel()), _stream()), "moba_build_lists")
-    return off, ql, chunk
+    return off, ql
 
 
 def forward(shape: Shape, Q, K_eff, V, idx, lists, ws=None, O=None, lse=None):
     """-> (O [b,h,N,d], lse [b,h,N] fp32).  ``lists`` as returned by topk / build_lists."""
-    off, ql, chunk = lists
+    off, ql = lists
     for t in (Q, K_eff, V):
         assert t.is_contiguous() and t.dtype == shape.torch_dtype
     if O is None:
@@ -173,7 +169,7 @@ def forward(shape: Shape, Q, K_eff, V, idx, lists, ws=None, O=None, lse=None):
     if ws is None:
         ws = _ws(workspace_bytes(shape)[1], Q)
     _check(lib().moba_forward(ctypes.byref(shape.c()), _p(Q), _p(K_eff), _p(V), _p(idx), _p(off),
-                              _p(ql), _p(chunk), _p(O), _p(lse), _p(ws), ctypes.c_size_t(ws.numel()),
+                              _p(ql), _p(O), _p(lse), _p(ws), ctypes.c_size_t(ws.numel()),
                               _stream()),
            "moba_forward")
     return O, lse
@@ -185,7 +181,7 @@ BWD_PREPROCESS, BWD_DQ, BWD_DKDV, BWD_ALL = 1, 2, 4, 7
 def backward(shape: Shape, Q, K_eff, V, O, lse, dO, idx, lists, ws=None, out=None, parts=None):
     """-> (dQ, dK, dV), each [b,h,N,d].  ``parts`` (a BWD_* bit set) runs only some of the
     backward's kernels through moba_backward_parts."""
-    off, ql, chunk = lists
+    off, ql = lists
     for t in (Q, K_eff, V, O, dO):
         assert t.is_contiguous() and t.dtype == shape.torch_dtype
     dQ, dK, dV = out if out is not None else (torch.empty_like(Q), torch.empty_like(Q),
@@ -194,11 +190,11 @@ def backward(shape: Shape, Q, K_eff, V, O, lse, dO, idx, lists, ws=None, out=Non
         ws = _ws(workspace_bytes(shape)[2], Q)
     if parts is None:
         _check(lib().moba_backward(ctypes.byref(shape.c()), _p(Q), _p(K_eff), _p(V), _p(O), _p(lse),
-                                   _p(dO), _p(idx), _p(off), _p(ql), _p(chunk), _p(dQ), _p(dK), _p(dV),
+                                   _p(dO), _p(idx), _p(off), _p(ql), _p(dQ), _p(dK), _p(dV),
                                    _p(ws), ctypes.c_size_t(ws.numel()), _stream()), "moba_backward")
     else:
         _check(lib().moba_backward_parts(ctypes.byref(shape.c()), _p(Q), _p(K_eff), _p(V), _p(O),
-                                         _p(lse), _p(dO), _p(idx), _p(off), _p(ql), _p(chunk), _p(dQ),
+                                         _p(lse), _p(dO), _p(idx), _p(off), _p(ql), _p(dQ),
                                          _p(dK), _p(dV), _p(ws), ctypes.c_size_t(ws.numel()), _stream(),
                                          ctypes.c_uint32(parts)), "moba_backward_parts")
     return dQ, dK, dV

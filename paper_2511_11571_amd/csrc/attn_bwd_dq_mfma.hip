@@ -299,7 +299,7 @@ size_t backward_mfma_ws_bytes(const Dims& s)
 
 hipError_t launch_dq_mfma(const Dims& s, const void* Q, const void* K, const void* V, const void* dO,
                           const float* lse, const int32_t* idx, const int32_t* off, const int32_t* ql,
-                          const int32_t* chunk, void* dQ, void* ws, hipStream_t st)
+                          void* dQ, void* ws, hipStream_t st)
 {
     char* p = (char*)ws;
     const float* Dv = (const float*)p;

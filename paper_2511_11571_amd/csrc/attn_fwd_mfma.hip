@@ -532,7 +532,7 @@ size_t forward_mfma_ws_bytes(const Dims& s)
 //     [bh*D fp32 bits: channel maxima of V]
 hipError_t launch_forward_mfma(const Dims& s, const void* Q, const void* K, const void* V,
                                void* ws, const int32_t* idx, const int32_t* off, const int32_t* ql,
-                               const int32_t* chunk, void* O, float* lse, hipStream_t st)
+                               void* O, float* lse, hipStream_t st)
 {
     const size_t vt_bytes = (sizeof(bf16_t) * (size_t)s.bh * s.N * s.D + 255) & ~(size_t)255;
     void* Ka = (char*)ws + vt_bytes;

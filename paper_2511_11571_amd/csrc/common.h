@@ -10,7 +10,7 @@ namespace moba {
 typedef uint16_t bf16_t;   // raw bfloat16 bits
 
 constexpr int kWave = 64;
-constexpr int kChunkQ = MOBA_CHUNK_QUERIES;   // queries per routing chunk (blk_chunk granularity)
+constexpr int kChunkQ = 128;   // queries per chunk of the list builder's per-(chunk, block) counts
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t x)
 {
@@ -142,7 +142,7 @@ hipError_t launch_centroids(const Dims& s, const void* K, const float* w, void* 
 hipError_t launch_topk_reference(const Dims& s, const void* Q, const float* cent, int32_t* idx,
                                  hipStream_t st);
 hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, int32_t* ql,
-                              int32_t* blk_chunk, hipStream_t st);
+                              int32_t* chunk_counts, hipStream_t st);
 hipError_t launch_forward_reference(const Dims& s, const void* Q, const void* K, const void* V,
                                     const int32_t* idx, void* O, float* lse, hipStream_t st);
 hipError_t launch_backward_reference(const Dims& s, const void* Q, const void* K, const void* V,

@@ -6,9 +6,7 @@
 //      (query, kept block) into an LDS bit matrix [block][256 bits]; the population
 //      count of a row is the number of queries of this chunk that kept that block.
 //   2. scan: per key block an exclusive scan over chunks (start of each chunk's segment
-//      inside the block's list; kept as the blk_chunk output, which lets a query-tile kernel
-//      find "its" rows of any block's list directly), then an exclusive scan of the block
-//      totals (blk_off).
+//      inside the block's list), then an exclusive scan of the block totals (blk_off).
 //   3. fill: the bit matrix is rebuilt; the place of query q in block j's list is
 //      blk_off[j] + chunk start + (number of set bits of row j below q), so every (query, kept
 //      block) pair writes its own entry and the lists come out ascending.
@@ -121,7 +119,7 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
     }
 }
 
-// per slice and key block: blk_chunk[c][j] <- sum_{c' < c} count[c'][j] (row nchunk: the total).
+// per slice and key block: cnt2[c][j] <- sum_{c' < c} cnt2[c'][j] (row nchunk: the total).
 // A workgroup takes 32 key blocks; 8 threads per block share the chunks.
 __global__ __launch_bounds__(256) void lists_scan_kernel(int32_t* __restrict__ cnt2,
                                                          int32_t* __restrict__ off, int n,

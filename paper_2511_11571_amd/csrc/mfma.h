@@ -237,12 +237,12 @@ hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, const 
 size_t forward_mfma_ws_bytes(const Dims& s);
 hipError_t launch_forward_mfma(const Dims& s, const void* Q, const void* K, const void* V,
                                void* ws, const int32_t* idx, const int32_t* off, const int32_t* ql,
-                               const int32_t* chunk, void* O, float* lse, hipStream_t st);
+                               void* O, float* lse, hipStream_t st);
 
 size_t backward_mfma_ws_bytes(const Dims& s);
 hipError_t launch_dq_mfma(const Dims& s, const void* Q, const void* K, const void* V, const void* dO,
                           const float* lse, const int32_t* idx, const int32_t* off, const int32_t* ql,
-                          const int32_t* chunk, void* dQ, void* ws, hipStream_t st);
+                          void* dQ, void* ws, hipStream_t st);
 
 hipError_t launch_dkdv_mfma(const Dims& s, const void* Q, const void* K, const void* V,
                             const void* dO, const float* lse, const float* Dv, const int32_t* off,

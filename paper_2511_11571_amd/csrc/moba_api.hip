@@ -57,8 +57,18 @@ int make_dims(const moba_shape* sh, Dims& d)
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// top-k: three bf16 terms of the centroids (MFMA scoring); the list builder needs none
-size_t topk_ws_bytes(const Dims& d) { return align256(topk_mfma_ws_bytes(d)) + 256; }
+// top-k: the list builder's per-(128-query chunk, key block) counts, then the three bf16 terms
+// of the centroids (MFMA scoring)
+size_t chunk_counts_bytes(const Dims& d)
+{
+    return align256(sizeof(int32_t) * (size_t)d.bh * (d.nchunk + 1) * d.n);
+}
+size_t topk_ws_bytes(const Dims& d)
+{
+    return chunk_counts_bytes(d) + align256(topk_mfma_ws_bytes(d)) + 256;
+}
+int32_t* chunk_counts(const Dims&, void* ws) { return static_cast<int32_t*>(ws); }
+void* topk_terms(const Dims& d, void* ws) { return static_cast<char*>(ws) + chunk_counts_bytes(d); }
 // forward: slot-ordered transposed copy of V for the MFMA kernel
 size_t fwd_ws_bytes(const Dims& d)
 {
@@ -181,50 +191,49 @@ int moba_centroids(const moba_shape* shape, const void* K, const float* conv_w, 
 }
 
 int moba_build_lists(const moba_shape* shape, const int32_t* topk_idx, int32_t* blk_off,
-                     int32_t* blk_q, int32_t* blk_chunk, void* ws, size_t ws_bytes, void* stream)
+                     int32_t* blk_q, void* ws, size_t ws_bytes, void* stream)
 {
     Dims d;
     const int st = make_dims(shape, d);
     if (st != MOBA_OK) return st;
-    if (!blk_off || !blk_chunk) return MOBA_EINVAL;
+    if (!blk_off) return MOBA_EINVAL;
     if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
     if (d.R > 0 && !blk_q) return MOBA_EINVAL;
     if (!ws || ws_bytes < topk_ws_bytes(d)) return MOBA_EWORKSPACE;
-    return hip_status(launch_build_lists(d, topk_idx, blk_off, blk_q, blk_chunk, (hipStream_t)stream));
+    return hip_status(launch_build_lists(d, topk_idx, blk_off, blk_q, chunk_counts(d, ws), (hipStream_t)stream));
 }
 
 int moba_topk(const moba_shape* shape, const void* Q, const float* centroids, int32_t* topk_idx,
-              int32_t* blk_off, int32_t* blk_q, int32_t* blk_chunk, void* ws, size_t ws_bytes,
-              void* stream)
+              int32_t* blk_off, int32_t* blk_q, void* ws, size_t ws_bytes, void* stream)
 {
     Dims d;
     const int st = make_dims(shape, d);
     if (st != MOBA_OK) return st;
-    if (!Q || !centroids || !blk_off || !blk_chunk) return MOBA_EINVAL;
+    if (!Q || !centroids || !blk_off) return MOBA_EINVAL;
     if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
     if (d.R > 0 && !blk_q) return MOBA_EINVAL;
     if (d.n > kMaxBlocks) return MOBA_EUNSUPPORTED;
     if (!ws || ws_bytes < topk_ws_bytes(d)) return MOBA_EWORKSPACE;
     hipError_t e = topk_mfma_supported(d)
-                       ? launch_topk_mfma(d, Q, centroids, topk_idx, ws, (hipStream_t)stream)
+                       ? launch_topk_mfma(d, Q, centroids, topk_idx, topk_terms(d, ws), (hipStream_t)stream)
                        : launch_topk_reference(d, Q, centroids, topk_idx, (hipStream_t)stream);
     if (e != hipSuccess) return hip_status(e);
-    return hip_status(launch_build_lists(d, topk_idx, blk_off, blk_q, blk_chunk, (hipStream_t)stream));
+    return hip_status(launch_build_lists(d, topk_idx, blk_off, blk_q, chunk_counts(d, ws), (hipStream_t)stream));
 }
 
 int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
                  const int32_t* topk_idx, const int32_t* blk_off, const int32_t* blk_q,
-                 const int32_t* blk_chunk, void* O, float* lse, void* ws, size_t ws_bytes, void* stream)
+                 void* O, float* lse, void* ws, size_t ws_bytes, void* stream)
 {
     Dims d;
     const int st = make_dims(shape, d);
     if (st != MOBA_OK) return st;
-    if (!Q || !K_eff || !V || !O || !lse || !blk_off || !blk_chunk) return MOBA_EINVAL;
+    if (!Q || !K_eff || !V || !O || !lse || !blk_off) return MOBA_EINVAL;
     if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
     if (d.R > 0 && !blk_q) return MOBA_EINVAL;
     if (!ws || ws_bytes < fwd_ws_bytes(d)) return MOBA_EWORKSPACE;
     if (mfma_path(d))
-        return hip_status(launch_forward_mfma(d, Q, K_eff, V, ws, topk_idx, blk_off, blk_q, blk_chunk, O, lse,
+        return hip_status(launch_forward_mfma(d, Q, K_eff, V, ws, topk_idx, blk_off, blk_q, O, lse,
                                               (hipStream_t)stream));
     return hip_status(
         launch_forward_reference(d, Q, K_eff, V, topk_idx, O, lse, (hipStream_t)stream));
@@ -232,7 +241,7 @@ int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, cons
 
 int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
                         const void* O, const float* lse, const void* dO, const int32_t* topk_idx,
-                        const int32_t* blk_off, const int32_t* blk_q, const int32_t* blk_chunk,
+                        const int32_t* blk_off, const int32_t* blk_q,
                         void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream,
                         uint32_t parts)
 {
@@ -240,7 +249,7 @@ int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_ef
     const int st = make_dims(shape, d);
     if (st != MOBA_OK) return st;
     if (parts == 0 || (parts & ~(uint32_t)MOBA_BWD_ALL)) return MOBA_EINVAL;
-    if (!Q || !K_eff || !V || !lse || !dO || !blk_off || !blk_chunk) return MOBA_EINVAL;
+    if (!Q || !K_eff || !V || !lse || !dO || !blk_off) return MOBA_EINVAL;
     if ((parts & MOBA_BWD_PREPROCESS) && !O) return MOBA_EINVAL;
     if ((parts & MOBA_BWD_DQ) && !dQ) return MOBA_EINVAL;
     if ((parts & MOBA_BWD_DKDV) && (!dK || !dV)) return MOBA_EINVAL;
@@ -257,7 +266,7 @@ int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_ef
             if (e != hipSuccess) return hip_status(e);
         }
         if (parts & MOBA_BWD_DQ) {
-            hipError_t e = launch_dq_mfma(d, Q, K_eff, V, dO, lse, topk_idx, blk_off, blk_q, blk_chunk, dQ, ws, hs);
+            hipError_t e = launch_dq_mfma(d, Q, K_eff, V, dO, lse, topk_idx, blk_off, blk_q, dQ, ws, hs);
             if (e != hipSuccess) return hip_status(e);
         }
         if (parts & MOBA_BWD_DKDV) {
@@ -273,10 +282,10 @@ int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_ef
 
 int moba_backward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
                   const void* O, const float* lse, const void* dO, const int32_t* topk_idx,
-                  const int32_t* blk_off, const int32_t* blk_q, const int32_t* blk_chunk, void* dQ,
+                  const int32_t* blk_off, const int32_t* blk_q, void* dQ,
                   void* dK, void* dV, void* ws, size_t ws_bytes, void* stream)
 {
-    return moba_backward_parts(shape, Q, K_eff, V, O, lse, dO, topk_idx, blk_off, blk_q, blk_chunk, dQ,
+    return moba_backward_parts(shape, Q, K_eff, V, O, lse, dO, topk_idx, blk_off, blk_q, dQ,
                                dK, dV, ws, ws_bytes, stream, MOBA_BWD_ALL);
 }
 

@@ -69,19 +69,19 @@ def test_null_pointers_and_short_workspace(lib):
     conv = _shape(conv_width=4).c()
     assert lib.moba_centroids(ctypes.byref(conv), one, z, one, one, z) == -1   # conv without weights
     assert lib.moba_centroids(ctypes.byref(conv), one, one, z, one, z) == -1   # conv needs K_eff
-    assert lib.moba_topk(ctypes.byref(sh), z, one, one, one, one, one, one, big, z) == -1
-    assert lib.moba_topk(ctypes.byref(sh), one, one, one, one, one, z, one, big, z) == -1      # no blk_chunk
-    assert lib.moba_topk(ctypes.byref(sh), one, one, one, one, one, one, z, big, z) == -3
-    assert lib.moba_topk(ctypes.byref(sh), one, one, one, one, one, one, one, ctypes.c_size_t(8), z) == -3
-    assert lib.moba_build_lists(ctypes.byref(sh), z, one, one, one, one, big, z) == -1
-    assert lib.moba_forward(ctypes.byref(sh), one, one, one, one, one, one, one, z, one, one, big, z) == -1
-    assert lib.moba_forward(ctypes.byref(sh), one, one, one, one, one, one, one, one, one, z, big, z) == -3
-    assert lib.moba_backward(ctypes.byref(sh), one, one, one, one, one, one, one, one, one, one,
+    assert lib.moba_topk(ctypes.byref(sh), z, one, one, one, one, one, big, z) == -1
+    assert lib.moba_topk(ctypes.byref(sh), one, one, one, z, one, one, big, z) == -1           # no blk_off
+    assert lib.moba_topk(ctypes.byref(sh), one, one, one, one, one, z, big, z) == -3
+    assert lib.moba_topk(ctypes.byref(sh), one, one, one, one, one, one, ctypes.c_size_t(8), z) == -3
+    assert lib.moba_build_lists(ctypes.byref(sh), z, one, one, one, big, z) == -1
+    assert lib.moba_forward(ctypes.byref(sh), one, one, one, one, one, one, z, one, one, big, z) == -1
+    assert lib.moba_forward(ctypes.byref(sh), one, one, one, one, one, one, one, one, z, big, z) == -3
+    assert lib.moba_backward(ctypes.byref(sh), one, one, one, one, one, one, one, one, one,
                              one, one, z, one, big, z) == -1
-    assert lib.moba_backward(ctypes.byref(sh), one, one, one, one, one, one, one, one, one, one,
+    assert lib.moba_backward(ctypes.byref(sh), one, one, one, one, one, one, one, one, one,
                              one, one, one, one, ctypes.c_size_t(16), z) == -3
     many = _shape(seqlen=32 * 5000).c()
-    assert lib.moba_topk(ctypes.byref(many), one, one, one, one, one, one, one, big, z) == -2
+    assert lib.moba_topk(ctypes.byref(many), one, one, one, one, one, one, big, z) == -2
 
 
 def test_binding_raises(lib):

@@ -27,7 +27,7 @@ def run_gpu(w):
     Keff, cent = moba.centroids(sh, d["K"], d["conv_w"])
     idx, lists = moba.topk(sh, d["Q"], cent)
     O, lse = moba.forward(sh, d["Q"], Keff, d["V"], idx, lists)
-    out = dict(Keff=Keff, cent=cent, idx=idx, off=lists[0], ql=lists[1], chunk=lists[2], O=O, lse=lse)
+    out = dict(Keff=Keff, cent=cent, idx=idx, off=lists[0], ql=lists[1], O=O, lse=lse)
     if w.backward:
         out["dQ"], out["dK"], out["dV"] = moba.backward(sh, d["Q"], Keff, d["V"], O, lse, d["dO"],
                                                         idx, lists)
@@ -77,13 +77,9 @@ def check_slice(oracle, w, t, out, s, n_rows, blocks, rng):
     assert g_off[0] == 0 and g_off[-1] == oracle.routes_per_slice(w.N, w.B, w.k)
     counts = np.bincount(g_idx[g_idx >= 0].ravel(), minlength=w.n)
     assert np.array_equal(np.diff(g_off), counts)
-    g_chunk = out["chunk"][b, h].cpu().numpy()
-    nchunk = (w.N + 127) // 128
-    assert np.array_equal(g_chunk[nchunk], counts)
     for j in rng.integers(0, w.n, 8):
         lst = g_ql[g_off[j]:g_off[j + 1]]
         assert np.array_equal(lst, np.nonzero((g_idx == j).any(-1))[0])
-        assert np.array_equal(g_chunk[:, j], np.searchsorted(lst, 128 * np.arange(nchunk + 1)))
 
     # forward / dQ on sampled rows, with the oracle's own routing
     sample = rows if not full else np.unique(rng.integers(0, w.N, n_rows)).astype(np.int64)
