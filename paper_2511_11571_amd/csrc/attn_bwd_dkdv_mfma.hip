@@ -102,8 +102,18 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
             dVT[mt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         }
 
-    // position a of the walk -> query: the block's list, then its own queries from this group on
-    auto query_at = [&](int a) { return a >= total ? own0 : (a < nlist ? qs[lo + a] : own0 + (a - nlist)); };
+    // position a of the walk -> query: the block's list, then its own queries from this group on;
+    // positions past the end read as the first own query (a valid row; its P is forced to 0).
+    // Every load below is unconditional (from an address that is always valid): a load inside a
+    // branch would be waited for at the end of the branch, and with it all the row gathers
+    // issued before it.
+    const int32_t* lsrc = nlist > 0 ? qs + lo : os;          // an empty list reads os[0] and ignores it
+    const int llast = max(nlist - 1, 0);
+    auto query_at = [&](int a) {
+        const int listed = lsrc[min(a, llast)];
+        const int t = a < nlist ? listed : own0 + (a - nlist);
+        return a >= total ? own0 : t;
+    };
     // The gathers are the long pole (two dependent global loads: list entry, then the row), so
     // they run ahead of the arithmetic: row ids two steps ahead, rows one step ahead.
     const int grow = lane / C::CPR;                          // row of this lane inside a gather instruction
@@ -113,6 +123,7 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
         for (int i = 0; i < C::NI; ++i) t[i] = query_at(a0 + C::RPI * i + grow);
         tl = query_at(a0 + (lane & 31));
     };
+    // lv: lse in log2 units (+inf past the end: P = 0); dv: -D, the start value of the dP product
     auto fetch = [&](int a0, const int (&t)[C::NI], int tl, u32x4_t (&qr)[C::NI], u32x4_t (&gr)[C::NI],
                      float& lv, float& dv) {
 #pragma unroll
@@ -121,12 +132,10 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
             qr[i] = *reinterpret_cast<const u32x4_t*>(Qg + o);
             gr[i] = *reinterpret_cast<const u32x4_t*>(Gg + o);
         }
-        lv = INFINITY;                                // rows past the end of the walk: P = 0
-        dv = 0.f;                                     // -D, the start value of the dP product
-        if (a0 + (lane & 31) < total) {
-            lv = lse[sbase + tl] * kLog2e;
-            dv = -Dv[sbase + tl];
-        }
+        const bool live = a0 + (lane & 31) < total;
+        const float l = lse[sbase + tl], dd = Dv[sbase + tl];
+        lv = live ? l * kLog2e : INFINITY;
+        dv = live ? -dd : 0.f;
     };
     const int stride = 32 * C::NW;
     int tN[C::NI], tlN;
