@@ -48,11 +48,14 @@ __device__ __forceinline__ void for_each_entry(const int32_t* __restrict__ rows0
 template <bool FILL>
 __global__ __launch_bounds__(256) void lists_chunk_kernel(
     const int32_t* __restrict__ idx, int32_t* __restrict__ cnt2, const int32_t* __restrict__ off,
-    int32_t* __restrict__ ql, int N, int B, int n, int k, int nchunk, int64_t R)
+    int32_t* __restrict__ ql, int N, int B, int n, int k, int nchunk, int64_t R, int bh)
 {
     __shared__ __align__(16) uint32_t mask[kRange * kWords];
     __shared__ int32_t start[FILL ? 2 * kRange : 2];     // first list position of each half's queries
-    const int c = blockIdx.x, s = blockIdx.z;
+    // consecutive query chunks of a slice go to the same XCD: the 128-byte lines of a block's
+    // list are completed by neighbouring chunks and should meet in one L2 before they are written back
+    int c, s;
+    if (!schedule(blockIdx.x, bh, (nchunk + 1) / 2, s, c)) return;
     const int lo = blockIdx.y * kRange;
     const int hi = min(n, lo + kRange);
     const int t0 = c * kListQ;
@@ -183,15 +186,15 @@ hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, i
                               int32_t* cnt2, hipStream_t st)
 {
     const int nranges = (s.n + kRange - 1) / kRange;
-    dim3 grid((s.nchunk + 1) / 2, nranges, s.bh), block(256);
+    dim3 grid(schedule_grid(s.bh, (s.nchunk + 1) / 2), nranges), block(256);
     hipLaunchKernelGGL((lists_chunk_kernel<false>), grid, block, 0, st, idx, cnt2,
-                       (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R);
+                       (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R, s.bh);
     hipLaunchKernelGGL(lists_scan_kernel, dim3((s.n + 31) / 32, s.bh), block, 0, st, cnt2, off, s.n,
                        s.nchunk);
     hipLaunchKernelGGL(lists_offsets_kernel, dim3(s.bh), block, 0, st, off, s.n);
     if (s.R > 0)
         hipLaunchKernelGGL((lists_chunk_kernel<true>), grid, block, 0, st, idx, cnt2,
-                           (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R);
+                           (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R, s.bh);
     return hipGetLastError();
 }
 

@@ -76,40 +76,6 @@ __host__ __device__ __forceinline__ constexpr int64_t slot_major_offset(int64_t 
     return (kap * (D / 16) + mt) * 512 + (int64_t)lane * 8;
 }
 
-// ---- workgroup -> (slice, position) ------------------------------------------------------
-// Workgroups are dealt to the chip's 8 XCDs round robin (workgroup i runs on XCD i % 8) and
-// every XCD has an L2 of its own.  The workgroups resident on one XCD at a time should
-// therefore read the same K / V (or Q / dO) rows: with a multiple of 8 slices, XCD x works
-// through the slices x, x + 8, ... one after the other; with 1, 2 or 4 slices, 8 / bh XCDs
-// share the positions of a slice.  Anything else falls back to slice-interleaved order.
-constexpr int kXcds = 8;
-__host__ __device__ inline int schedule_grid(int bh, int npos)
-{
-    if (bh % kXcds != 0 && kXcds % bh == 0) {
-        const int X = kXcds / bh;
-        return kXcds * ((npos + X - 1) / X);
-    }
-    return bh * npos;
-}
-// false: this workgroup has nothing to do
-__device__ __forceinline__ bool schedule(int bid, int bh, int npos, int& s, int& pos)
-{
-    const int xcd = bid % kXcds, local = bid / kXcds;
-    if (bh % kXcds == 0) {
-        s = xcd + kXcds * (local / npos);
-        pos = local % npos;
-        return true;
-    }
-    if (kXcds % bh == 0) {
-        s = xcd % bh;
-        pos = local * (kXcds / bh) + xcd / bh;
-        return pos < npos;
-    }
-    s = bid % bh;
-    pos = bid / bh;
-    return true;
-}
-
 // Ascending list of the non-empty blocks of a set of row lists (offs as built below):
 // ulist[0 .. *count).  All NT threads; ends with a workgroup barrier.
 template <int NT>
