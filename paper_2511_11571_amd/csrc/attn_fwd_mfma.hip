@@ -34,16 +34,10 @@
 
 namespace moba {
 
-#ifndef MOBA_FWD_NW64
-#define MOBA_FWD_NW64 16
-#define MOBA_FWD_UPRE64 false
-#define MOBA_FWD_SPIPE64 false
-#endif
-
 template <int D>
 struct FwdCfg {
     static constexpr int TILE = D == 64 ? 256 : 128;   // queries per workgroup
-    static constexpr int NW = D == 64 ? MOBA_FWD_NW64 : 8;   // waves per workgroup
+    static constexpr int NW = D == 64 ? 16 : 12;       // waves per workgroup (registers allow no more)
     static constexpr int NT = NW * kWave;
     static constexpr int QSTRIDE = D * 2 + 16;         // bytes per Q row in LDS
     static constexpr int OSTRIDE = D + 1;              // words per accumulator row
@@ -51,9 +45,6 @@ struct FwdCfg {
     static constexpr int KS = D / 32;                  // contraction steps of q.k
     static constexpr int RANGE = 1024;                 // key blocks per set of row lists (at most)
     static constexpr int LCAP = 16384;                 // (row, block) pairs per set of row lists
-    static constexpr bool UPRE = D == 64 ? MOBA_FWD_UPRE64 : true;   // K operands fetched one unit ahead
-    static constexpr bool PREV = D == 64;              // ... and the V operands too (registers allow)
-    static constexpr bool SPIPE = D == 64 ? MOBA_FWD_SPIPE64 : true; // Q gather one sub-tile ahead
     static constexpr size_t LDS = (size_t)TILE * QSTRIDE + 4 * TILE * OSTRIDE + 4 * 2 * TILE +
                                   4 * 2 * (RANGE + 1) + 4 * NW + 8 + LCAP + 64;
 };
@@ -374,17 +365,13 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                 end = offs[j + 1];
                 const int kap = (lo + j) * NG + gi;
                 load_k(kap, ka);
-                if (C::PREV && pass == 1) load_v(kap, va);
-                return kap;
+                if (pass == 1) load_v(kap, va);
             };
-            auto run_unit = [&](int kap, int beg_v, int end_v, const Frag (&ka)[2][C::KS], Frag (&va)[C::MT]) {
-                if (!C::PREV && pass == 1) load_v(kap, va);
+            auto run_unit = [&](int beg_v, int end_v, const Frag (&ka)[2][C::KS], const Frag (&va)[C::MT]) {
                 const int beg = __builtin_amdgcn_readfirstlane(beg_v);
                 const int end = min(__builtin_amdgcn_readfirstlane(end_v), (int)C::LCAP);
-                // Sub-tiles of 16 rows.  The row ids of four sub-tiles are read at once, and the
-                // LDS gather of the next sub-tile is issued before the arithmetic and the atomics
-                // of the current one, so it never waits behind them.  Lanes beyond the list work
-                // on whatever row id they read (always inside the tile) and add nothing.
+                // Sub-tiles of 16 listed rows.  Lanes beyond the list work on whatever row id they
+                // read (always inside the tile) and add nothing.
                 auto gather = [&](int row, Frag (&qb)[C::KS], float& mr) {
                     gather_q(row, qb);
                     mr = pass == 1 ? __int_as_float(mkey[row]) : 0.f;
@@ -408,79 +395,27 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                         accumulate(row, x, va, valid);
                     }
                 };
-                if constexpr (C::SPIPE) {
-                    for (int c0 = beg; c0 < end; c0 += 64) {
-                        const int left = end - c0;          // > 0
-                        bool val[4];
-                        int rows[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            val[j] = 16 * j + m16 < left;
-                            rows[j] = rows8[c0 + 16 * j + m16] & (C::TILE - 1);
-                        }
-                        Frag qA[C::KS], qB[C::KS];
-                        float mA, mB;
-                        gather(rows[0], qA, mA);
-                        if (left > 16) gather(rows[1], qB, mB);
-                        compute(val[0], rows[0], qA, mA);
-                        if (left > 16) {
-                            if (left > 32) gather(rows[2], qA, mA);
-                            compute(val[1], rows[1], qB, mB);
-                            if (left > 32) {
-                                if (left > 48) gather(rows[3], qB, mB);
-                                compute(val[2], rows[2], qA, mA);
-                                if (left > 48) compute(val[3], rows[3], qB, mB);
-                            }
-                        }
-                    }
-                } else {
-                    for (int c0 = beg; c0 < end; c0 += 16) {
-                        const bool valid = m16 < end - c0;
-                        const int row = rows8[c0 + m16] & (C::TILE - 1);
-                        Frag qA[C::KS];
-                        float mA;
-                        gather(row, qA, mA);
-                        compute(valid, row, qA, mA);
-                    }
+                for (int c0 = beg; c0 < end; c0 += 16) {
+                    const bool valid = m16 < end - c0;
+                    const int row = rows8[c0 + m16] & (C::TILE - 1);
+                    Frag qA[C::KS];
+                    float mA;
+                    gather(row, qA, mA);
+                    compute(valid, row, qA, mA);
                 }
             };
 
-            // waves take the listed blocks round robin; the operands of a wave's next unit are in
-            // flight while it works on the current one
-            if constexpr (C::UPRE) {
-                Frag kaA[2][C::KS], vaA[C::MT], kaB[2][C::KS];
-                Frag vaB_[C::PREV ? C::MT : 1];
-                Frag (&vaB)[C::MT] = *reinterpret_cast<Frag (*)[C::MT]>(C::PREV ? (void*)&vaB_ : (void*)&vaA);
-                int begA = 0, endA = 0, begB = 0, endB = 0, kapA = 0, kapB = 0;
-                int e = wave, gi = 0;
-                auto advance = [&](int& e2, int& gi2) {
-                    if (++gi2 == NG) { gi2 = 0; e2 += C::NW; }
-                };
-                if (e < nblk) kapA = load_unit(e, gi, kaA, vaA, begA, endA);
-                while (e < nblk) {
-                    int en = e, gn = gi;
-                    advance(en, gn);
-                    if (en < nblk) kapB = load_unit(en, gn, kaB, vaB, begB, endB);
-                    run_unit(kapA, begA, endA, kaA, vaA);
-                    e = en; gi = gn;
-                    if (e >= nblk) break;
-                    advance(en, gn);
-                    if (en < nblk) kapA = load_unit(en, gn, kaA, vaA, begA, endA);
-                    run_unit(kapB, begB, endB, kaB, vaB);
-                    e = en; gi = gn;
+            // waves take the listed blocks as they get free (other waves cover the operand latency)
+            int e = take_unit(take, lane);
+            while (e < nblk) {
+                const int en = take_unit(take, lane);     // asked for early: its latency hides behind this unit
+                for (int gi = 0; gi < NG; ++gi) {
+                    Frag ka[2][C::KS], va[C::MT];
+                    int beg, end;
+                    load_unit(e, gi, ka, va, beg, end);
+                    run_unit(beg, end, ka, va);
                 }
-            } else {
-                int e = take_unit(take, lane);
-                while (e < nblk) {
-                    const int en = take_unit(take, lane);     // asked for early: its latency hides behind this unit
-                    for (int gi = 0; gi < NG; ++gi) {
-                        Frag ka[2][C::KS], va[C::MT];
-                        int beg, end;
-                        const int kap = load_unit(e, gi, ka, va, beg, end);
-                        run_unit(kap, beg, end, ka, va);
-                    }
-                    e = en;
-                }
+                e = en;
             }
         }
         __syncthreads();
