@@ -66,6 +66,8 @@ SMALL = [
     W("bf16_one_block", 1, 1, 128, 64, 128, 4, seed=19),       # n = 1
     W("bf16_B1", 1, 1, 256, 64, 1, 7, seed=20),                # centroid = key
     W("bf16_skew", 1, 2, 2048, 64, 64, 6, skew=True, seed=21),
+    # more (row, block) pairs per query tile than one set of LDS row lists holds: several ranges
+    W("bf16_k80_ranges", 1, 1, 4096, 64, 32, 80, seed=22),
 ]
 IDS = [w.name for w in SMALL]
 
