@@ -21,6 +21,8 @@
 //   dV^T += dO_g^T P, dK^T += Q_g^T dS   the A operands are the parked rows transposed, which
 //                                        the LDS transpose read of gfx950 (ds_read_b64_tr_b16)
 //                                        delivers four query slots per lane at a time.
+#include <type_traits>
+
 #include "mfma.h"
 
 namespace moba {
@@ -118,21 +120,29 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
     // they run ahead of the arithmetic: row ids two steps ahead, rows one step ahead.
     const int grow = lane / C::CPR;                          // row of this lane inside a gather instruction
     const uint32_t gcol = (uint32_t)(lane % C::CPR) * 16u;   // its bytes inside the row
-    auto ids = [&](int a0, int (&t)[C::NI], int& tl) {
+    // `inside` (a compile-time flag): all 32 positions lie in the block's list -- the bulk of the
+    // walk, which then needs no selects
+    auto ids = [&](int a0, int (&t)[C::NI], int& tl, auto inside) {
+        if constexpr (decltype(inside)::value) {
 #pragma unroll
-        for (int i = 0; i < C::NI; ++i) t[i] = query_at(a0 + C::RPI * i + grow);
-        tl = query_at(a0 + (lane & 31));
+            for (int i = 0; i < C::NI; ++i) t[i] = lsrc[a0 + C::RPI * i + grow];
+            tl = lsrc[a0 + (lane & 31)];
+        } else {
+#pragma unroll
+            for (int i = 0; i < C::NI; ++i) t[i] = query_at(a0 + C::RPI * i + grow);
+            tl = query_at(a0 + (lane & 31));
+        }
     };
     // lv: lse in log2 units (+inf past the end: P = 0); dv: -D, the start value of the dP product
     auto fetch = [&](int a0, const int (&t)[C::NI], int tl, u32x4_t (&qr)[C::NI], u32x4_t (&gr)[C::NI],
-                     float& lv, float& dv) {
+                     float& lv, float& dv, auto inside) {
 #pragma unroll
         for (int i = 0; i < C::NI; ++i) {
             const uint32_t o = (uint32_t)t[i] * (uint32_t)(2 * D) + gcol;
             qr[i] = *reinterpret_cast<const u32x4_t*>(Qg + o);
             gr[i] = *reinterpret_cast<const u32x4_t*>(Gg + o);
         }
-        const bool live = a0 + (lane & 31) < total;
+        const bool live = decltype(inside)::value || a0 + (lane & 31) < total;
         const float l = lse[sbase + tl], dd = Dv[sbase + tl];
         lv = live ? l * kLog2e : INFINITY;
         dv = live ? -dd : 0.f;
@@ -143,9 +153,9 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
     float lv, dv;
     {
         int t0[C::NI], tl0;
-        ids(32 * wave, t0, tl0);
-        fetch(32 * wave, t0, tl0, qr, gr, lv, dv);
-        ids(32 * wave + stride, tN, tlN);
+        ids(32 * wave, t0, tl0, std::false_type());
+        fetch(32 * wave, t0, tl0, qr, gr, lv, dv, std::false_type());
+        ids(32 * wave + stride, tN, tlN, std::false_type());
     }
     const uint32_t park = (uint32_t)grow * C::SB + gcol;                       // gather lane -> parked bytes
     const uint32_t arow = (uint32_t)m16 * C::SB + 16u * g;                     // row-major operand of this lane
@@ -153,7 +163,7 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
     const int te = (lane >> 2) & 3, ta = lane & 3;
     const uint32_t tr0 = (uint32_t)slot_key(g, te) * C::SB + 8u * ta;
     const uint32_t tr1 = (uint32_t)slot_key(g, te + 4) * C::SB + 8u * ta;
-    for (int a0 = 32 * wave; a0 < total; a0 += stride) {
+    auto step = [&](int a0, auto inside) {
         // park this step's rows, then put the next step's loads in flight
 #pragma unroll
         for (int i = 0; i < C::NI; ++i) {
@@ -161,8 +171,8 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
             *reinterpret_cast<u32x4_t*>(stG + park + i * C::RPI * C::SB) = gr[i];
         }
         if (lane < 32) { ls[lane] = lv; Ds[lane] = dv; }
-        fetch(a0 + stride, tN, tlN, qr, gr, lv, dv);
-        ids(a0 + 2 * stride, tN, tlN);
+        fetch(a0 + stride, tN, tlN, qr, gr, lv, dv, inside);
+        ids(a0 + 2 * stride, tN, tlN, inside);
         __builtin_amdgcn_wave_barrier();
         // S and dP
         f32x4_t sc[2][2], dp[2][2];
@@ -187,7 +197,7 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
             }
         }
         // own queries of this very group are causal: key (16 nt + m16) must not exceed the query
-        const bool causal = a0 + 32 > nlist && a0 < nlist + 32;    // the step touches own rows 0..31
+        const bool causal = !decltype(inside)::value && a0 + 32 > nlist && a0 < nlist + 32;    // the step touches own rows 0..31
         Frag pb[2], sb[2];
         f32x4_t l4[2];
 #pragma unroll
@@ -229,7 +239,12 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
             }
         }
         __builtin_amdgcn_wave_barrier();
-    }
+    };
+    // the bulk of the walk: this step, the rows fetched in it and the ids looked up in it all lie
+    // inside the block's list; then the general steps (own rows, causal mask, end of the walk)
+    int a0 = 32 * wave;
+    for (; a0 + 2 * stride + 32 <= nlist; a0 += stride) step(a0, std::true_type());
+    for (; a0 < total; a0 += stride) step(a0, std::false_type());
 
     // sum the four waves' accumulators through LDS: red[tensor][key][channel]
     for (int w = 0; w < C::NW; ++w) {
