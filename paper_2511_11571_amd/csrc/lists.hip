@@ -7,9 +7,8 @@
 //      count of a row is the number of queries of this chunk that kept that block.
 //   2. scan: per key block an exclusive scan over chunks (start of each chunk's segment
 //      inside the block's list), then an exclusive scan of the block totals (blk_off).
-//   3. fill: the bit matrix is rebuilt; the place of query q in block j's list is
-//      blk_off[j] + chunk start + (number of set bits of row j below q), so every (query, kept
-//      block) pair writes its own entry and the lists come out ascending.
+//   3. fill: the bit matrix is rebuilt and its rows are written out in ascending order at
+//      blk_off[j] + chunk start, eight lanes per row.
 // The bit matrix lives in LDS only and covers 1024 key blocks at a time.
 #include "common.h"
 
@@ -51,7 +50,7 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
     int32_t* __restrict__ ql, int N, int B, int n, int k, int nchunk, int64_t R, int bh)
 {
     __shared__ __align__(16) uint32_t mask[kRange * kWords];
-    __shared__ int32_t start[FILL ? 2 * kRange : 2];     // first list position of each half's queries
+    __shared__ int32_t start[FILL ? kRange : 1];         // where this workgroup's queries start in each list
     // consecutive query chunks of a slice go to the same XCD: the 128-byte lines of a block's
     // list are completed by neighbouring chunks and should meet in one L2 before they are written back
     int c, s;
@@ -78,7 +77,6 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
         const int32_t* orow = off + (int64_t)s * (n + 1) + lo;
         for (int j = tid; j < nblk; j += 256) {
             start[j] = orow[j] + crow[j];
-            start[kRange + j] = orow[j] + (two ? crow[n + j] : 0);
         }
     }
     __syncthreads();
@@ -103,22 +101,29 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
             if (two) crow[n + j] = c1;
         }
     } else {
+        // Eight lanes per block, one 32-query word each: a lane writes the queries of its word
+        // after those of the lanes before it.  The 256 queries of this workgroup are neighbours
+        // in every list, so a store instruction touches one short run of addresses per block.
         int32_t* qs = ql + (int64_t)s * R;
-        for_each_entry(rows0, rows, k, tid, [&](int r, int b) {
-            b -= lo;
-            if (!(b >= 0 && b < nblk && b + lo < (t0 + r) / B)) return;
-            const int half = r >> 7, w = (r >> 5) & 3;
-            const uint4 m = *reinterpret_cast<const uint4*>(&mask[b * kWords + 4 * half]);
-            const uint32_t below = (1u << (r & 31)) - 1u;
-            const int rank = __popc(m.x & (w > 0 ? ~0u : below)) +
-                             (w >= 1 ? __popc(m.y & (w > 1 ? ~0u : below)) : 0) +
-                             (w >= 2 ? __popc(m.z & (w > 2 ? ~0u : below)) : 0) +
-                             (w >= 3 ? __popc(m.w & below) : 0);
-            const int pos = start[half * kRange + b] + rank;
-            // a routing that breaks the contract (repeats, too many kept blocks) must not write
-            // outside the slice's lists
-            if ((int64_t)pos < R) qs[pos] = t0 + r;
-        });
+        const int lane8 = tid & 7;
+        for (int b = tid >> 3; b < nblk; b += 256 / 8) {
+            uint32_t word = mask[b * kWords + lane8];
+            const int cnt = __popc(word);
+            int incl = cnt;
+#pragma unroll
+            for (int o = 1; o < 8; o <<= 1) {
+                const int up = __shfl_up(incl, o, 8);
+                if (lane8 >= o) incl += up;
+            }
+            int64_t pos = (int64_t)start[b] + (incl - cnt);
+            while (word) {
+                // a routing that breaks the contract (repeats, too many kept blocks) must not
+                // write outside the slice's lists
+                if (pos < R) qs[pos] = t0 + 32 * lane8 + (__ffs(word) - 1);
+                ++pos;
+                word &= word - 1u;
+            }
+        }
     }
 }
 
