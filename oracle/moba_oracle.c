@@ -14,7 +14,8 @@
  *     softmax(q K_S^T / sqrt(d)) V_S over the selected tokens S.
  *   - Appendix B (Key Convolution Design): k'_t = k_t + SiLU(sum_l W_l * k_{t-l}),
  *     depthwise, causal (terms with t-l < 0 are dropped), applied before the
- *     centroids and before attention.
+ *     centroids and before attention; its backward (gradient of K' to K and to the
+ *     kernel weights) is the chain rule through that formula.
  *   - Appendix C.3 (backward): D = rowsum(dO o O), P = exp(S - L),
  *     dV = P^T dO, dP = dO V^T, dS = P o (dP - D), dQ = dS K, dK = dS^T Q,
  *     with the 1/sqrt(d) factor of Section 2 restored on S, dQ and dK.
@@ -27,7 +28,9 @@
  *   - routing is an input of attention and is not differentiated;
  *   - lse is the natural log of the sum of exp of the scaled logits;
  *   - the convolved key is rounded once to the I/O type and that rounded tensor
- *     feeds both the centroids and attention; centroids are stored as fp32.
+ *     feeds both the centroids and attention; centroids are stored as fp32;
+ *   - in the convolution's backward that rounding is the identity, and the weight
+ *     gradient is summed over the batch (the weights are per head and channel).
  *
  * All arithmetic is binary64.  Tensors are row-major [bh, N, d] with
  * bh = batch*heads flattened (head index = slice % heads).
@@ -90,6 +93,49 @@ void oracle_key_conv(const double *K, const double *w, double *Kp,
                 Ps[(int64_t)t * d + c] = round_io(Ks[(int64_t)t * d + c] + silu, round_mode);
             }
     }
+}
+
+/* Backward of the key convolution (Appendix B: the gradients of the attention go back through
+ * the convolution to the token-level keys and to the kernel weights).  With
+ * a[t][c] = sum_{l<W, t-l>=0} w[h][c][l] K[t-l][c] and K' = K + SiLU(a) (the rounding of K' to
+ * the storage type is treated as the identity), G = dL/dK':
+ *   g[t][c]   = G[t][c] * SiLU'(a[t][c]),   SiLU'(x) = s(x) (1 + x (1 - s(x))),  s = sigmoid
+ *   dK[t][c]  = G[t][c] + sum_{l<W, t+l<N} w[h][c][l] g[t+l][c]
+ *   dw[h][c][l] = sum over the slices of head h and over t >= l of  g[t][c] K[t-l][c]
+ * K, G, dK: [bh, N, d];  w, dw: [heads, d, W] (the weights are shared across the batch). */
+void oracle_key_conv_bwd(const double *K, const double *w, const double *G, double *dK, double *dw,
+                         int bh, int heads, int N, int d, int W)
+{
+    for (int64_t i = 0; i < (int64_t)heads * d * W; ++i) dw[i] = 0.0;
+    double *g = (double *)malloc(sizeof(double) * (size_t)N * d);
+    for (int s = 0; s < bh; ++s) {
+        const double *Ks = K + (int64_t)s * N * d, *Gs = G + (int64_t)s * N * d;
+        double *dKs = dK + (int64_t)s * N * d;
+        const double *ws = w + (int64_t)(s % heads) * d * W;
+        double *dws = dw + (int64_t)(s % heads) * d * W;
+        for (int t = 0; t < N; ++t)
+            for (int c = 0; c < d; ++c) {
+                double a = 0.0;
+                for (int l = 0; l < W; ++l)
+                    if (t - l >= 0) a += ws[c * W + l] * Ks[(int64_t)(t - l) * d + c];
+                double sg = 1.0 / (1.0 + exp(-a));
+                g[(int64_t)t * d + c] = Gs[(int64_t)t * d + c] * sg * (1.0 + a * (1.0 - sg));
+            }
+        for (int t = 0; t < N; ++t)
+            for (int c = 0; c < d; ++c) {
+                double acc = Gs[(int64_t)t * d + c];
+                for (int l = 0; l < W; ++l)
+                    if (t + l < N) acc += ws[c * W + l] * g[(int64_t)(t + l) * d + c];
+                dKs[(int64_t)t * d + c] = acc;
+            }
+        for (int c = 0; c < d; ++c)
+            for (int l = 0; l < W; ++l) {
+                double acc = 0.0;
+                for (int t = l; t < N; ++t) acc += g[(int64_t)t * d + c] * Ks[(int64_t)(t - l) * d + c];
+                dws[c * W + l] += acc;
+            }
+    }
+    free(g);
 }
 
 /* ---------- Section 2: centroids -------------------------------------------- */

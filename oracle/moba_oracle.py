@@ -97,6 +97,20 @@ def key_conv(K, w, heads, round_mode):
     return Kp
 
 
+def key_conv_bwd(K, w, G, heads):
+    """Appendix B, backward: G = dL/dK' [bh,N,d] -> (dL/dK [bh,N,d], dL/dw [heads,d,W]); the
+    rounding of K' to the storage type is taken as the identity."""
+    K, pK = _f64(K)
+    w, pw = _f64(w)
+    G, pG = _f64(G)
+    bh, N, d = K.shape
+    assert w.shape[0] == heads and w.shape[1] == d and G.shape == K.shape
+    dK, pdK = _out(K.shape)
+    dw, pdw = _out(w.shape)
+    _L().oracle_key_conv_bwd(pK, pw, pG, pdK, pdw, bh, heads, N, d, w.shape[2])
+    return dK, dw
+
+
 def centroids(K, B):
     """Section 2.  Mean key of each block, stored as fp32 values -> [bh, n, d]."""
     K, pK = _f64(K)

@@ -305,6 +305,57 @@ def test_conv_is_causal_and_rounds_to_io_type(oracle):
     np.testing.assert_array_equal(t, r)                # already bf16 values
 
 
+@pytest.mark.parametrize("W", [1, 3, 4, 5])
+def test_conv_backward_matches_torch_autograd(oracle, W):
+    """Appendix B, backward through the convolution: dK and dw against autograd on the
+    library formulation (left-padded depthwise conv1d + SiLU + residual), weights shared
+    across the batch."""
+    N, d, heads, batch = 37, 6, 2, 3
+    K = RNG(60 + W).standard_normal((batch * heads, N, d))
+    w = RNG(70 + W).standard_normal((heads, d, W)) * 0.5
+    G = RNG(80 + W).standard_normal((batch * heads, N, d))
+    dK, dw = oracle.key_conv_bwd(K, w, G, heads)
+    Kt = torch.from_numpy(K).requires_grad_(True)
+    wt = torch.from_numpy(w).requires_grad_(True)
+    loss = 0.0
+    for s in range(batch * heads):
+        x = Kt[s].T[None]                                             # [1, d, N]
+        y = torch.nn.functional.conv1d(torch.nn.functional.pad(x, (W - 1, 0)),
+                                       wt[s % heads].flip(-1)[:, None, :], groups=d)
+        loss = loss + ((x + torch.nn.functional.silu(y))[0].T * torch.from_numpy(G[s])).sum()
+    loss.backward()
+    np.testing.assert_allclose(dK, Kt.grad.numpy(), atol=1e-11)
+    np.testing.assert_allclose(dw, wt.grad.numpy(), atol=1e-10)
+
+
+def test_conv_backward_finite_differences_and_closed_forms(oracle):
+    N, d, heads, W = 12, 3, 2, 3
+    K = RNG(90).standard_normal((heads, N, d))
+    w = RNG(91).standard_normal((heads, d, W)) * 0.7
+    G = RNG(92).standard_normal((heads, N, d))
+    dK, dw = oracle.key_conv_bwd(K, w, G, heads)
+    f = lambda K_, w_: (oracle.key_conv(K_, w_, heads, oracle.ROUND_NONE) * G).sum()
+    eps = 1e-6
+    for idx in [(0, 0, 0), (1, 5, 2), (0, N - 1, 1), (1, N - 2, 0)]:     # incl. the last rows
+        Kp, Km = K.copy(), K.copy()
+        Kp[idx] += eps
+        Km[idx] -= eps
+        assert abs((f(Kp, w) - f(Km, w)) / (2 * eps) - dK[idx]) < 1e-7
+    for idx in [(0, 0, 0), (1, 2, 2), (0, 1, 1)]:
+        wp, wm = w.copy(), w.copy()
+        wp[idx] += eps
+        wm[idx] -= eps
+        assert abs((f(K, wp) - f(K, wm)) / (2 * eps) - dw[idx]) < 1e-7
+    # w = 0: a = 0, SiLU'(0) = 1/2, so dK = G and dw[l] = sum_t G[t]/2 * K[t-l]
+    dK0, dw0 = oracle.key_conv_bwd(K, np.zeros_like(w), G, heads)
+    np.testing.assert_allclose(dK0, G, atol=1e-14)
+    for l in range(W):
+        np.testing.assert_allclose(dw0[:, :, l], 0.5 * (G[:, l:] * K[:, :N - l]).sum(1), atol=1e-13)
+    # G = 0: no gradient at all
+    z = oracle.key_conv_bwd(K, w, np.zeros_like(G), heads)
+    assert not z[0].any() and not z[1].any()
+
+
 def test_bf16_rounding_matches_torch(oracle):
     x = torch.randn(200000, generator=torch.Generator().manual_seed(1)) * 37.0
     x[:1000] *= 1e-38                                   # reach the subnormal range
