@@ -234,6 +234,28 @@ def main():
         "roofline": roofline,
         "hbm_stages": hbm,
     }
+    if w.conv_width:
+        # Not part of a step (the benchmark workloads with a convolution are forward-only): the
+        # convolution's backward, timed on its own with a synthetic dK_eff.  HBM-bound: it has
+        # to read K and dK_eff and write dK.
+        G = torch.randn(d["K"].shape, device=dev, dtype=torch.float32).to(d["K"].dtype)
+        nws = __import__("ctypes").c_size_t(0)
+        moba.lib().moba_key_conv_backward_workspace(__import__("ctypes").byref(sh.c()),
+                                                    __import__("ctypes").byref(nws))
+        ws_cb = torch.empty(nws.value, dtype=torch.uint8, device=dev)
+        for _ in range(2):
+            moba.key_conv_backward(sh, d["K"], d["conv_w"], G, ws=ws_cb)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(5):
+            moba.key_conv_backward(sh, d["K"], d["conv_w"], G, ws=ws_cb)
+        e1.record()
+        torch.cuda.synchronize()
+        cb_ms = e0.elapsed_time(e1) / 5
+        cb_bytes = 3 * w.bh * w.N * w.d * es
+        out["key_conv_backward"] = {"ms": cb_ms, "GBs": cb_bytes / (cb_ms * 1e-3) / 1e9,
+                                    "frac_of_hbm_peak": cb_bytes / (cb_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
     if a.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read, 1 GiB written
         dst = torch.empty_like(src)

@@ -79,6 +79,24 @@ int moba_centroids(const moba_shape* shape, const void* K, const float* conv_w,
                    void* K_eff, float* centroids, void* stream);
 
 /*
+ * Backward of the key convolution (Appendix B: training sends the gradients through the
+ * convolution to the token-level keys and to the kernel weights).  The rounding of K_eff to
+ * dtype is taken as the identity.  With a_t = sum_l W_l * k_{t-l}, g_t = dK_eff_t * SiLU'(a_t):
+ *   dK_t = dK_eff_t + sum_{l, t+l<N} W_l * g_{t+l},   dconv_w[h][c][l] = sum_{batch, t>=l} g_t k_{t-l}
+ *   K        in   [b,h,N,d] dtype: the keys the convolution was applied to
+ *   conv_w   in   [heads,d,W] fp32
+ *   dK_eff   in   [b,h,N,d] dtype: gradient with respect to K_eff (dK of moba_backward)
+ *   dK       out  [b,h,N,d] dtype: gradient with respect to K; must not overlap dK_eff
+ *   dconv_w  out  [heads,d,W] fp32, summed over the batch in a fixed order
+ *   ws            at least moba_key_conv_backward_workspace bytes
+ * conv_width must be at least 1.
+ */
+int moba_key_conv_backward_workspace(const moba_shape* shape, size_t* ws_bytes);
+int moba_key_conv_backward(const moba_shape* shape, const void* K, const float* conv_w,
+                           const void* dK_eff, void* dK, float* dconv_w, void* ws,
+                           size_t ws_bytes, void* stream);
+
+/*
  * Gate scores and causal top-k (Section 2; Appendix C.1, top-k selection algorithm)
  * followed by the key-block-major query lists (Appendix C.1, varlen reformatting).
  * The N x n score matrix is never written to memory.

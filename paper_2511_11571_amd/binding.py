@@ -74,7 +74,8 @@ def lib():
         L.moba_last_hip_error.restype = ctypes.c_int
         for name in ("moba_routes_per_slice", "moba_workspace_bytes", "moba_centroids", "moba_topk",
                      "moba_build_lists", "moba_forward", "moba_backward", "moba_backward_parts",
-                     "moba_profile_begin", "moba_profile_end"):
+                     "moba_profile_begin", "moba_profile_end", "moba_key_conv_backward",
+                     "moba_key_conv_backward_workspace"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -123,6 +124,23 @@ def centroids(shape: Shape, K, conv_w=None, K_eff=None, out=None):
     return (K_eff if K_eff is not None else K), out
 
 
+
+
+def key_conv_backward(shape: Shape, K, conv_w, dK_eff, ws=None):
+    """Backward of the key convolution -> (dK [b,h,N,d] in the I/O type, dconv_w [heads,d,W] fp32)."""
+    assert K.is_contiguous() and dK_eff.is_contiguous() and K.dtype == shape.torch_dtype
+    assert dK_eff.dtype == shape.torch_dtype and conv_w.is_contiguous() and conv_w.dtype == torch.float32
+    if ws is None:
+        n = ctypes.c_size_t(0)
+        _check(lib().moba_key_conv_backward_workspace(ctypes.byref(shape.c()), ctypes.byref(n)),
+               "moba_key_conv_backward_workspace")
+        ws = _ws(n.value, K)
+    dK = torch.empty_like(K)
+    dw = torch.empty_like(conv_w)
+    _check(lib().moba_key_conv_backward(ctypes.byref(shape.c()), _p(K), _p(conv_w), _p(dK_eff), _p(dK),
+                                        _p(dw), _p(ws), ctypes.c_size_t(ws.numel()), _stream()),
+           "moba_key_conv_backward")
+    return dK, dw
 
 
 def _list_buffers(shape, like):

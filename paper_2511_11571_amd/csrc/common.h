@@ -173,6 +173,9 @@ struct ProfileScope {
 // launchers (one translation unit each); every one returns a hipError_t
 hipError_t launch_centroids(const Dims& s, const void* K, const float* w, void* Keff,
                             float* cent, hipStream_t st);
+hipError_t launch_conv_backward(const Dims& s, const void* K, const float* w, const void* G, void* dK,
+                                float* dw, void* ws, hipStream_t st);
+size_t conv_bwd_ws_bytes(const Dims& s);
 hipError_t launch_topk_reference(const Dims& s, const void* Q, const float* cent, int32_t* idx,
                                  hipStream_t st);
 hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, int32_t* ql,

@@ -190,6 +190,28 @@ int moba_centroids(const moba_shape* shape, const void* K, const float* conv_w, 
     return hip_status(launch_centroids(d, K, conv_w, K_eff, centroids, (hipStream_t)stream));
 }
 
+int moba_key_conv_backward_workspace(const moba_shape* shape, size_t* ws_bytes)
+{
+    Dims d;
+    const int st = make_dims(shape, d);
+    if (st != MOBA_OK) return st;
+    if (!ws_bytes || d.W < 1) return MOBA_EINVAL;
+    *ws_bytes = align256(conv_bwd_ws_bytes(d)) + 256;
+    return MOBA_OK;
+}
+
+int moba_key_conv_backward(const moba_shape* shape, const void* K, const float* conv_w,
+                           const void* dK_eff, void* dK, float* dconv_w, void* ws, size_t ws_bytes,
+                           void* stream)
+{
+    Dims d;
+    const int st = make_dims(shape, d);
+    if (st != MOBA_OK) return st;
+    if (d.W < 1 || !K || !conv_w || !dK_eff || !dK || !dconv_w || dK == dK_eff) return MOBA_EINVAL;
+    if (!ws || ws_bytes < align256(conv_bwd_ws_bytes(d)) + 256) return MOBA_EWORKSPACE;
+    return hip_status(launch_conv_backward(d, K, conv_w, dK_eff, dK, dconv_w, ws, (hipStream_t)stream));
+}
+
 int moba_build_lists(const moba_shape* shape, const int32_t* topk_idx, int32_t* blk_off,
                      int32_t* blk_q, void* ws, size_t ws_bytes, void* stream)
 {

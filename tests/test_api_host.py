@@ -80,6 +80,14 @@ def test_null_pointers_and_short_workspace(lib):
                              one, one, z, one, big, z) == -1
     assert lib.moba_backward(ctypes.byref(sh), one, one, one, one, one, one, one, one, one,
                              one, one, one, one, ctypes.c_size_t(16), z) == -3
+    n = ctypes.c_size_t(0)
+    assert lib.moba_key_conv_backward_workspace(ctypes.byref(sh), ctypes.byref(n)) == -1       # no conv
+    assert lib.moba_key_conv_backward_workspace(ctypes.byref(conv), ctypes.byref(n)) == 0 and n.value > 0
+    assert lib.moba_key_conv_backward(ctypes.byref(sh), one, one, one, one, one, one, big, z) == -1
+    assert lib.moba_key_conv_backward(ctypes.byref(conv), one, one, z, one, one, one, big, z) == -1
+    assert lib.moba_key_conv_backward(ctypes.byref(conv), one, one, one, one, one, one, big, z) == -1  # in place
+    two = ctypes.c_void_p(512)
+    assert lib.moba_key_conv_backward(ctypes.byref(conv), one, one, one, two, one, one, ctypes.c_size_t(8), z) == -3
     many = _shape(seqlen=32 * 5000).c()
     assert lib.moba_topk(ctypes.byref(many), one, one, one, one, one, one, big, z) == -2
 

@@ -181,3 +181,22 @@ def test_config4_conv_long_sequence(oracle):
     rng = np.random.default_rng(4)
     for s in (0, 11):
         print(w.name, s, check_slice(oracle, w, t, out, s, 512, [], rng), flush=True)
+
+
+def test_config4_conv_backward(oracle):
+    """Backward of the key convolution at the config-4 shape (1024 chunks of 128 rows per slice,
+    row offsets beyond 2^31 bytes): two whole slices against the oracle.  The weights are per
+    head and config 4 has batch 1, so every head's dw comes from exactly one slice."""
+    w = workloads.CONFIGS[4]
+    t = workloads.generate(w)
+    G = torch.randn(t["K"].shape, generator=torch.Generator().manual_seed(44)).to(t["K"].dtype)
+    dK, dw = moba.key_conv_backward(shape_of(w), t["K"].cuda(), t["conv_w"].cuda(), G.cuda())
+    torch.cuda.synchronize()
+    for s in (0, 13):
+        K1 = workloads.to_f64(t["K"][:, s:s + 1])
+        G1 = workloads.to_f64(G[:, s:s + 1])
+        ref_dK, ref_dw = oracle.key_conv_bwd(K1, t["conv_w"][s:s + 1].double().numpy(), G1, 1)
+        got = slice64(dK, s, w.heads)
+        assert (np.abs(got - ref_dK) <= 2.0 ** -8 * np.abs(ref_dK) + 1e-5).all()
+        assert parity.rel_l2(dw[s:s + 1].double().cpu().numpy(), ref_dw) < 1e-5
+        print(w.name, "conv backward, slice", s, "ok", flush=True)

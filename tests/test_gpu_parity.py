@@ -112,6 +112,31 @@ def test_key_conv_and_centroids(oracle, dtype, d, width):
         assert parity.max_abs(np64(cent), oracle.centroids(Kp, w.B)) < 2e-5
 
 
+@pytest.mark.parametrize("dtype,d,width,N", [("bf16", 64, 4, 640), ("bf16", 128, 3, 320), ("bf16", 64, 1, 256),
+                                             ("bf16", 64, 8, 416), ("f32", 64, 5, 640), ("f32", 128, 2, 96)])
+def test_key_conv_backward(oracle, dtype, d, width, N):
+    """dK and dw of the convolution's backward against the oracle on the same inputs; N covers
+    several 128-row chunks with a ragged last one, and a sequence shorter than a chunk."""
+    w = W("convbwd", 2, 3, N, d, 32, 2, dtype=dtype, conv_width=width, seed=130 + width)
+    t = workloads.generate(w)
+    Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
+    G = t["dO"]                                     # any tensor of the right shape and type
+    dK, dw = moba.key_conv_backward(shape_of(w), t["K"].cuda(), t["conv_w"].cuda(), G.cuda())
+    ref_dK, ref_dw = oracle.key_conv_bwd(K, t["conv_w"].double().numpy(), workloads.to_f64(G), w.heads)
+    got = np64(dK)
+    if dtype == "bf16":         # fp32 arithmetic, one rounding to bf16 at the end
+        assert (np.abs(got - ref_dK) <= 2.0 ** -8 * np.abs(ref_dK) + 1e-5).all()
+    else:
+        assert (np.abs(got - ref_dK) <= 1e-5 * (1 + np.abs(ref_dK))).all()
+    assert dw.dtype == torch.float32 and dw.shape == t["conv_w"].shape
+    assert parity.rel_l2(dw.double().cpu().numpy(), ref_dw) < 1e-5
+    # bit-reproducible (fixed summation order), and dK == dK_eff where the weights vanish
+    dK2, dw2 = moba.key_conv_backward(shape_of(w), t["K"].cuda(), t["conv_w"].cuda(), G.cuda())
+    assert torch.equal(dK, dK2) and torch.equal(dw, dw2)
+    dK0, _ = moba.key_conv_backward(shape_of(w), t["K"].cuda(), torch.zeros_like(t["conv_w"]).cuda(), G.cuda())
+    assert torch.equal(dK0.cpu(), G)
+
+
 # ------------------------------------------------------------------ routing
 
 @pytest.mark.parametrize("flags", FLAGS)
