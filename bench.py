@@ -43,8 +43,13 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5")
+    ap.add_argument("--shape", default="",
+                    help="instead of --config: batch,heads,N,d,B,k[,fwd] (bf16, no conv), e.g. the "
+                         "paper's latency sweep 2,16,65536,64,128,8")
     ap.add_argument("--reference-kernels", action="store_true",
                     help="force the plain (non-MFMA) kernels")
+    ap.add_argument("--attention", choices=["auto", "tiles", "keymajor"], default="auto",
+                    help="force the query-tile or the key-block-major attention kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB device to device once (a kernel of "
@@ -123,9 +128,16 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     w = workloads.CONFIGS[a.config]
+    if a.shape:
+        f = a.shape.split(",")
+        b_, h_, N_, d_, B_, k_ = (int(x) for x in f[:6])
+        w = workloads.Workload("shape_%s" % a.shape.replace(",", "_"), b_, h_, N_, d_, B_, k_,
+                               backward=not (len(f) > 6 and f[6] == "fwd"), seed=9000)
+        a.config = 0
     t = workloads.generate(w)
     d = {k: (v.cuda() if v is not None else None) for k, v in t.items()}
     flags = binding.FLAG_REFERENCE_KERNELS if a.reference_kernels else 0
+    flags |= {"auto": 0, "tiles": binding.FLAG_QUERY_TILES, "keymajor": binding.FLAG_KEY_MAJOR}[a.attention]
     sh = moba.Shape(w.batch, w.heads, w.N, w.d, w.B, w.k, w.conv_width,
                     binding.BF16 if w.dtype == "bf16" else binding.F32, 0.0, flags)
     R = moba.routes_per_slice(sh)
@@ -227,7 +239,7 @@ def main():
             w.name, w.batch, w.heads, w.N, w.d, w.B, w.k,
             ", key conv W=%d" % w.conv_width if w.conv_width else "",
             "forward+backward" if w.backward else "forward"),
-            "kernels": "plain" if a.reference_kernels else "default",
+            "kernels": "plain" if a.reference_kernels else "default", "attention": a.attention,
             "attended_pairs": pairs, "fwd_gflop": fwd_flop / 1e9, "bwd_gflop": bwd_flop / 1e9},
         "stage_ms": stage_ms,
         "kernel_ms": kernel_ms,

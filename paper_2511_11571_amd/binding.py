@@ -16,6 +16,8 @@ _LIB_PATH = os.path.join(_PKG, "libmoba.so")
 
 F32, BF16 = 0, 1
 FLAG_REFERENCE_KERNELS = 1
+FLAG_KEY_MAJOR = 2
+FLAG_QUERY_TILES = 4
 
 
 class MobaError(RuntimeError):

@@ -1,0 +1,371 @@
+// MoBA forward, key-block major, for sparse routing (paper Section 4.2, forward pass with
+// gather-and-densify: one logical key block at a time, the queries routed to it gathered into
+// dense tiles).  The query-tile kernel of attn_fwd_mfma.hip needs a 256-query tile to meet a key
+// block with many of its rows; with few kept blocks out of very many (long sequences) a tile
+// meets a block with one or two rows and the work per (query, block) pair explodes.  Here a
+// workgroup owns up to 128 keys of one key block -- their K and V MFMA operands stay in
+// registers for the whole walk -- and walks the list of ALL queries that kept the block (then
+// the block's own queries, causally masked), 32 queries per step and wave: the tiles are dense
+// whatever the sequence length, and nothing but the gathered query rows is read in the loop.
+//
+// A query's softmax spans several key blocks, i.e. several workgroups.  As in the paper's
+// forward each (query, block) pair therefore produces a partial result -- the local softmax
+// reference m, the sum l of exp(s - m), and sum p v / l rounded to bf16 -- and a second kernel
+// merges a query's partials (Section 4.2: the partial outputs are combined with the
+// log-sum-exp weights).  The partials of query t lie together, [t][e][c] for its e-th kept
+// block (e = k: own block) and 128-key part c, so the merge streams them; the walk finds e by
+// looking j up in the query's (ascending) row of kept blocks.  No atomics anywhere; results are
+// bit-reproducible.
+#include <type_traits>
+
+#include "mfma.h"
+
+namespace moba {
+
+typedef uint32_t kmvec4_t __attribute__((ext_vector_type(4)));
+
+template <int D>
+struct KmCfg {
+    static constexpr int NW = 4;
+    static constexpr int NT = NW * kWave;
+    static constexpr int SB = D * 2 + 16;              // bytes per parked row: the row, then (t, e)
+    static constexpr int MT = D / 16;
+    static constexpr int KS = D / 32;
+    static constexpr int CPR = D / 8;                  // 16-byte chunks per row = lanes per gathered row
+    static constexpr int RPI = kWave / CPR;            // rows per gather instruction
+    static constexpr int NI = 32 / RPI;                // gather instructions per step
+    static constexpr size_t LDS = (size_t)NW * 32 * SB;
+};
+
+// keys per workgroup: the whole block up to 128 keys, else 128-key parts
+__host__ __device__ inline int km_part_keys(int B) { return B <= kKeyMajorPart ? B : kKeyMajorPart; }
+
+// NG: 32-key groups per workgroup; KC: a query's row of kept blocks is searched CPR entries at a
+// time, KC times (k <= KC * CPR)
+template <int D, int NG, int KC>
+__global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Ka, const bf16_t* __restrict__ Vt,
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ off, const int32_t* __restrict__ ql,
+    bf16_t* __restrict__ PO, float* __restrict__ Pml, int N, int B, int n, int k, int nsub,
+    float scale, int64_t R, int bh)
+{
+    using C = KmCfg<D>;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int m16 = lane & 15, g = lane >> 4;
+    unsigned char* stQ = smem + (size_t)wave * 32 * C::SB;
+
+    int s, u;                                               // slice, (key block, part)
+    if (!schedule(blockIdx.x, bh, n * nsub, s, u)) return;
+    const int j = u / nsub, c = u - j * nsub;
+    const int own_first = c * (32 * NG);                    // first key of the part inside the block
+    const int64_t sbase = (int64_t)s * N;
+    const float c2 = scale * kLog2e;
+    const int32_t* os = off + (int64_t)s * (n + 1);
+    const int32_t* qs = ql + (int64_t)s * R;
+    const int lo = os[j], nlist = os[j + 1] - lo;
+    const int own0 = j * B + own_first;                     // own queries that see keys of this part
+    const int total = nlist + (B - own_first);
+    const char* Qg = reinterpret_cast<const char*>(Q + sbase * D);
+    const uint32_t vlane = (uint32_t)lane * 16u;
+
+    // the part's keys and values as MFMA operands, resident for the whole walk
+    Frag ka[NG][2][C::KS], va[NG][C::MT];
+    {
+        const char* Kag = reinterpret_cast<const char*>(Ka + (sbase + own0) * D);
+        const char* Vtg = reinterpret_cast<const char*>(Vt + (sbase + own0) * D);
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int ks = 0; ks < C::KS; ++ks)
+                    ka[gi][mt][ks].q = *reinterpret_cast<const uint4*>(Kag + gi * (64 * D) + vlane +
+                                                                       (mt * C::KS + ks) * 1024);
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt)
+                va[gi][mt].q = *reinterpret_cast<const uint4*>(Vtg + gi * (64 * D) + vlane + mt * 1024);
+        }
+    }
+
+    // every load of the walk is unconditional and from an address that is always valid (a load
+    // inside a branch is waited for at the end of the branch)
+    const int32_t* lsrc = nlist > 0 ? qs + lo : os;
+    const int llast = max(nlist - 1, 0);
+    auto query_at = [&](int a) {
+        const int listed = lsrc[min(a, llast)];
+        const int t = a < nlist ? listed : own0 + (a - nlist);
+        return a >= total ? own0 : t;
+    };
+    const int grow = lane / C::CPR, lcol = lane % C::CPR;
+    const uint32_t gcol = (uint32_t)lcol * 16u;
+    auto ids = [&](int a0, int (&t)[C::NI]) {
+#pragma unroll
+        for (int i = 0; i < C::NI; ++i) t[i] = query_at(a0 + C::RPI * i + grow);
+    };
+    auto fetch = [&](const int (&t)[C::NI], kmvec4_t (&qr)[C::NI]) {
+#pragma unroll
+        for (int i = 0; i < C::NI; ++i)
+            qr[i] = *reinterpret_cast<const kmvec4_t*>(Qg + (uint32_t)t[i] * (uint32_t)(2 * D) + gcol);
+    };
+    // the kept blocks of the gathered queries, CPR entries per row and instruction
+    const int32_t* isrc = k > 0 ? idx + sbase * k : os;
+    const int klast = max(k - 1, 0);
+    auto lookup = [&](const int (&t)[C::NI], int (&ev)[C::NI][KC]) {
+#pragma unroll
+        for (int i = 0; i < C::NI; ++i)
+#pragma unroll
+            for (int cc = 0; cc < KC; ++cc)
+                ev[i][cc] = isrc[(int64_t)t[i] * k + min(lcol + C::CPR * cc, klast)];
+    };
+    // Two steps of gathered rows are in flight while a third is worked on: t (the rows), qr
+    // (their 16-byte pieces) and ev (their kept blocks) of step i sit in buffer i % 2, the rows
+    // of step i + 2 in tN.  The loads for tN go out before the gather of the step before it, so
+    // that waiting for them (loads complete in order) leaves that gather in flight.
+    const int stride = 32 * C::NW;
+    int t0[C::NI], t1[C::NI], tN[C::NI], ev0[C::NI][KC], ev1[C::NI][KC];
+    kmvec4_t qr0[C::NI], qr1[C::NI];
+    ids(32 * wave, t0);
+    ids(32 * wave + stride, t1);
+    ids(32 * wave + 2 * stride, tN);
+    fetch(t0, qr0);
+    lookup(t0, ev0);
+    fetch(t1, qr1);
+    lookup(t1, ev1);
+    const uint32_t park = (uint32_t)grow * C::SB + gcol;
+    const uint32_t arow = (uint32_t)m16 * C::SB + 16u * g;
+    const int64_t slots = (int64_t)(k + 1) * nsub;          // partials per query
+
+    auto step = [&](int a0, int (&tA)[C::NI], kmvec4_t (&qr)[C::NI], int (&ev)[C::NI][KC]) {
+        // park the gathered rows, t behind each, and e from the lane that finds j in the query's
+        // row of kept blocks (own rows: e = k)
+#pragma unroll
+        for (int i = 0; i < C::NI; ++i) {
+            *reinterpret_cast<kmvec4_t*>(stQ + park + i * C::RPI * C::SB) = qr[i];
+            int e = -1;
+#pragma unroll
+            for (int cc = 0; cc < KC; ++cc) {
+                const int ent = lcol + C::CPR * cc;
+                if (ev[i][cc] == j && ent < k) e = ent;
+            }
+            if (a0 + C::RPI * i + grow >= nlist) e = lcol == 0 ? k : -1;
+            // t always, e where found: lists that do not match the rows of kept blocks give a
+            // wrong result, never an address outside the query's partials
+            unsigned char* note = stQ + (grow + i * C::RPI) * C::SB + 2 * D;
+            if (lcol == 0) *reinterpret_cast<int*>(note) = tA[i];
+            if (e >= 0) *reinterpret_cast<int*>(note + 4) = e;
+        }
+#pragma unroll
+        for (int i = 0; i < C::NI; ++i) tA[i] = tN[i];
+        ids(a0 + 3 * stride, tN);
+        fetch(tA, qr);
+        lookup(tA, ev);
+        __builtin_amdgcn_wave_barrier();
+        const bool masked = a0 + 32 > nlist;                       // the step holds own rows
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            Frag qb[C::KS];
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ++ks)
+                qb[ks].q = *reinterpret_cast<const uint4*>(stQ + arow + qt * 16 * C::SB + 64 * ks);
+            const int2 te = *reinterpret_cast<const int2*>(stQ + (16 * qt + m16) * C::SB + 2 * D);
+            const int av = a0 + 16 * qt + m16;                     // this lane's row of the walk
+            // raw scores of the row against the part's keys: x[gi][4 mt + i] is key
+            // 32 gi + 16 mt + 4 g + i of the part
+            float x[NG][8];
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < C::KS; ++ks) sc = mfma16(ka[gi][mt][ks], qb[ks], sc);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) x[gi][4 * mt + i] = sc[i];
+                }
+            if (masked) {                                          // own row r sees keys 0 .. r of the part
+                const int r = av - nlist;
+#pragma unroll
+                for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (r >= 0 && 32 * gi + 16 * (e >> 2) + 4 * g + (e & 3) > r) x[gi][e] = -INFINITY;
+            }
+            float mref = -INFINITY;
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) mref = fmaxf(mref, x[gi][e]);
+            mref = fmaxf(mref, __shfl_xor(mref, 16, kWave));
+            mref = fmaxf(mref, __shfl_xor(mref, 32, kWave));
+            mref *= c2;                                            // c2 > 0: the maximum commutes
+            if (av >= total) mref = 0.f;                           // no such row: keep the arithmetic finite
+            f32x4_t o[C::MT];
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt) o[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            float l = 0.f;
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    x[gi][e] = fast_exp2(fmaf(x[gi][e], c2, -mref));
+                    l += x[gi][e];
+                }
+                Frag pb;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pb.u[e] = pack2(x[gi][2 * e], x[gi][2 * e + 1]);
+#pragma unroll
+                for (int mt = 0; mt < C::MT; ++mt) o[mt] = mfma16(va[gi][mt], pb, o[mt]);
+            }
+            l += __shfl_xor(l, 16, kWave);
+            l += __shfl_xor(l, 32, kWave);
+            // the partial: this lane holds D/4 consecutive channels of the row
+            if (av < total) {
+                const int e = min(max(te.y, 0), k);
+                const int64_t prow = (sbase + te.x) * slots + (int64_t)e * nsub + c;
+                const float inv = 1.f / l;
+                uint32_t w[C::MT * 2];
+#pragma unroll
+                for (int mt = 0; mt < C::MT; ++mt) {
+                    w[2 * mt] = pack_bf16x2(o[mt][0] * inv, o[mt][1] * inv);
+                    w[2 * mt + 1] = pack_bf16x2(o[mt][2] * inv, o[mt][3] * inv);
+                }
+                uint4* dst = reinterpret_cast<uint4*>(PO + prow * D + g * (D / 4));
+#pragma unroll
+                for (int q4 = 0; q4 < C::MT / 2; ++q4)
+                    dst[q4] = make_uint4(w[4 * q4], w[4 * q4 + 1], w[4 * q4 + 2], w[4 * q4 + 3]);
+                if (g == 0) *reinterpret_cast<float2*>(Pml + prow * 2) = make_float2(mref, l);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+    for (int a0 = 32 * wave; a0 < total; a0 += 2 * stride) {
+        step(a0, t0, qr0, ev0);
+        if (a0 + stride >= total) break;
+        step(a0 + stride, t1, qr1, ev1);
+    }
+}
+
+// O_t = sum w O_p, w = l_p 2^(m_p - M) / L over the query's partials: all parts of its kept
+// blocks, and the parts of its own block up to its own key; lse_t = (M + log2 L) ln 2.
+// D / 8 lanes per query.
+template <int D>
+__global__ __launch_bounds__(256) void fwd_km_merge_kernel(
+    const int32_t* __restrict__ idx, const bf16_t* __restrict__ PO, const float* __restrict__ Pml,
+    bf16_t* __restrict__ O, float* __restrict__ lse, int N, int B, int k, int nsub, int64_t rows_total)
+{
+    constexpr int G = D / 8;
+    const int64_t row = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;      // s * N + t
+    const int part = threadIdx.x % G;
+    if (row >= rows_total) return;
+    const int t = (int)(row % N);
+    const int own_parts = (t % B) / km_part_keys(B) + 1;
+    const int32_t* irow = idx + row * k;
+    const int64_t p0 = row * (k + 1) * nsub;
+    auto parts_of = [&](int e) { return e == k ? own_parts : (irow[e] < 0 ? 0 : nsub); };
+    float M = -INFINITY;
+    for (int e = 0; e <= k; ++e) {
+        const int np = parts_of(e);
+        for (int c = 0; c < np; ++c) M = fmaxf(M, Pml[(p0 + e * nsub + c) * 2]);
+    }
+    float L = 0.f, acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int e = 0; e <= k; ++e) {
+        const int np = parts_of(e);
+        for (int c = 0; c < np; ++c) {
+            const int64_t pr = p0 + e * nsub + c;
+            const float2 ml = *reinterpret_cast<const float2*>(Pml + pr * 2);
+            const float wgt = ml.y * fast_exp2(ml.x - M);
+            float v[8];
+            Vec8<bf16_t>::load(PO + pr * D + part * 8, v);
+            L += wgt;
+#pragma unroll
+            for (int ch = 0; ch < 8; ++ch) acc[ch] = fmaf(wgt, v[ch], acc[ch]);
+        }
+    }
+    const float inv = 1.f / L;
+#pragma unroll
+    for (int ch = 0; ch < 8; ++ch) acc[ch] *= inv;
+    Vec8<bf16_t>::store(O + row * D + part * 8, acc);
+    if (part == 0) lse[row] = (M + fast_log2(L)) * kLn2;
+}
+
+// ---- workspace: [slot-ordered V][operand-ordered K][partial O: bh*N*(k+1)*parts*D bf16]
+// [partial (m, l): bh*N*(k+1)*parts*2 fp32], each 256-byte aligned
+static size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static size_t km_partials(const Dims& s)
+{
+    return (size_t)s.bh * s.N * (size_t)(s.k + 1) * (size_t)(s.B / km_part_keys(s.B));
+}
+
+size_t forward_km_ws_bytes(const Dims& s)
+{
+    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
+    return 2 * tensor + a256(sizeof(bf16_t) * km_partials(s) * s.D) + a256(sizeof(float) * km_partials(s) * 2);
+}
+
+template <int D, int NG, int KC>
+static hipError_t km_launch3(const Dims& s, const void* Q, const void* Ka, const void* Vt,
+                             const int32_t* idx, const int32_t* off, const int32_t* ql, bf16_t* PO,
+                             float* Pml, void* O, float* lse, hipStream_t st)
+{
+    using C = KmCfg<D>;
+    const int nsub = s.B / km_part_keys(s.B);
+    {
+        ProfileScope timing(MOBA_PROFILE_FORWARD, st);
+        hipLaunchKernelGGL((fwd_km_kernel<D, NG, KC>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
+                           dim3(C::NT), C::LDS, st, (const bf16_t*)Q, (const bf16_t*)Ka, (const bf16_t*)Vt,
+                           idx, off, ql, PO, Pml, s.N, s.B, s.n, s.k, nsub, s.scale, s.R, s.bh);
+    }
+    const int64_t rows = (int64_t)s.bh * s.N;
+    const int rpw = 256 / (D / 8);
+    hipLaunchKernelGGL((fwd_km_merge_kernel<D>), dim3((unsigned)((rows + rpw - 1) / rpw)), dim3(256), 0, st,
+                       idx, PO, Pml, (bf16_t*)O, lse, s.N, s.B, s.k, nsub, rows);
+    return hipGetLastError();
+}
+
+template <int D, int NG, typename... A>
+static hipError_t km_launch2(const Dims& s, A... a)
+{
+    constexpr int CPR = KmCfg<D>::CPR, KCMAX = kKeyMajorMaxTopk / CPR;
+    if (s.k <= CPR) return km_launch3<D, NG, 1>(s, a...);
+    if (s.k <= 2 * CPR) return km_launch3<D, NG, 2>(s, a...);
+    return km_launch3<D, NG, KCMAX>(s, a...);
+}
+
+template <int D, typename... A>
+static hipError_t km_launch(const Dims& s, A... a)
+{
+    switch (km_part_keys(s.B) / 32) {
+        case 1: return km_launch2<D, 1>(s, a...);
+        case 2: return km_launch2<D, 2>(s, a...);
+        case 3: return km_launch2<D, 3>(s, a...);
+        case 4: return km_launch2<D, 4>(s, a...);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_forward_km(const Dims& s, const void* Q, const void* K, const void* V, void* ws,
+                             const int32_t* idx, const int32_t* off, const int32_t* ql, void* O,
+                             float* lse, hipStream_t st)
+{
+    if (s.bh == 0 || s.N == 0) return hipSuccess;
+    if (!key_major_shape(s)) return hipErrorInvalidValue;
+    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
+    char* p = static_cast<char*>(ws);
+    void* Vt = p;
+    p += tensor;
+    void* Ka = p;
+    p += tensor;
+    bf16_t* PO = reinterpret_cast<bf16_t*>(p);
+    p += a256(sizeof(bf16_t) * km_partials(s) * s.D);
+    float* Pml = reinterpret_cast<float*>(p);
+    hipError_t e = launch_slot_major_copy(s, V, Vt, nullptr, st);
+    if (e != hipSuccess) return e;
+    e = launch_operand_copy(s, K, Ka, st);
+    if (e != hipSuccess) return e;
+    return s.D == 64 ? km_launch<64>(s, Q, Ka, Vt, idx, off, ql, PO, Pml, O, lse, st)
+                     : km_launch<128>(s, Q, Ka, Vt, idx, off, ql, PO, Pml, O, lse, st);
+}
+
+}  // namespace moba

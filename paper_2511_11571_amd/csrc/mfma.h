@@ -219,10 +219,36 @@ bool topk_mfma_supported(const Dims& s);
 hipError_t launch_topk_mfma(const Dims& s, const void* Q, const float* cent, int32_t* idx, void* ws,
                             hipStream_t st);
 
+constexpr int kKeyMajorBelowRows = 6;     // rows per (tile, block) visit below which key-major wins
+constexpr int kKeyMajorPart = 128;        // keys a key-major workgroup holds in registers
+constexpr int kKeyMajorMaxTopk = 64;      // longest row of kept blocks the key-major walk searches
+
 // shapes the MFMA kernels cover: bf16 I/O and key blocks made of whole 32-key groups
 inline bool mfma_path(const Dims& s)
 {
     return s.dtype == MOBA_BF16 && s.B % 32 == 0 && !(s.flags & MOBA_FLAG_REFERENCE_KERNELS);
 }
+
+// shapes the key-major kernels cover: blocks of up to 128 keys or of whole 128-key parts
+inline bool key_major_shape(const Dims& s)
+{
+    return mfma_path(s) && (s.B <= kKeyMajorPart || s.B % kKeyMajorPart == 0) && s.k <= kKeyMajorMaxTopk;
+}
+
+// Query-tile or key-major attention?  A tile of T consecutive queries (256 for d = 64, 128 for
+// d = 128) meets a past key block with about T k / n of its rows; the tile kernels need a good
+// part of a 16-row MFMA tile there, the key-major kernels do not care.
+inline bool key_major_path(const Dims& s)
+{
+    if (!key_major_shape(s) || (s.flags & MOBA_FLAG_QUERY_TILES)) return false;
+    if (s.flags & MOBA_FLAG_KEY_MAJOR) return true;
+    const int T = s.D == 64 ? 256 : 128;
+    return (int64_t)T * s.k < (int64_t)kKeyMajorBelowRows * s.n;
+}
+
+size_t forward_km_ws_bytes(const Dims& s);
+hipError_t launch_forward_km(const Dims& s, const void* Q, const void* K, const void* V, void* ws,
+                             const int32_t* idx, const int32_t* off, const int32_t* ql, void* O,
+                             float* lse, hipStream_t st);
 
 }  // namespace moba

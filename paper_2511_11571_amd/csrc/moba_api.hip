@@ -29,7 +29,9 @@ int make_dims(const moba_shape* sh, Dims& d)
     if (sh->block <= 0 || sh->topk < 0 || sh->conv_width < 0) return MOBA_EINVAL;
     if (sh->seqlen % sh->block != 0) return MOBA_EINVAL;
     if (sh->dtype != MOBA_F32 && sh->dtype != MOBA_BF16) return MOBA_EINVAL;
-    if (sh->flags & ~(uint32_t)MOBA_FLAG_REFERENCE_KERNELS) return MOBA_EINVAL;
+    if (sh->flags & ~(uint32_t)(MOBA_FLAG_REFERENCE_KERNELS | MOBA_FLAG_KEY_MAJOR | MOBA_FLAG_QUERY_TILES))
+        return MOBA_EINVAL;
+    if ((sh->flags & MOBA_FLAG_KEY_MAJOR) && (sh->flags & MOBA_FLAG_QUERY_TILES)) return MOBA_EINVAL;
     if (!(sh->softmax_scale == sh->softmax_scale) || isinf(sh->softmax_scale)) return MOBA_EINVAL;
     if (sh->head_dim != 64 && sh->head_dim != 128) return MOBA_EUNSUPPORTED;
     if (sh->conv_width > 8) return MOBA_EUNSUPPORTED;
@@ -69,10 +71,11 @@ size_t topk_ws_bytes(const Dims& d)
 }
 int32_t* chunk_counts(const Dims&, void* ws) { return static_cast<int32_t*>(ws); }
 void* topk_terms(const Dims& d, void* ws) { return static_cast<char*>(ws) + chunk_counts_bytes(d); }
-// forward: slot-ordered transposed copy of V for the MFMA kernel
+// forward: operand copies of K and V (+ the per-pair partials of the key-major kernel)
 size_t fwd_ws_bytes(const Dims& d)
 {
-    return mfma_path(d) ? align256(forward_mfma_ws_bytes(d)) : 256;
+    if (!mfma_path(d)) return 256;
+    return align256(key_major_path(d) ? forward_km_ws_bytes(d) : forward_mfma_ws_bytes(d));
 }
 size_t bwd_ws_bytes(const Dims& d)
 {
@@ -254,6 +257,9 @@ int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, cons
     if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
     if (d.R > 0 && !blk_q) return MOBA_EINVAL;
     if (!ws || ws_bytes < fwd_ws_bytes(d)) return MOBA_EWORKSPACE;
+    if (mfma_path(d) && key_major_path(d))
+        return hip_status(launch_forward_km(d, Q, K_eff, V, ws, topk_idx, blk_off, blk_q, O, lse,
+                                            (hipStream_t)stream));
     if (mfma_path(d))
         return hip_status(launch_forward_mfma(d, Q, K_eff, V, ws, topk_idx, blk_off, blk_q, O, lse,
                                               (hipStream_t)stream));

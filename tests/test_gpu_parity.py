@@ -15,6 +15,9 @@ pytestmark = pytest.mark.gpu
 
 REF = binding.FLAG_REFERENCE_KERNELS
 FLAGS = [pytest.param(0, id="default"), pytest.param(REF, id="plain")]
+# attention kernels also exist in two cuts, query tiles and key-block major: force each
+ATTN_FLAGS = FLAGS + [pytest.param(binding.FLAG_KEY_MAJOR, id="keymajor"),
+                      pytest.param(binding.FLAG_QUERY_TILES, id="tiles")]
 
 
 def shape_of(w, flags=0):
@@ -204,7 +207,7 @@ def test_build_lists_from_a_given_routing(oracle, w):
 
 # ------------------------------------------------------------------ attention at the oracle's routing
 
-@pytest.mark.parametrize("flags", FLAGS)
+@pytest.mark.parametrize("flags", ATTN_FLAGS)
 @pytest.mark.parametrize("w", SMALL, ids=IDS)
 def test_forward_backward_at_oracle_routing(oracle, w, flags):
     t = workloads.generate(w)
@@ -220,6 +223,44 @@ def test_forward_backward_at_oracle_routing(oracle, w, flags):
     assert parity.max_abs(np64(lse), rlse) < parity.LSE_TOL[w.dtype]
     dQ, dK, dV = moba.backward(sh, d["Q"], d["K"], d["V"], O, lse, d["dO"], idx, lists)
     # the oracle's backward starts from its own forward (binary64 O and lse)
+    rQ, rK, rV = oracle.attn_bwd(Q, K, V, ref_idx, dO, w.B, w.scale)
+    tol = parity.GRAD_TOL[w.dtype]
+    assert parity.rel_l2(np64(dQ), rQ) < tol
+    assert parity.rel_l2(np64(dK), rK) < tol
+    assert parity.rel_l2(np64(dV), rV) < tol
+
+
+# shapes that reach every variant of the key-block-major kernels: key blocks in 128-key parts,
+# three 32-key groups, and rows of kept blocks searched in one, two and more steps
+KEY_MAJOR = [
+    W("km_B256_parts", 1, 2, 2048, 64, 256, 3, seed=61),
+    W("km_B512_d128", 1, 1, 2048, 128, 512, 2, seed=62),
+    W("km_B96", 1, 1, 960, 64, 96, 3, seed=63),
+    W("km_k16", 1, 1, 2048, 64, 32, 16, seed=64),
+    W("km_k40", 1, 1, 4096, 64, 32, 40, seed=65),
+    W("km_d128_k20", 1, 1, 2048, 128, 32, 20, seed=66),
+    W("km_d128_k40", 1, 1, 4096, 128, 64, 40, seed=67),
+    W("km_sparse_default", 1, 2, 16384, 64, 128, 2, seed=68),   # the library itself picks key-major
+]
+
+
+@pytest.mark.parametrize("w", KEY_MAJOR, ids=[w.name for w in KEY_MAJOR])
+def test_key_major_variants(oracle, w):
+    t = workloads.generate(w)
+    Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
+    ref_idx, _ = oracle.topk(Q, oracle.centroids(Kp, w.B), w.B, w.k)
+    sh = shape_of(w, 0 if w.name.endswith("default") else binding.FLAG_KEY_MAJOR)
+    d = dev(t)
+    idx = torch.from_numpy(ref_idx).reshape(w.batch, w.heads, w.N, w.k).cuda()
+    lists = moba.build_lists(sh, idx)
+    O, lse = moba.forward(sh, d["Q"], d["K"], d["V"], idx, lists)
+    rO, rlse = oracle.attn_fwd(Q, K, V, ref_idx, w.B, w.scale)
+    assert parity.max_abs(np64(O), rO) < parity.O_TOL[w.dtype]
+    assert parity.max_abs(np64(lse), rlse) < parity.LSE_TOL[w.dtype]
+    # the same forward by query tiles: the two cuts must agree far inside the tolerance
+    O2, lse2 = moba.forward(shape_of(w, binding.FLAG_QUERY_TILES), d["Q"], d["K"], d["V"], idx, lists)
+    assert parity.max_abs(np64(lse), np64(lse2)) < 1e-4
+    dQ, dK, dV = moba.backward(sh, d["Q"], d["K"], d["V"], O, lse, d["dO"], idx, lists)
     rQ, rK, rV = oracle.attn_bwd(Q, K, V, ref_idx, dO, w.B, w.scale)
     tol = parity.GRAD_TOL[w.dtype]
     assert parity.rel_l2(np64(dQ), rQ) < tol
