@@ -1,0 +1,360 @@
+// dQ of the MoBA backward, key-block major, for sparse routing (paper Section 4.2 backward and
+// Appendix C.3: key blocks outermost, the queries routed to a block gathered into dense tiles,
+// S recomputed, dS = P o (dP - D), dQ += scale dS K).  The companion of attn_fwd_km.hip: a
+// workgroup owns up to 128 (d = 64) or 64 (d = 128) keys of one key block -- K, V and K^T stay
+// in registers as MFMA operands -- and walks the block's query list, then the block's own
+// queries (causally masked), 32 queries per step and wave.
+//
+// The paper's kernel adds each block's contribution to dQ with atomic additions into a
+// high-precision buffer.  Here the contribution of (query t, kept block e, part c) is written
+// once, as bf16, to [t][e][c], and a second kernel adds a query's contributions up in fp32 in a
+// fixed order: no atomics, bit-reproducible, and the partial sums stream.
+//
+// Per 16-query tile (queries are the columns of every product, so a lane owns one query):
+//   S^T  = K Q_g^T, dP^T = V dO_g^T - D      keys x queries; -D is the start value of the sum
+//   dS^T = 2^(c S^T - lse) o dP^T            in the result layout, which packed to bf16 is the
+//                                            B operand over the keys (slot order of mfma.h)
+//   dQ^T += K^T dS^T                         channels x queries
+#include <type_traits>
+
+#include "mfma.h"
+
+namespace moba {
+
+typedef uint32_t dqvec4_t __attribute__((ext_vector_type(4)));
+
+template <int D>
+struct DqKmCfg {
+    static constexpr int NW = 4;
+    static constexpr int NT = NW * kWave;
+    static constexpr int SB = D * 2 + 16;              // bytes per parked row: the row, then (t, e)
+    static constexpr int MT = D / 16;
+    static constexpr int KS = D / 32;
+    static constexpr int CPR = D / 8;                  // 16-byte chunks per row = lanes per gathered row
+    static constexpr int RPI = kWave / CPR;            // rows per gather instruction
+    static constexpr int NI = 32 / RPI;                // gather instructions per tensor and step
+    static constexpr size_t WAVE = (size_t)2 * 32 * SB + 256;       // Q rows, dO rows, lse and -D
+    static constexpr size_t LDS = NW * WAVE;
+};
+
+// NG: 32-key groups per workgroup; KC: a query's row of kept blocks is searched CPR entries at a
+// time, KC times (k <= KC * CPR)
+template <int D, int NG, int KC>
+__global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO, const bf16_t* __restrict__ Ka,
+    const bf16_t* __restrict__ Va, const bf16_t* __restrict__ Kt, const float* __restrict__ lse,
+    const float* __restrict__ Dv, const int32_t* __restrict__ idx, const int32_t* __restrict__ off,
+    const int32_t* __restrict__ ql, bf16_t* __restrict__ PdQ, int N, int B, int n, int k, int nsub,
+    float scale, int64_t R, int bh)
+{
+    using C = DqKmCfg<D>;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int m16 = lane & 15, g = lane >> 4;
+    unsigned char* stQ = smem + (size_t)wave * C::WAVE;
+    unsigned char* stG = stQ + 32 * C::SB;
+    float* ls = reinterpret_cast<float*>(stG + 32 * C::SB);
+    float* Ds = ls + 32;
+
+    int s, u;                                               // slice, (key block, part)
+    if (!schedule(blockIdx.x, bh, n * nsub, s, u)) return;
+    const int j = u / nsub, c = u - j * nsub;
+    const int own_first = c * (32 * NG);                    // first key of the part inside the block
+    const int64_t sbase = (int64_t)s * N;
+    const float c2 = scale * kLog2e;
+    const int32_t* os = off + (int64_t)s * (n + 1);
+    const int32_t* qs = ql + (int64_t)s * R;
+    const int lo = os[j], nlist = os[j + 1] - lo;
+    const int own0 = j * B + own_first;                     // own queries that see keys of this part
+    const int total = nlist + (B - own_first);
+    const char* Qg = reinterpret_cast<const char*>(Q + sbase * D);
+    const char* Gg = reinterpret_cast<const char*>(dO + sbase * D);
+    const float* lses = lse + sbase;
+    const float* Dvs = Dv + sbase;
+    const uint32_t vlane = (uint32_t)lane * 16u;
+
+    // the part's keys (rows, and transposed) and values as MFMA operands, resident for the walk
+    Frag ka[NG][2][C::KS], va[NG][2][C::KS], kt[NG][C::MT];
+    {
+        const char* Kag = reinterpret_cast<const char*>(Ka + (sbase + own0) * D);
+        const char* Vag = reinterpret_cast<const char*>(Va + (sbase + own0) * D);
+        const char* Ktg = reinterpret_cast<const char*>(Kt + (sbase + own0) * D);
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int ks = 0; ks < C::KS; ++ks) {
+                    const int o = gi * (64 * D) + (mt * C::KS + ks) * 1024;
+                    ka[gi][mt][ks].q = *reinterpret_cast<const uint4*>(Kag + o + vlane);
+                    va[gi][mt][ks].q = *reinterpret_cast<const uint4*>(Vag + o + vlane);
+                }
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt)
+                kt[gi][mt].q = *reinterpret_cast<const uint4*>(Ktg + gi * (64 * D) + vlane + mt * 1024);
+        }
+    }
+
+    // every load of the walk is unconditional and from an address that is always valid (a load
+    // inside a branch is waited for at the end of the branch)
+    const int32_t* lsrc = nlist > 0 ? qs + lo : os;
+    const int llast = max(nlist - 1, 0);
+    auto query_at = [&](int a) {
+        const int listed = lsrc[min(a, llast)];
+        const int t = a < nlist ? listed : own0 + (a - nlist);
+        return a >= total ? own0 : t;
+    };
+    const int grow = lane / C::CPR, lcol = lane % C::CPR;
+    const uint32_t gcol = (uint32_t)lcol * 16u;
+    // t: the rows this lane gathers a piece of; tl: the row whose lse and D lane (lane & 31) brings
+    auto ids = [&](int a0, int (&t)[C::NI], int& tl) {
+#pragma unroll
+        for (int i = 0; i < C::NI; ++i) t[i] = query_at(a0 + C::RPI * i + grow);
+        tl = query_at(a0 + (lane & 31));
+    };
+    const int32_t* isrc = k > 0 ? idx + sbase * k : os;
+    const int klast = max(k - 1, 0);
+    // one step's loads: the pieces of the Q and dO rows, the rows' kept blocks (CPR entries per
+    // row and instruction), lse in log2 units (+inf past the end: P = 0) and -D
+    auto fetch = [&](int a0, const int (&t)[C::NI], int tl, dqvec4_t (&qr)[C::NI], dqvec4_t (&gr)[C::NI],
+                     int (&ev)[C::NI][KC], float& lv, float& dv) {
+#pragma unroll
+        for (int i = 0; i < C::NI; ++i) {
+            const uint32_t o = (uint32_t)t[i] * (uint32_t)(2 * D) + gcol;
+            qr[i] = *reinterpret_cast<const dqvec4_t*>(Qg + o);
+            gr[i] = *reinterpret_cast<const dqvec4_t*>(Gg + o);
+        }
+#pragma unroll
+        for (int i = 0; i < C::NI; ++i)
+#pragma unroll
+            for (int cc = 0; cc < KC; ++cc)
+                ev[i][cc] = isrc[(int64_t)t[i] * k + min(lcol + C::CPR * cc, klast)];
+        const float l = lses[tl] * kLog2e;
+        lv = a0 + (lane & 31) < total ? l : INFINITY;
+        dv = -Dvs[tl];
+    };
+    // Two steps of gathered rows are in flight while a third is worked on; the row ids of the
+    // step after those (tN, tlN) are loaded before the gather that precedes them, so that
+    // waiting for them (loads complete in order) leaves that gather in flight.
+    const int stride = 32 * C::NW;
+    int t0[C::NI], t1[C::NI], tN[C::NI], tl0, tl1, tlN, ev0[C::NI][KC], ev1[C::NI][KC];
+    dqvec4_t qr0[C::NI], gr0[C::NI], qr1[C::NI], gr1[C::NI];
+    float lv0, dv0, lv1, dv1;
+    ids(32 * wave, t0, tl0);
+    ids(32 * wave + stride, t1, tl1);
+    ids(32 * wave + 2 * stride, tN, tlN);
+    fetch(32 * wave, t0, tl0, qr0, gr0, ev0, lv0, dv0);
+    fetch(32 * wave + stride, t1, tl1, qr1, gr1, ev1, lv1, dv1);
+    const uint32_t park = (uint32_t)grow * C::SB + gcol;
+    const uint32_t arow = (uint32_t)m16 * C::SB + 16u * g;
+    const int64_t slots = (int64_t)(k + 1) * nsub;          // partials per query
+
+    auto step = [&](int a0, int (&tA)[C::NI], int& tlA, dqvec4_t (&qr)[C::NI], dqvec4_t (&gr)[C::NI],
+                    int (&ev)[C::NI][KC], float& lv, float& dv) {
+        // park the gathered rows, t behind each Q row, and e from the lane that finds j in the
+        // query's row of kept blocks (own rows: e = k)
+#pragma unroll
+        for (int i = 0; i < C::NI; ++i) {
+            *reinterpret_cast<dqvec4_t*>(stQ + park + i * C::RPI * C::SB) = qr[i];
+            *reinterpret_cast<dqvec4_t*>(stG + park + i * C::RPI * C::SB) = gr[i];
+            int e = -1;
+#pragma unroll
+            for (int cc = 0; cc < KC; ++cc) {
+                const int ent = lcol + C::CPR * cc;
+                if (ev[i][cc] == j && ent < k) e = ent;
+            }
+            if (a0 + C::RPI * i + grow >= nlist) e = lcol == 0 ? k : -1;
+            // t always, e where found: lists that do not match the rows of kept blocks give a
+            // wrong result, never an address outside the query's partials
+            unsigned char* note = stQ + (grow + i * C::RPI) * C::SB + 2 * D;
+            if (lcol == 0) *reinterpret_cast<int*>(note) = tA[i];
+            if (e >= 0) *reinterpret_cast<int*>(note + 4) = e;
+        }
+        if (lane < 32) { ls[lane] = lv; Ds[lane] = dv; }
+#pragma unroll
+        for (int i = 0; i < C::NI; ++i) tA[i] = tN[i];
+        tlA = tlN;
+        ids(a0 + 3 * stride, tN, tlN);
+        fetch(a0 + 2 * stride, tA, tlA, qr, gr, ev, lv, dv);
+        __builtin_amdgcn_wave_barrier();
+        const bool masked = a0 + 32 > nlist;                       // the step holds own rows
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            Frag qb[C::KS], gb[C::KS];
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ++ks) {
+                qb[ks].q = *reinterpret_cast<const uint4*>(stQ + arow + qt * 16 * C::SB + 64 * ks);
+                gb[ks].q = *reinterpret_cast<const uint4*>(stG + arow + qt * 16 * C::SB + 64 * ks);
+            }
+            const int2 te = *reinterpret_cast<const int2*>(stQ + (16 * qt + m16) * C::SB + 2 * D);
+            const float lq = ls[16 * qt + m16], nd = Ds[16 * qt + m16];
+            const int av = a0 + 16 * qt + m16;                     // this lane's row of the walk
+            const int r = av - nlist;                              // own row r sees keys 0 .. r of the part
+            f32x4_t o[C::MT];
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt) o[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi) {
+                // x[4 mt + i]: dS of key 32 gi + 16 mt + 4 g + i of the part
+                float x[8];
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f}, dp = f32x4_t{nd, nd, nd, nd};
+#pragma unroll
+                    for (int ks = 0; ks < C::KS; ++ks) sc = mfma16(ka[gi][mt][ks], qb[ks], sc);
+#pragma unroll
+                    for (int ks = 0; ks < C::KS; ++ks) dp = mfma16(va[gi][mt][ks], gb[ks], dp);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float p = fast_exp2(fmaf(sc[i], c2, -lq));
+                        if (masked && r >= 0 && 32 * gi + 16 * mt + 4 * g + i > r) p = 0.f;
+                        x[4 * mt + i] = p * dp[i];
+                    }
+                }
+                Frag pb;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pb.u[e] = pack2(x[2 * e], x[2 * e + 1]);
+#pragma unroll
+                for (int mt = 0; mt < C::MT; ++mt) o[mt] = mfma16(kt[gi][mt], pb, o[mt]);
+            }
+            // the partial: this lane holds D/4 consecutive channels of the row
+            if (av < total) {
+                const int e = min(max(te.y, 0), k);
+                const int64_t prow = (sbase + te.x) * slots + (int64_t)e * nsub + c;
+                uint32_t w[C::MT * 2];
+#pragma unroll
+                for (int mt = 0; mt < C::MT; ++mt) {
+                    w[2 * mt] = pack_bf16x2(o[mt][0] * scale, o[mt][1] * scale);
+                    w[2 * mt + 1] = pack_bf16x2(o[mt][2] * scale, o[mt][3] * scale);
+                }
+                uint4* dst = reinterpret_cast<uint4*>(PdQ + prow * D + g * (D / 4));
+#pragma unroll
+                for (int q4 = 0; q4 < C::MT / 2; ++q4)
+                    dst[q4] = make_uint4(w[4 * q4], w[4 * q4 + 1], w[4 * q4 + 2], w[4 * q4 + 3]);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+    for (int a0 = 32 * wave; a0 < total; a0 += 2 * stride) {
+        step(a0, t0, tl0, qr0, gr0, ev0, lv0, dv0);
+        if (a0 + stride >= total) break;
+        step(a0 + stride, t1, tl1, qr1, gr1, ev1, lv1, dv1);
+    }
+}
+
+// dQ_t = sum of the query's partials, in the order [kept block][part], then the parts of its
+// own block up to its own key.  D / 8 lanes per query.
+template <int D>
+__global__ __launch_bounds__(256) void dq_km_merge_kernel(
+    const int32_t* __restrict__ idx, const bf16_t* __restrict__ PdQ, bf16_t* __restrict__ dQ, int N,
+    int B, int k, int nsub, int64_t rows_total)
+{
+    constexpr int G = D / 8;
+    const int64_t row = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;      // s * N + t
+    const int part = threadIdx.x % G;
+    if (row >= rows_total) return;
+    const int t = (int)(row % N);
+    const int own_parts = (t % B) / km_part_keys(B, D) + 1;
+    const int32_t* irow = idx + row * k;
+    const int64_t p0 = row * (k + 1) * nsub;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int e = 0; e <= k; ++e) {
+        const int np = e == k ? own_parts : (irow[e] < 0 ? 0 : nsub);
+        for (int c = 0; c < np; ++c) {
+            float v[8];
+            Vec8<bf16_t>::load(PdQ + (p0 + e * nsub + c) * D + part * 8, v);
+#pragma unroll
+            for (int ch = 0; ch < 8; ++ch) acc[ch] += v[ch];
+        }
+    }
+    Vec8<bf16_t>::store(dQ + row * D + part * 8, acc);
+}
+
+// ---- workspace: [D: bh*N fp32][slot-ordered K][operand-ordered K][operand-ordered V]
+// [partial dQ: bh*N*(k+1)*parts*D bf16], each 256-byte aligned
+static size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static size_t km_partials(const Dims& s)
+{
+    return (size_t)s.bh * s.N * (size_t)(s.k + 1) * (size_t)(s.B / km_part_keys(s.B, s.D));
+}
+
+size_t backward_km_ws_bytes(const Dims& s)
+{
+    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
+    return a256(sizeof(float) * (size_t)s.bh * s.N) + 3 * tensor + a256(sizeof(bf16_t) * km_partials(s) * s.D);
+}
+
+template <int D, int NG, int KC>
+static hipError_t dq_launch3(const Dims& s, const void* Q, const void* dO, const void* Ka, const void* Va,
+                             const void* Kt, const float* lse, const float* Dv, const int32_t* idx,
+                             const int32_t* off, const int32_t* ql, bf16_t* PdQ, void* dQ, hipStream_t st)
+{
+    using C = DqKmCfg<D>;
+    const int nsub = s.B / km_part_keys(s.B, s.D);
+    hipError_t e = hipFuncSetAttribute((const void*)dq_km_kernel<D, NG, KC>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+    if (e != hipSuccess) return e;
+    {
+        ProfileScope timing(MOBA_PROFILE_DQ, st);
+        hipLaunchKernelGGL((dq_km_kernel<D, NG, KC>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
+                           dim3(C::NT), C::LDS, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ka,
+                           (const bf16_t*)Va, (const bf16_t*)Kt, lse, Dv, idx, off, ql, PdQ, s.N, s.B, s.n,
+                           s.k, nsub, s.scale, s.R, s.bh);
+    }
+    const int64_t rows = (int64_t)s.bh * s.N;
+    const int rpw = 256 / (D / 8);
+    hipLaunchKernelGGL((dq_km_merge_kernel<D>), dim3((unsigned)((rows + rpw - 1) / rpw)), dim3(256), 0, st,
+                       idx, PdQ, (bf16_t*)dQ, s.N, s.B, s.k, nsub, rows);
+    return hipGetLastError();
+}
+
+template <int D, int NG, typename... A>
+static hipError_t dq_launch2(const Dims& s, A... a)
+{
+    constexpr int CPR = DqKmCfg<D>::CPR, KCMAX = kKeyMajorMaxTopk / CPR;
+    if (s.k <= CPR) return dq_launch3<D, NG, 1>(s, a...);
+    if (s.k <= 2 * CPR) return dq_launch3<D, NG, 2>(s, a...);
+    return dq_launch3<D, NG, KCMAX>(s, a...);
+}
+
+template <int D, typename... A>
+static hipError_t dq_launch(const Dims& s, A... a)
+{
+    switch (km_part_keys(s.B, D) / 32) {
+        case 1: return dq_launch2<D, 1>(s, a...);
+        case 2: return dq_launch2<D, 2>(s, a...);
+        case 3: if constexpr (D == 64) return dq_launch2<D, 3>(s, a...); else break;
+        case 4: if constexpr (D == 64) return dq_launch2<D, 4>(s, a...); else break;
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_dq_km(const Dims& s, const void* Q, const void* K, const void* V, const void* dO,
+                        const float* lse, const int32_t* idx, const int32_t* off, const int32_t* ql,
+                        void* dQ, void* ws, hipStream_t st)
+{
+    if (s.bh == 0 || s.N == 0) return hipSuccess;
+    if (!key_major_shape(s)) return hipErrorInvalidValue;
+    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
+    char* p = static_cast<char*>(ws);
+    const float* Dv = reinterpret_cast<const float*>(p);
+    p += a256(sizeof(float) * (size_t)s.bh * s.N);
+    void* Kt = p;
+    p += tensor;
+    void* Ka = p;
+    p += tensor;
+    void* Va = p;
+    p += tensor;
+    bf16_t* PdQ = reinterpret_cast<bf16_t*>(p);
+    hipError_t e = launch_slot_major_copy(s, K, Kt, nullptr, st);
+    if (e != hipSuccess) return e;
+    e = launch_operand_copy(s, K, Ka, st);
+    if (e != hipSuccess) return e;
+    e = launch_operand_copy(s, V, Va, st);
+    if (e != hipSuccess) return e;
+    return s.D == 64 ? dq_launch<64>(s, Q, dO, Ka, Va, Kt, lse, Dv, idx, off, ql, PdQ, dQ, st)
+                     : dq_launch<128>(s, Q, dO, Ka, Va, Kt, lse, Dv, idx, off, ql, PdQ, dQ, st);
+}
+
+}  // namespace moba

@@ -3,7 +3,7 @@
 // dense tiles).  The query-tile kernel of attn_fwd_mfma.hip needs a 256-query tile to meet a key
 // block with many of its rows; with few kept blocks out of very many (long sequences) a tile
 // meets a block with one or two rows and the work per (query, block) pair explodes.  Here a
-// workgroup owns up to 128 keys of one key block -- their K and V MFMA operands stay in
+// workgroup owns up to 128 (d = 64) or 64 (d = 128) keys of one key block -- their K and V MFMA operands stay in
 // registers for the whole walk -- and walks the list of ALL queries that kept the block (then
 // the block's own queries, causally masked), 32 queries per step and wave: the tiles are dense
 // whatever the sequence length, and nothing but the gathered query rows is read in the loop.
@@ -13,7 +13,7 @@
 // reference m, the sum l of exp(s - m), and sum p v / l rounded to bf16 -- and a second kernel
 // merges a query's partials (Section 4.2: the partial outputs are combined with the
 // log-sum-exp weights).  The partials of query t lie together, [t][e][c] for its e-th kept
-// block (e = k: own block) and 128-key part c, so the merge streams them; the walk finds e by
+// block (e = k: own block) and part c of the block's keys, so the merge streams them; the walk finds e by
 // looking j up in the query's (ascending) row of kept blocks.  No atomics anywhere; results are
 // bit-reproducible.
 #include <type_traits>
@@ -36,9 +36,6 @@ struct KmCfg {
     static constexpr int NI = 32 / RPI;                // gather instructions per step
     static constexpr size_t LDS = (size_t)NW * 32 * SB;
 };
-
-// keys per workgroup: the whole block up to 128 keys, else 128-key parts
-__host__ __device__ inline int km_part_keys(int B) { return B <= kKeyMajorPart ? B : kKeyMajorPart; }
 
 // NG: 32-key groups per workgroup; KC: a query's row of kept blocks is searched CPR entries at a
 // time, KC times (k <= KC * CPR)
@@ -259,7 +256,7 @@ __global__ __launch_bounds__(256) void fwd_km_merge_kernel(
     const int part = threadIdx.x % G;
     if (row >= rows_total) return;
     const int t = (int)(row % N);
-    const int own_parts = (t % B) / km_part_keys(B) + 1;
+    const int own_parts = (t % B) / km_part_keys(B, D) + 1;
     const int32_t* irow = idx + row * k;
     const int64_t p0 = row * (k + 1) * nsub;
     auto parts_of = [&](int e) { return e == k ? own_parts : (irow[e] < 0 ? 0 : nsub); };
@@ -295,7 +292,7 @@ static size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static size_t km_partials(const Dims& s)
 {
-    return (size_t)s.bh * s.N * (size_t)(s.k + 1) * (size_t)(s.B / km_part_keys(s.B));
+    return (size_t)s.bh * s.N * (size_t)(s.k + 1) * (size_t)(s.B / km_part_keys(s.B, s.D));
 }
 
 size_t forward_km_ws_bytes(const Dims& s)
@@ -310,7 +307,10 @@ static hipError_t km_launch3(const Dims& s, const void* Q, const void* Ka, const
                              float* Pml, void* O, float* lse, hipStream_t st)
 {
     using C = KmCfg<D>;
-    const int nsub = s.B / km_part_keys(s.B);
+    const int nsub = s.B / km_part_keys(s.B, s.D);
+    hipError_t e = hipFuncSetAttribute((const void*)fwd_km_kernel<D, NG, KC>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+    if (e != hipSuccess) return e;
     {
         ProfileScope timing(MOBA_PROFILE_FORWARD, st);
         hipLaunchKernelGGL((fwd_km_kernel<D, NG, KC>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
@@ -336,11 +336,11 @@ static hipError_t km_launch2(const Dims& s, A... a)
 template <int D, typename... A>
 static hipError_t km_launch(const Dims& s, A... a)
 {
-    switch (km_part_keys(s.B) / 32) {
+    switch (km_part_keys(s.B, D) / 32) {
         case 1: return km_launch2<D, 1>(s, a...);
         case 2: return km_launch2<D, 2>(s, a...);
-        case 3: return km_launch2<D, 3>(s, a...);
-        case 4: return km_launch2<D, 4>(s, a...);
+        case 3: if constexpr (D == 64) return km_launch2<D, 3>(s, a...); else break;
+        case 4: if constexpr (D == 64) return km_launch2<D, 4>(s, a...); else break;
     }
     return hipErrorInvalidValue;
 }

@@ -219,9 +219,16 @@ bool topk_mfma_supported(const Dims& s);
 hipError_t launch_topk_mfma(const Dims& s, const void* Q, const float* cent, int32_t* idx, void* ws,
                             hipStream_t st);
 
-constexpr int kKeyMajorBelowRows = 6;     // rows per (tile, block) visit below which key-major wins
-constexpr int kKeyMajorPart = 128;        // keys a key-major workgroup holds in registers
+constexpr int kKeyMajorBelowRows = 8;     // rows per (tile, block) visit below which key-major wins
 constexpr int kKeyMajorMaxTopk = 64;      // longest row of kept blocks the key-major walk searches
+
+// keys a key-major workgroup holds in registers as MFMA operands: the whole block up to 128
+// (d = 64) or 64 (d = 128) keys, else parts of that size
+__host__ __device__ inline int km_part_keys(int B, int D)
+{
+    const int cap = D == 64 ? 128 : 64;
+    return B <= cap ? B : cap;
+}
 
 // shapes the MFMA kernels cover: bf16 I/O and key blocks made of whole 32-key groups
 inline bool mfma_path(const Dims& s)
@@ -229,10 +236,10 @@ inline bool mfma_path(const Dims& s)
     return s.dtype == MOBA_BF16 && s.B % 32 == 0 && !(s.flags & MOBA_FLAG_REFERENCE_KERNELS);
 }
 
-// shapes the key-major kernels cover: blocks of up to 128 keys or of whole 128-key parts
+// shapes the key-major kernels cover: key blocks of one part or of whole parts
 inline bool key_major_shape(const Dims& s)
 {
-    return mfma_path(s) && (s.B <= kKeyMajorPart || s.B % kKeyMajorPart == 0) && s.k <= kKeyMajorMaxTopk;
+    return mfma_path(s) && s.B % km_part_keys(s.B, s.D) == 0 && s.k <= kKeyMajorMaxTopk;
 }
 
 // Query-tile or key-major attention?  A tile of T consecutive queries (256 for d = 64, 128 for
@@ -243,10 +250,14 @@ inline bool key_major_path(const Dims& s)
     if (!key_major_shape(s) || (s.flags & MOBA_FLAG_QUERY_TILES)) return false;
     if (s.flags & MOBA_FLAG_KEY_MAJOR) return true;
     const int T = s.D == 64 ? 256 : 128;
-    return (int64_t)T * s.k < (int64_t)kKeyMajorBelowRows * s.n;
+    return (int64_t)T * s.k <= (int64_t)kKeyMajorBelowRows * s.n;
 }
 
 size_t forward_km_ws_bytes(const Dims& s);
+size_t backward_km_ws_bytes(const Dims& s);
+hipError_t launch_dq_km(const Dims& s, const void* Q, const void* K, const void* V, const void* dO,
+                        const float* lse, const int32_t* idx, const int32_t* off, const int32_t* ql,
+                        void* dQ, void* ws, hipStream_t st);
 hipError_t launch_forward_km(const Dims& s, const void* Q, const void* K, const void* V, void* ws,
                              const int32_t* idx, const int32_t* off, const int32_t* ql, void* O,
                              float* lse, hipStream_t st);

@@ -79,7 +79,8 @@ size_t fwd_ws_bytes(const Dims& d)
 }
 size_t bwd_ws_bytes(const Dims& d)
 {
-    return mfma_path(d) ? align256(backward_mfma_ws_bytes(d)) : align256(sizeof(float) * (size_t)d.bh * d.N);
+    if (!mfma_path(d)) return align256(sizeof(float) * (size_t)d.bh * d.N);
+    return align256(key_major_path(d) ? backward_km_ws_bytes(d) : backward_mfma_ws_bytes(d));
 }
 
 }  // namespace
@@ -294,7 +295,9 @@ int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_ef
             if (e != hipSuccess) return hip_status(e);
         }
         if (parts & MOBA_BWD_DQ) {
-            hipError_t e = launch_dq_mfma(d, Q, K_eff, V, dO, lse, topk_idx, blk_off, blk_q, dQ, ws, hs);
+            hipError_t e = key_major_path(d)
+                ? launch_dq_km(d, Q, K_eff, V, dO, lse, topk_idx, blk_off, blk_q, dQ, ws, hs)
+                : launch_dq_mfma(d, Q, K_eff, V, dO, lse, topk_idx, blk_off, blk_q, dQ, ws, hs);
             if (e != hipSuccess) return hip_status(e);
         }
         if (parts & MOBA_BWD_DKDV) {

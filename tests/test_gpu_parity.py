@@ -236,6 +236,7 @@ KEY_MAJOR = [
     W("km_B256_parts", 1, 2, 2048, 64, 256, 3, seed=61),
     W("km_B512_d128", 1, 1, 2048, 128, 512, 2, seed=62),
     W("km_B96", 1, 1, 960, 64, 96, 3, seed=63),
+    W("km_d128_B128_parts", 1, 2, 2048, 128, 128, 3, seed=69),
     W("km_k16", 1, 1, 2048, 64, 32, 16, seed=64),
     W("km_k40", 1, 1, 4096, 64, 32, 40, seed=65),
     W("km_d128_k20", 1, 1, 2048, 128, 32, 20, seed=66),
