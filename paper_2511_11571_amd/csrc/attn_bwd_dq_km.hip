@@ -34,15 +34,16 @@ struct DqKmCfg {
     static constexpr int RPI = kWave / CPR;            // rows per gather instruction
     static constexpr int NI = 32 / RPI;                // gather instructions per tensor and step
     static constexpr size_t WAVE = (size_t)2 * 32 * SB + 256;       // Q rows, dO rows, lse and -D
-    static constexpr size_t LDS = NW * WAVE;
+    static constexpr size_t PARK = NW * WAVE;
+    static constexpr size_t lds(int ng) { return PARK + (size_t)2 * ng * 64 * D; }   // + the part's K and V
 };
 
 // NG: 32-key groups per workgroup; KC: a query's row of kept blocks is searched CPR entries at a
 // time, KC times (k <= KC * CPR)
 template <int D, int NG, int KC>
 __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
-    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO, const bf16_t* __restrict__ Ka,
-    const bf16_t* __restrict__ Va, const bf16_t* __restrict__ Kt, const float* __restrict__ lse,
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO, const bf16_t* __restrict__ K,
+    const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kt, const float* __restrict__ lse,
     const float* __restrict__ Dv, const int32_t* __restrict__ idx, const int32_t* __restrict__ off,
     const int32_t* __restrict__ ql, bf16_t* __restrict__ PdQ, int N, int B, int n, int k, int nsub,
     float scale, int64_t R, int bh)
@@ -55,6 +56,8 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     unsigned char* stG = stQ + 32 * C::SB;
     float* ls = reinterpret_cast<float*>(stG + 32 * C::SB);
     float* Ds = ls + 32;
+    unsigned char* sK = smem + C::PARK;
+    unsigned char* sV = sK + NG * 64 * D;
 
     int s, u;                                               // slice, (key block, part)
     if (!schedule(blockIdx.x, bh, n * nsub, s, u)) return;
@@ -73,27 +76,33 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     const float* Dvs = Dv + sbase;
     const uint32_t vlane = (uint32_t)lane * 16u;
 
-    // the part's keys (rows, and transposed) and values as MFMA operands, resident for the walk
-    Frag ka[NG][2][C::KS], va[NG][2][C::KS], kt[NG][C::MT];
+    // The part's K and V rows go to LDS in MFMA operand order -- the 16 bytes lane (m, g) feeds as
+    // rows 16 mt + m, channels 32 ks + 8 g .. + 8 of 32-key group gi sit at
+    // ((gi * 2 + mt) * KS + ks) * 1024 + 16 * lane -- and are read from there in every step; K^T
+    // (slot order) stays in registers for the whole walk.  (All three in registers would leave
+    // room for one wave per SIMD only, and the walk needs a second one to fill the waits of the
+    // first.)
     {
-        const char* Kag = reinterpret_cast<const char*>(Ka + (sbase + own0) * D);
-        const char* Vag = reinterpret_cast<const char*>(Va + (sbase + own0) * D);
+        const char* Kg = reinterpret_cast<const char*>(K + (sbase + own0) * D);
+        const char* Vg = reinterpret_cast<const char*>(V + (sbase + own0) * D);
+        for (int ch = tid; ch < NG * 32 * C::CPR; ch += C::NT) {
+            const int row = ch / C::CPR, col = ch % C::CPR;             // key of the part, 16-byte piece
+            const int gi = row >> 5, mt = (row >> 4) & 1, m = row & 15, ks = col >> 2, gg = col & 3;
+            const int o = ((gi * 2 + mt) * C::KS + ks) * 1024 + (16 * gg + m) * 16;
+            *reinterpret_cast<dqvec4_t*>(sK + o) = *reinterpret_cast<const dqvec4_t*>(Kg + (size_t)ch * 16);
+            *reinterpret_cast<dqvec4_t*>(sV + o) = *reinterpret_cast<const dqvec4_t*>(Vg + (size_t)ch * 16);
+        }
+    }
+    Frag kt[NG][C::MT];
+    {
         const char* Ktg = reinterpret_cast<const char*>(Kt + (sbase + own0) * D);
 #pragma unroll
-        for (int gi = 0; gi < NG; ++gi) {
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int ks = 0; ks < C::KS; ++ks) {
-                    const int o = gi * (64 * D) + (mt * C::KS + ks) * 1024;
-                    ka[gi][mt][ks].q = *reinterpret_cast<const uint4*>(Kag + o + vlane);
-                    va[gi][mt][ks].q = *reinterpret_cast<const uint4*>(Vag + o + vlane);
-                }
+        for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
             for (int mt = 0; mt < C::MT; ++mt)
                 kt[gi][mt].q = *reinterpret_cast<const uint4*>(Ktg + gi * (64 * D) + vlane + mt * 1024);
-        }
     }
+    __syncthreads();
 
     // every load of the walk is unconditional and from an address that is always valid (a load
     // inside a branch is waited for at the end of the branch)
@@ -133,18 +142,16 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
         lv = a0 + (lane & 31) < total ? l : INFINITY;
         dv = -Dvs[tl];
     };
-    // Two steps of gathered rows are in flight while a third is worked on; the row ids of the
-    // step after those (tN, tlN) are loaded before the gather that precedes them, so that
-    // waiting for them (loads complete in order) leaves that gather in flight.
+    // The rows of the next step are in flight while one step is worked on; the row ids of the
+    // step after that (tN, tlN) are loaded before that gather, so that waiting for them (loads
+    // complete in order) leaves the gather in flight.
     const int stride = 32 * C::NW;
-    int t0[C::NI], t1[C::NI], tN[C::NI], tl0, tl1, tlN, ev0[C::NI][KC], ev1[C::NI][KC];
-    dqvec4_t qr0[C::NI], gr0[C::NI], qr1[C::NI], gr1[C::NI];
-    float lv0, dv0, lv1, dv1;
+    int t0[C::NI], tN[C::NI], tl0, tlN, ev0[C::NI][KC];
+    dqvec4_t qr0[C::NI], gr0[C::NI];
+    float lv0, dv0;
     ids(32 * wave, t0, tl0);
-    ids(32 * wave + stride, t1, tl1);
-    ids(32 * wave + 2 * stride, tN, tlN);
+    ids(32 * wave + stride, tN, tlN);
     fetch(32 * wave, t0, tl0, qr0, gr0, ev0, lv0, dv0);
-    fetch(32 * wave + stride, t1, tl1, qr1, gr1, ev1, lv1, dv1);
     const uint32_t park = (uint32_t)grow * C::SB + gcol;
     const uint32_t arow = (uint32_t)m16 * C::SB + 16u * g;
     const int64_t slots = (int64_t)(k + 1) * nsub;          // partials per query
@@ -174,8 +181,8 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
 #pragma unroll
         for (int i = 0; i < C::NI; ++i) tA[i] = tN[i];
         tlA = tlN;
-        ids(a0 + 3 * stride, tN, tlN);
-        fetch(a0 + 2 * stride, tA, tlA, qr, gr, ev, lv, dv);
+        ids(a0 + 2 * stride, tN, tlN);
+        fetch(a0 + stride, tA, tlA, qr, gr, ev, lv, dv);
         __builtin_amdgcn_wave_barrier();
         const bool masked = a0 + 32 > nlist;                       // the step holds own rows
 #pragma unroll
@@ -201,9 +208,14 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
                 for (int mt = 0; mt < 2; ++mt) {
                     f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f}, dp = f32x4_t{nd, nd, nd, nd};
 #pragma unroll
-                    for (int ks = 0; ks < C::KS; ++ks) sc = mfma16(ka[gi][mt][ks], qb[ks], sc);
-#pragma unroll
-                    for (int ks = 0; ks < C::KS; ++ks) dp = mfma16(va[gi][mt][ks], gb[ks], dp);
+                    for (int ks = 0; ks < C::KS; ++ks) {
+                        Frag ka, va;
+                        const int o = ((gi * 2 + mt) * C::KS + ks) * 1024 + vlane;
+                        ka.q = *reinterpret_cast<const uint4*>(sK + o);
+                        va.q = *reinterpret_cast<const uint4*>(sV + o);
+                        sc = mfma16(ka, qb[ks], sc);
+                        dp = mfma16(va, gb[ks], dp);
+                    }
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         float p = fast_exp2(fmaf(sc[i], c2, -lq));
@@ -235,11 +247,7 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
         }
         __builtin_amdgcn_wave_barrier();
     };
-    for (int a0 = 32 * wave; a0 < total; a0 += 2 * stride) {
-        step(a0, t0, tl0, qr0, gr0, ev0, lv0, dv0);
-        if (a0 + stride >= total) break;
-        step(a0 + stride, t1, tl1, qr1, gr1, ev1, lv1, dv1);
-    }
+    for (int a0 = 32 * wave; a0 < total; a0 += stride) step(a0, t0, tl0, qr0, gr0, ev0, lv0, dv0);
 }
 
 // dQ_t = sum of the query's partials, in the order [kept block][part], then the parts of its
@@ -270,8 +278,8 @@ __global__ __launch_bounds__(256) void dq_km_merge_kernel(
     Vec8<bf16_t>::store(dQ + row * D + part * 8, acc);
 }
 
-// ---- workspace: [D: bh*N fp32][slot-ordered K][operand-ordered K][operand-ordered V]
-// [partial dQ: bh*N*(k+1)*parts*D bf16], each 256-byte aligned
+// ---- workspace: [D: bh*N fp32][slot-ordered K][partial dQ: bh*N*(k+1)*parts*D bf16], each
+// 256-byte aligned
 static size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static size_t km_partials(const Dims& s)
@@ -282,24 +290,24 @@ static size_t km_partials(const Dims& s)
 size_t backward_km_ws_bytes(const Dims& s)
 {
     const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
-    return a256(sizeof(float) * (size_t)s.bh * s.N) + 3 * tensor + a256(sizeof(bf16_t) * km_partials(s) * s.D);
+    return a256(sizeof(float) * (size_t)s.bh * s.N) + tensor + a256(sizeof(bf16_t) * km_partials(s) * s.D);
 }
 
 template <int D, int NG, int KC>
-static hipError_t dq_launch3(const Dims& s, const void* Q, const void* dO, const void* Ka, const void* Va,
+static hipError_t dq_launch3(const Dims& s, const void* Q, const void* dO, const void* K, const void* V,
                              const void* Kt, const float* lse, const float* Dv, const int32_t* idx,
                              const int32_t* off, const int32_t* ql, bf16_t* PdQ, void* dQ, hipStream_t st)
 {
     using C = DqKmCfg<D>;
     const int nsub = s.B / km_part_keys(s.B, s.D);
     hipError_t e = hipFuncSetAttribute((const void*)dq_km_kernel<D, NG, KC>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::lds(NG));
     if (e != hipSuccess) return e;
     {
         ProfileScope timing(MOBA_PROFILE_DQ, st);
         hipLaunchKernelGGL((dq_km_kernel<D, NG, KC>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
-                           dim3(C::NT), C::LDS, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ka,
-                           (const bf16_t*)Va, (const bf16_t*)Kt, lse, Dv, idx, off, ql, PdQ, s.N, s.B, s.n,
+                           dim3(C::NT), C::lds(NG), st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)K,
+                           (const bf16_t*)V, (const bf16_t*)Kt, lse, Dv, idx, off, ql, PdQ, s.N, s.B, s.n,
                            s.k, nsub, s.scale, s.R, s.bh);
     }
     const int64_t rows = (int64_t)s.bh * s.N;
@@ -342,19 +350,11 @@ hipError_t launch_dq_km(const Dims& s, const void* Q, const void* K, const void*
     p += a256(sizeof(float) * (size_t)s.bh * s.N);
     void* Kt = p;
     p += tensor;
-    void* Ka = p;
-    p += tensor;
-    void* Va = p;
-    p += tensor;
     bf16_t* PdQ = reinterpret_cast<bf16_t*>(p);
     hipError_t e = launch_slot_major_copy(s, K, Kt, nullptr, st);
     if (e != hipSuccess) return e;
-    e = launch_operand_copy(s, K, Ka, st);
-    if (e != hipSuccess) return e;
-    e = launch_operand_copy(s, V, Va, st);
-    if (e != hipSuccess) return e;
-    return s.D == 64 ? dq_launch<64>(s, Q, dO, Ka, Va, Kt, lse, Dv, idx, off, ql, PdQ, dQ, st)
-                     : dq_launch<128>(s, Q, dO, Ka, Va, Kt, lse, Dv, idx, off, ql, PdQ, dQ, st);
+    return s.D == 64 ? dq_launch<64>(s, Q, dO, K, V, Kt, lse, Dv, idx, off, ql, PdQ, dQ, st)
+                     : dq_launch<128>(s, Q, dO, K, V, Kt, lse, Dv, idx, off, ql, PdQ, dQ, st);
 }
 
 }  // namespace moba

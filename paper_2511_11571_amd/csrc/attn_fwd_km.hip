@@ -34,14 +34,15 @@ struct KmCfg {
     static constexpr int CPR = D / 8;                  // 16-byte chunks per row = lanes per gathered row
     static constexpr int RPI = kWave / CPR;            // rows per gather instruction
     static constexpr int NI = 32 / RPI;                // gather instructions per step
-    static constexpr size_t LDS = (size_t)NW * 32 * SB;
+    static constexpr size_t PARK = (size_t)NW * 32 * SB;                 // the waves' parked rows
+    static constexpr size_t lds(int ng) { return PARK + (size_t)ng * 64 * D; }   // + the part's keys
 };
 
 // NG: 32-key groups per workgroup; KC: a query's row of kept blocks is searched CPR entries at a
 // time, KC times (k <= KC * CPR)
 template <int D, int NG, int KC>
 __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
-    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Ka, const bf16_t* __restrict__ Vt,
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ off, const int32_t* __restrict__ ql,
     bf16_t* __restrict__ PO, float* __restrict__ Pml, int N, int B, int n, int k, int nsub,
     float scale, int64_t R, int bh)
@@ -51,6 +52,7 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int m16 = lane & 15, g = lane >> 4;
     unsigned char* stQ = smem + (size_t)wave * 32 * C::SB;
+    unsigned char* sK = smem + C::PARK;
 
     int s, u;                                               // slice, (key block, part)
     if (!schedule(blockIdx.x, bh, n * nsub, s, u)) return;
@@ -66,24 +68,31 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
     const char* Qg = reinterpret_cast<const char*>(Q + sbase * D);
     const uint32_t vlane = (uint32_t)lane * 16u;
 
-    // the part's keys and values as MFMA operands, resident for the whole walk
-    Frag ka[NG][2][C::KS], va[NG][C::MT];
+    // The part's keys go to LDS in MFMA operand order -- the 16 bytes lane (m, g) feeds as rows
+    // 16 mt + m, channels 32 ks + 8 g .. + 8 of 32-key group gi sit at
+    // ((gi * 2 + mt) * KS + ks) * 1024 + 16 * lane -- and are read from there in every step; the
+    // values (transposed, slot order) stay in registers for the whole walk.  (Keys in registers
+    // as well would leave room for one wave per SIMD only, and the walk needs a second one to
+    // fill the waits of the first.)
     {
-        const char* Kag = reinterpret_cast<const char*>(Ka + (sbase + own0) * D);
+        const char* Kg = reinterpret_cast<const char*>(K + (sbase + own0) * D);
+        for (int ch = tid; ch < NG * 32 * C::CPR; ch += C::NT) {
+            const int row = ch / C::CPR, col = ch % C::CPR;             // key of the part, 16-byte piece
+            const int gi = row >> 5, mt = (row >> 4) & 1, m = row & 15, ks = col >> 2, gg = col & 3;
+            *reinterpret_cast<kmvec4_t*>(sK + ((gi * 2 + mt) * C::KS + ks) * 1024 + (16 * gg + m) * 16) =
+                *reinterpret_cast<const kmvec4_t*>(Kg + (size_t)ch * 16);
+        }
+    }
+    Frag va[NG][C::MT];
+    {
         const char* Vtg = reinterpret_cast<const char*>(Vt + (sbase + own0) * D);
 #pragma unroll
-        for (int gi = 0; gi < NG; ++gi) {
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int ks = 0; ks < C::KS; ++ks)
-                    ka[gi][mt][ks].q = *reinterpret_cast<const uint4*>(Kag + gi * (64 * D) + vlane +
-                                                                       (mt * C::KS + ks) * 1024);
+        for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
             for (int mt = 0; mt < C::MT; ++mt)
                 va[gi][mt].q = *reinterpret_cast<const uint4*>(Vtg + gi * (64 * D) + vlane + mt * 1024);
-        }
     }
+    __syncthreads();
 
     // every load of the walk is unconditional and from an address that is always valid (a load
     // inside a branch is waited for at the end of the branch)
@@ -176,7 +185,11 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
                 for (int mt = 0; mt < 2; ++mt) {
                     f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int ks = 0; ks < C::KS; ++ks) sc = mfma16(ka[gi][mt][ks], qb[ks], sc);
+                    for (int ks = 0; ks < C::KS; ++ks) {
+                        Frag ka;
+                        ka.q = *reinterpret_cast<const uint4*>(sK + ((gi * 2 + mt) * C::KS + ks) * 1024 + vlane);
+                        sc = mfma16(ka, qb[ks], sc);
+                    }
 #pragma unroll
                     for (int i = 0; i < 4; ++i) x[gi][4 * mt + i] = sc[i];
                 }
@@ -286,8 +299,8 @@ __global__ __launch_bounds__(256) void fwd_km_merge_kernel(
     if (part == 0) lse[row] = (M + fast_log2(L)) * kLn2;
 }
 
-// ---- workspace: [slot-ordered V][operand-ordered K][partial O: bh*N*(k+1)*parts*D bf16]
-// [partial (m, l): bh*N*(k+1)*parts*2 fp32], each 256-byte aligned
+// ---- workspace: [slot-ordered V][partial O: bh*N*(k+1)*parts*D bf16][partial (m, l):
+// bh*N*(k+1)*parts*2 fp32], each 256-byte aligned
 static size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static size_t km_partials(const Dims& s)
@@ -298,23 +311,23 @@ static size_t km_partials(const Dims& s)
 size_t forward_km_ws_bytes(const Dims& s)
 {
     const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
-    return 2 * tensor + a256(sizeof(bf16_t) * km_partials(s) * s.D) + a256(sizeof(float) * km_partials(s) * 2);
+    return tensor + a256(sizeof(bf16_t) * km_partials(s) * s.D) + a256(sizeof(float) * km_partials(s) * 2);
 }
 
 template <int D, int NG, int KC>
-static hipError_t km_launch3(const Dims& s, const void* Q, const void* Ka, const void* Vt,
+static hipError_t km_launch3(const Dims& s, const void* Q, const void* K, const void* Vt,
                              const int32_t* idx, const int32_t* off, const int32_t* ql, bf16_t* PO,
                              float* Pml, void* O, float* lse, hipStream_t st)
 {
     using C = KmCfg<D>;
     const int nsub = s.B / km_part_keys(s.B, s.D);
     hipError_t e = hipFuncSetAttribute((const void*)fwd_km_kernel<D, NG, KC>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::lds(NG));
     if (e != hipSuccess) return e;
     {
         ProfileScope timing(MOBA_PROFILE_FORWARD, st);
         hipLaunchKernelGGL((fwd_km_kernel<D, NG, KC>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
-                           dim3(C::NT), C::LDS, st, (const bf16_t*)Q, (const bf16_t*)Ka, (const bf16_t*)Vt,
+                           dim3(C::NT), C::lds(NG), st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)Vt,
                            idx, off, ql, PO, Pml, s.N, s.B, s.n, s.k, nsub, s.scale, s.R, s.bh);
     }
     const int64_t rows = (int64_t)s.bh * s.N;
@@ -355,17 +368,13 @@ hipError_t launch_forward_km(const Dims& s, const void* Q, const void* K, const 
     char* p = static_cast<char*>(ws);
     void* Vt = p;
     p += tensor;
-    void* Ka = p;
-    p += tensor;
     bf16_t* PO = reinterpret_cast<bf16_t*>(p);
     p += a256(sizeof(bf16_t) * km_partials(s) * s.D);
     float* Pml = reinterpret_cast<float*>(p);
     hipError_t e = launch_slot_major_copy(s, V, Vt, nullptr, st);
     if (e != hipSuccess) return e;
-    e = launch_operand_copy(s, K, Ka, st);
-    if (e != hipSuccess) return e;
-    return s.D == 64 ? km_launch<64>(s, Q, Ka, Vt, idx, off, ql, PO, Pml, O, lse, st)
-                     : km_launch<128>(s, Q, Ka, Vt, idx, off, ql, PO, Pml, O, lse, st);
+    return s.D == 64 ? km_launch<64>(s, Q, K, Vt, idx, off, ql, PO, Pml, O, lse, st)
+                     : km_launch<128>(s, Q, K, Vt, idx, off, ql, PO, Pml, O, lse, st);
 }
 
 }  // namespace moba

@@ -219,7 +219,7 @@ bool topk_mfma_supported(const Dims& s);
 hipError_t launch_topk_mfma(const Dims& s, const void* Q, const float* cent, int32_t* idx, void* ws,
                             hipStream_t st);
 
-constexpr int kKeyMajorBelowRows = 8;     // rows per (tile, block) visit below which key-major wins
+constexpr int kKeyMajorAboveRatio = 20;    // N / (T k) above which the key-major kernels win
 constexpr int kKeyMajorMaxTopk = 64;      // longest row of kept blocks the key-major walk searches
 
 // keys a key-major workgroup holds in registers as MFMA operands: the whole block up to 128
@@ -243,14 +243,16 @@ inline bool key_major_shape(const Dims& s)
 }
 
 // Query-tile or key-major attention?  A tile of T consecutive queries (256 for d = 64, 128 for
-// d = 128) meets a past key block with about T k / n of its rows; the tile kernels need a good
-// part of a 16-row MFMA tile there, the key-major kernels do not care.
+// d = 128) meets a past key block with about T k / n of its rows and pays for at least a
+// 16-row MFMA tile against the block's B keys; the key-major kernels pay a fixed price per
+// (query, block) pair -- the gathered row, the partial result written and read back --
+// whatever B.  Measured, the two meet near B n / (T k) = N / (T k) = 20.
 inline bool key_major_path(const Dims& s)
 {
     if (!key_major_shape(s) || (s.flags & MOBA_FLAG_QUERY_TILES)) return false;
     if (s.flags & MOBA_FLAG_KEY_MAJOR) return true;
     const int T = s.D == 64 ? 256 : 128;
-    return (int64_t)T * s.k <= (int64_t)kKeyMajorBelowRows * s.n;
+    return s.k > 0 && (int64_t)s.N > (int64_t)kKeyMajorAboveRatio * T * s.k;
 }
 
 size_t forward_km_ws_bytes(const Dims& s);
