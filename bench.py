@@ -50,6 +50,11 @@ def parse():
                     help="force the plain (non-MFMA) kernels")
     ap.add_argument("--attention", choices=["auto", "tiles", "keymajor"], default="auto",
                     help="force the query-tile or the key-block-major attention kernels")
+    ap.add_argument("--latency-sweep", default="",
+                    help="instead of one workload: the paper's latency sweep (Section 5.3: batch 2, "
+                         "B = 128, top-k 8, forward + backward; here 16 heads of d = 64) over the "
+                         "comma-separated sequence lengths given, e.g. 8192,16384,...,524288; "
+                         "prints one JSON line with one point per length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB device to device once (a kernel of "
@@ -112,28 +117,8 @@ def cpu_baseline(w, t, target_seconds=15.0, max_slices=0):
     }
 
 
-def main():
-    a = parse()
-    if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (every (batch, head) slice is independent; "
-              "multi-GPU sharding is described in DESIGN.md but not built). Use --gpus 1.",
-              file=sys.stderr)
-        sys.exit(2)
-    import torch
-    import workloads
-    import paper_2511_11571_amd as moba
-    from paper_2511_11571_amd import binding
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    w = workloads.CONFIGS[a.config]
-    if a.shape:
-        f = a.shape.split(",")
-        b_, h_, N_, d_, B_, k_ = (int(x) for x in f[:6])
-        w = workloads.Workload("shape_%s" % a.shape.replace(",", "_"), b_, h_, N_, d_, B_, k_,
-                               backward=not (len(f) > 6 and f[6] == "fwd"), seed=9000)
-        a.config = 0
+def measure(w, a, moba, binding, workloads, torch):
+    """Times a.steps passes of the whole path over workload w (inputs resident in HBM)."""
     t = workloads.generate(w)
     d = {k: (v.cuda() if v is not None else None) for k, v in t.items()}
     flags = binding.FLAG_REFERENCE_KERNELS if a.reference_kernels else 0
@@ -187,6 +172,55 @@ def main():
     ms_step = 1e3 * wall / a.steps
     stage_ms = {name: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(a.steps)) / a.steps
                 for i, name in enumerate(stages)}
+
+    return {"t": t, "d": d, "sh": sh, "R": R, "dev": dev, "ms_step": ms_step, "stage_ms": stage_ms,
+            "kernel_ms": kernel_ms, "stages": stages}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (every (batch, head) slice is independent; "
+              "multi-GPU sharding is described in DESIGN.md but not built). Use --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads
+    import paper_2511_11571_amd as moba
+    from paper_2511_11571_amd import binding
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    if a.latency_sweep:
+        points = []
+        for N_ in (int(x) for x in a.latency_sweep.split(",")):
+            w = workloads.Workload("sweep_N%d" % N_, 2, 16, N_, 64, 128, 8, backward=True, seed=9100)
+            m = measure(w, a, moba, binding, workloads, torch)
+            points.append({"N": N_, "ms_per_step": m["ms_step"], "stage_ms": m["stage_ms"],
+                           "kernel_ms": m["kernel_ms"],
+                           "effective_tflops": 14.0 * w.d * w.bh * workloads.attended_pairs_per_slice(
+                               w.N, w.B, w.k) / (m["ms_step"] * 1e-3) / 1e12})
+            del m
+            torch.cuda.empty_cache()
+        print(json.dumps({
+            "metric": "moba_fwd_bwd_latency_sweep", "unit": "ms", "n_gpus": 1, "steps": a.steps,
+            "warmup": a.warmup, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "batch 2, heads 16, d 64, B 128, top-k 8, forward+backward "
+                                   "(gate + top-k + lists + attention + gradients)",
+                       "attention": a.attention},
+            "points": points}))
+        return
+    w = workloads.CONFIGS[a.config]
+    if a.shape:
+        f = a.shape.split(",")
+        b_, h_, N_, d_, B_, k_ = (int(x) for x in f[:6])
+        w = workloads.Workload("shape_%s" % a.shape.replace(",", "_"), b_, h_, N_, d_, B_, k_,
+                               backward=not (len(f) > 6 and f[6] == "fwd"), seed=9000)
+        a.config = 0
+    m = measure(w, a, moba, binding, workloads, torch)
+    t, d, sh, R, dev = m["t"], m["d"], m["sh"], m["R"], m["dev"]
+    ms_step, stage_ms, kernel_ms, stages = m["ms_step"], m["stage_ms"], m["kernel_ms"], m["stages"]
 
     pairs = w.bh * workloads.attended_pairs_per_slice(w.N, w.B, w.k)
     fwd_flop = 4.0 * w.d * pairs

@@ -50,13 +50,16 @@ typedef enum moba_dtype { MOBA_F32 = 0, MOBA_BF16 = 1 } moba_dtype;
 
 /* flags */
 #define MOBA_FLAG_REFERENCE_KERNELS 1u /* use the plain (non-MFMA) kernels for every stage */
-#define MOBA_FLAG_KEY_MAJOR 2u         /* attention by key block (suits sparse routing): force it
-                                        * where that path exists (bf16; B a multiple of 32 up to
-                                        * 128, or a multiple of 128; topk <= 64)                  */
+#define MOBA_FLAG_KEY_MAJOR 2u         /* attention forward and dQ by key block with one partial per
+                                        * (query, block) pair and a merge kernel (paper Section 4.2):
+                                        * force it where that path exists (bf16; B a multiple of 32
+                                        * up to 128 (d = 64) / 64 (d = 128), or a multiple of that;
+                                        * topk <= 64); elsewhere the flag is ignored              */
 #define MOBA_FLAG_QUERY_TILES 4u       /* attention by query tile (suits dense routing): force it   */
-/* with neither of the two the library picks by the expected number of rows with which a query
- * tile meets a key block; forward and backward of one call pair must see the same flags only
- * in so far as their workspaces are sized for the flags given */
+/* With neither of the two the library picks: key blocks if seqlen > 20 * T * topk (T = 256 queries
+ * per tile at d = 64, 128 at d = 128), i.e. where a tile would meet a key block with too few of
+ * its rows; query tiles otherwise.  KEY_MAJOR and QUERY_TILES together are MOBA_EINVAL.  The
+ * workspace sizes depend on the choice: size and call with the same flags. */
 
 typedef struct moba_shape {
     int32_t batch, heads, seqlen, head_dim;

@@ -25,7 +25,7 @@ namespace moba {
 constexpr int kHistWords = 32;            // 64 bins of 16 bits per query
 constexpr int kHistStride = 33;           // odd row stride: queries land on different LDS banks
 constexpr int kCand = 16;                 // a final bin this small is resolved from a candidate list
-constexpr int kTopkMfmaMaxBlocks = 2048;  // bit row of a query: at most 64 words
+constexpr int kTopkMfmaMaxBlocks = 4096;  // a 16-bit histogram bin holds any count of blocks up to this
 
 // c3 <- the three bf16 terms of the fp32 centroids, in MFMA operand order: the 16 bytes lane
 // (m, g) feeds to the MFMA for blocks 16 jt + m, channels 32 ks + 8 g .. + 8, term t, sit at

@@ -142,8 +142,12 @@ def test_key_conv_backward(oracle, dtype, d, width, N):
 
 # ------------------------------------------------------------------ routing
 
+# the largest number of key blocks per head the library takes (4096), ragged against the bit rows
+MANY_BLOCKS = [W("n4096_B2", 1, 1, 8192, 64, 2, 8, seed=23), W("n4000_B2_k40", 1, 1, 8000, 64, 2, 40, seed=24)]
+
+
 @pytest.mark.parametrize("flags", FLAGS)
-@pytest.mark.parametrize("w", SMALL, ids=IDS)
+@pytest.mark.parametrize("w", SMALL + MANY_BLOCKS, ids=IDS + [w.name for w in MANY_BLOCKS])
 def test_topk_and_lists(oracle, w, flags):
     t = workloads.generate(w)
     Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
