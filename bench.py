@@ -55,6 +55,10 @@ def parse():
                          "B = 128, top-k 8, forward + backward; here 16 heads of d = 64) over the "
                          "comma-separated sequence lengths given, e.g. 8192,16384,...,524288; "
                          "prints one JSON line with one point per length")
+    ap.add_argument("--dense-upto", type=int, default=0,
+                    help="with --latency-sweep: for sequence lengths up to this one also time the "
+                         "same kernels with every past block kept (top-k = n: full causal attention), "
+                         "the reference line of the sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB device to device once (a kernel of "
@@ -203,6 +207,13 @@ def main():
                                w.N, w.B, w.k) / (m["ms_step"] * 1e-3) / 1e12})
             del m
             torch.cuda.empty_cache()
+            if N_ <= a.dense_upto:
+                wd = workloads.Workload("dense_N%d" % N_, 2, 16, N_, 64, 128, N_ // 128, backward=True, seed=9100)
+                m = measure(wd, a, moba, binding, workloads, torch)
+                points[-1]["dense_ms_per_step"] = m["ms_step"]
+                points[-1]["dense_stage_ms"] = m["stage_ms"]
+                del m
+                torch.cuda.empty_cache()
         print(json.dumps({
             "metric": "moba_fwd_bwd_latency_sweep", "unit": "ms", "n_gpus": 1, "steps": a.steps,
             "warmup": a.warmup, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
