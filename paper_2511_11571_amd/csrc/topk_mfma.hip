@@ -71,48 +71,45 @@ __device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int ti
                                             int step, const Frag (&qb)[4][D / 32], int lane, int g, F f)
 {
     constexpr int KS = D / 32;
-    auto load = [&](int jt, Frag (&a)[3][KS]) {
-        const char* tb = c3s + (int64_t)jt * (3 * KS * 1024) + lane * 16;
+    // One tile of operands in registers: the MFMAs of a term are issued, then the same term of
+    // the wave's next tile is loaded over it, so every load has a whole tile of work to arrive.
+    // (Past the last tile the loads repeat that tile: unconditional, always valid.)
+    Frag a[3][KS];
+    auto load = [&](int jt, int term) {
+        const char* tb = c3s + (int64_t)jt * (3 * KS * 1024) + lane * 16 + term * (KS * 1024);
 #pragma unroll
-        for (int term = 0; term < 3; ++term)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                a[term][ks].q = *reinterpret_cast<const uint4*>(tb + (term * KS + ks) * 1024);
+        for (int ks = 0; ks < KS; ++ks) a[term][ks].q = *reinterpret_cast<const uint4*>(tb + ks * 1024);
     };
-    auto run = [&](int jt, const Frag (&a)[3][KS]) {
+    int jt = tile_lo;
+    if (jt >= tile_hi) return;
+#pragma unroll
+    for (int term = 2; term >= 0; --term) load(jt, term);
+    while (jt < tile_hi) {
+        const int nx = jt + step, ld = nx < tile_hi ? nx : jt;
         // the four 16-query tiles are independent accumulation chains: issue them interleaved so
         // that no MFMA waits for the one before it
         f32x4_t sc[4];
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) sc[qt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int term = 2; term >= 0; --term)           // smallest terms first
+        for (int term = 2; term >= 0; --term) {         // smallest terms first
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int qt = 0; qt < 4; ++qt) sc[qt] = mfma16(a[term][ks], qb[qt][ks], sc[qt]);
+            load(ld, term);
+        }
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) f(qt, sc[qt], 16 * jt + 4 * g);
-    };
-    // the operands of the next tile are in flight while the current one is worked on
-    Frag a0[3][KS], a1[3][KS];
-    int jt = tile_lo;
-    if (jt < tile_hi) load(jt, a0);
-    while (jt < tile_hi) {
-        if (jt + step < tile_hi) load(jt + step, a1);
-        run(jt, a0);
-        jt += step;
-        if (jt >= tile_hi) break;
-        if (jt + step < tile_hi) load(jt + step, a0);
-        run(jt, a1);
-        jt += step;
+        jt = nx;
     }
 }
 
 constexpr int kTopkWaves = 2;             // waves per 64-query strip (= per workgroup)
 
 template <int D>
-__global__ __launch_bounds__(kTopkWaves * kWave) void topk_mfma_kernel(
+__global__ __launch_bounds__(kTopkWaves * kWave) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2)))
+void topk_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ c3, int ntile_all,
     int32_t* __restrict__ idx, int N, int B, int n, int k, int strips_per_slice, int Wn)
 {
