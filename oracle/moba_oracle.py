@@ -7,8 +7,9 @@ module imports nothing from the GPU package.
 All tensors are numpy float64, row-major ``[bh, N, d]`` (batch*heads flattened).
 The arithmetic lives in the C file; this module only marshals arguments, plus two
 one-line numpy steps that are part of the definition:
-``D = rowsum(dO * O)`` (paper Appendix C.3, backward preprocessing) and the
-count of routed pairs.
+``D = rowsum(dO * O)`` (paper Appendix C.3, backward preprocessing), the
+count of routed pairs, and the head sharing of grouped-query attention written out
+as a copy (forward) and a sum (gradients) -- Appendix C, last paragraph.
 """
 from __future__ import annotations
 
@@ -237,6 +238,36 @@ def attn_bwd(Q, K, V, idx, dO, B, scale):
     dQ = attn_bwd_dq(Q, K, V, idx, dO, lse, Dv, B, scale)
     dK, dV = attn_bwd_dkdv(Q, K, V, dO, lse, Dv, off, ql, B, scale)
     return dQ, dK, dV
+
+
+def gqa_expand(X, heads, kv_heads):
+    """Grouped-query / multi-query attention (Appendix C, last paragraph): query head h
+    reads key/value head h // (heads / kv_heads).  The paper's kernels remap indices
+    instead of duplicating; the duplication written out is the definition.
+    ``X`` is ``[batch*kv_heads, ...]``; returns ``[batch*heads, ...]``, after which
+    every other function of this module applies head by head."""
+    X = np.asarray(X)
+    assert heads % kv_heads == 0 and X.shape[0] % kv_heads == 0
+    G, b = heads // kv_heads, X.shape[0] // kv_heads
+    Y = np.empty((b, heads) + X.shape[1:], dtype=X.dtype)
+    Xv = X.reshape((b, kv_heads) + X.shape[1:])
+    for h in range(heads):
+        Y[:, h] = Xv[:, h // G]
+    return Y.reshape((b * heads,) + X.shape[1:])
+
+
+def gqa_reduce(dX, heads, kv_heads):
+    """Gradients of shared key/value heads are summed over the query heads that share
+    them (same paragraph).  ``dX`` is ``[batch*heads, ...]`` (per query head, e.g. from
+    attn_bwd on expanded K, V); returns ``[batch*kv_heads, ...]``."""
+    dX = np.asarray(dX, dtype=np.float64)
+    assert heads % kv_heads == 0 and dX.shape[0] % heads == 0
+    G, b = heads // kv_heads, dX.shape[0] // heads
+    out = np.zeros((b, kv_heads) + dX.shape[1:], dtype=np.float64)
+    dv = dX.reshape((b, heads) + dX.shape[1:])
+    for h in range(heads):
+        out[:, h // G] += dv[:, h]
+    return out.reshape((b * kv_heads,) + dX.shape[1:])
 
 
 def moba_forward(Q, K, V, B, k, scale, conv_w=None, heads=1, round_mode=ROUND_NONE):

@@ -418,6 +418,58 @@ def test_backward_matches_autograd_on_dense_mask(oracle):
         np.testing.assert_allclose(dV[s], v.grad.numpy(), atol=1e-12)
 
 
+def test_grouped_query_heads_share_keys_and_sum_gradients(oracle):
+    """Appendix C, last paragraph.  Forward: each query head against the key/value head
+    h // G, by brute force with an explicit mask.  Gradients of the shared heads: torch's
+    autograd through repeat_interleave (whose backward is that sum), and finite
+    differences of the whole shared-head loss."""
+    b, H, Hkv, N, d, B, k = 2, 6, 2, 32, 4, 4, 2
+    G = H // Hkv
+    r = RNG(70)
+    Q = r.standard_normal((b * H, N, d))
+    K = r.standard_normal((b * Hkv, N, d))
+    V = r.standard_normal((b * Hkv, N, d))
+    dO = r.standard_normal((b * H, N, d))
+    scale = 0.5
+    # the remap itself, against explicit indexing, and G = 1 is the identity
+    Ke, Ve = oracle.gqa_expand(K, H, Hkv), oracle.gqa_expand(V, H, Hkv)
+    for bb in range(b):
+        for h in range(H):
+            assert np.array_equal(Ke[bb * H + h], K[bb * Hkv + h // G])
+    assert np.array_equal(oracle.gqa_expand(K, Hkv, Hkv), K)
+    assert np.array_equal(oracle.gqa_reduce(Ke, Hkv * 1, Hkv)[0], Ke[0])
+    res = oracle.moba_forward(Q, Ke, Ve, B, k, scale)
+    for bb in range(b):
+        for h in range(H):
+            s, skv = bb * H + h, bb * Hkv + h // G
+            mask, chosen = brute.block_mask(Q[s], K[skv], B, k)
+            assert all(_sets(res["idx"][s, t]) == chosen[t] for t in range(N))
+            O, lse, _ = brute.dense_attention(Q[s], K[skv], V[skv], mask, scale)
+            np.testing.assert_allclose(res["O"][s], O, rtol=0, atol=1e-12)
+    idx = res["idx"]
+    dQ, dKe, dVe = oracle.attn_bwd(Q, Ke, Ve, idx, dO, B, scale)
+    dK, dV = oracle.gqa_reduce(dKe, H, Hkv), oracle.gqa_reduce(dVe, H, Hkv)
+    # the sum over sharing heads is the backward of the copy
+    x = torch.tensor(K.reshape(b, Hkv, N, d), requires_grad=True)
+    (x.repeat_interleave(G, dim=1) * torch.from_numpy(dKe.reshape(b, H, N, d))).sum().backward()
+    np.testing.assert_allclose(dK.reshape(b, Hkv, N, d), x.grad.numpy(), atol=1e-12)
+
+    def loss(kk, vv):
+        O, _ = oracle.attn_fwd(Q, oracle.gqa_expand(kk, H, Hkv), oracle.gqa_expand(vv, H, Hkv), idx, B, scale)
+        return float((O * dO).sum())
+
+    eps = 1e-6
+    for which, grad in (("K", dK), ("V", dV)):
+        for _ in range(10):
+            s, t, c = int(r.integers(b * Hkv)), int(r.integers(N)), int(r.integers(d))
+            args = {"K": K.copy(), "V": V.copy()}
+            args[which][s, t, c] += eps
+            up = loss(args["K"], args["V"])
+            args[which][s, t, c] -= 2 * eps
+            dn = loss(args["K"], args["V"])
+            assert abs((up - dn) / (2 * eps) - grad[s, t, c]) < 2e-7, (which, s, t, c)
+
+
 def test_backward_invariants(oracle):
     N, d, B, k = 32, 4, 4, 2
     Q, K, V = _rand(55, N, d)
