@@ -59,6 +59,9 @@ def parse():
                     help="with --latency-sweep: for sequence lengths up to this one also time the "
                          "same kernels with every past block kept (top-k = n: full causal attention), "
                          "the reference line of the sweep")
+    ap.add_argument("--kv-heads", type=int, default=0,
+                    help="grouped-query attention: key/value heads of the workload (0 = as many as "
+                         "query heads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB device to device once (a kernel of "
@@ -128,16 +131,16 @@ def measure(w, a, moba, binding, workloads, torch):
     flags = binding.FLAG_REFERENCE_KERNELS if a.reference_kernels else 0
     flags |= {"auto": 0, "tiles": binding.FLAG_QUERY_TILES, "keymajor": binding.FLAG_KEY_MAJOR}[a.attention]
     sh = moba.Shape(w.batch, w.heads, w.N, w.d, w.B, w.k, w.conv_width,
-                    binding.BF16 if w.dtype == "bf16" else binding.F32, 0.0, flags)
+                    binding.BF16 if w.dtype == "bf16" else binding.F32, 0.0, flags, w.kv_heads)
     R = moba.routes_per_slice(sh)
     ws_topk, ws_fwd, ws_bwd = (torch.empty(max(x, 256), dtype=torch.uint8, device="cuda")
                                for x in moba.workspace_bytes(sh))
     dev = torch.device("cuda")
     Keff = torch.empty_like(d["K"]) if w.conv_width else None
-    cent = torch.empty((w.batch, w.heads, w.n, w.d), dtype=torch.float32, device=dev)
+    cent = torch.empty((w.batch, w.hkv, w.n, w.d), dtype=torch.float32, device=dev)
     O = torch.empty_like(d["Q"])
     lse = torch.empty((w.batch, w.heads, w.N), dtype=torch.float32, device=dev)
-    grads = tuple(torch.empty_like(d["Q"]) for _ in range(3))
+    grads = (torch.empty_like(d["Q"]), torch.empty_like(d["K"]), torch.empty_like(d["V"]))
 
     stages = ["centroids", "topk_lists", "forward", "bwd_pre", "bwd_dq", "bwd_dkdv"]
     if not w.backward:
@@ -229,6 +232,9 @@ def main():
         w = workloads.Workload("shape_%s" % a.shape.replace(",", "_"), b_, h_, N_, d_, B_, k_,
                                backward=not (len(f) > 6 and f[6] == "fwd"), seed=9000)
         a.config = 0
+    if a.kv_heads:
+        w = w.scaled(kv_heads=a.kv_heads, name=w.name + "_kv%d" % a.kv_heads)
+        a.config = 0
     m = measure(w, a, moba, binding, workloads, torch)
     t, d, sh, R, dev = m["t"], m["d"], m["sh"], m["R"], m["dev"]
     ms_step, stage_ms, kernel_ms, stages = m["ms_step"], m["stage_ms"], m["kernel_ms"], m["stages"]
@@ -280,8 +286,9 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": "%s: batch %d, heads %d, N %d, d %d, B %d, top-k %d%s, %s" % (
-            w.name, w.batch, w.heads, w.N, w.d, w.B, w.k,
+        "config": {"workload": "%s: batch %d, heads %d%s, N %d, d %d, B %d, top-k %d%s, %s" % (
+            w.name, w.batch, w.heads, " (%d key/value heads)" % w.hkv if w.hkv != w.heads else "",
+            w.N, w.d, w.B, w.k,
             ", key conv W=%d" % w.conv_width if w.conv_width else "",
             "forward+backward" if w.backward else "forward"),
             "kernels": "plain" if a.reference_kernels else "default", "attention": a.attention,
@@ -319,7 +326,7 @@ def main():
         torch.cuda.synchronize()
         dst.copy_(src)
         torch.cuda.synchronize()
-    if not a.no_cpu_baseline:
+    if not a.no_cpu_baseline and w.hkv == w.heads:      # (the CPU leg times the multi-head form only)
         out["cpu_baseline"] = cpu_baseline(w, t, max_slices=a.cpu_max_slices)
     print(json.dumps(out))
 

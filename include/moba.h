@@ -69,6 +69,12 @@ typedef struct moba_shape {
     int32_t dtype;         /* moba_dtype                                               */
     float   softmax_scale; /* <= 0 selects 1/sqrt(head_dim)                            */
     uint32_t flags;        /* MOBA_FLAG_*                                              */
+    int32_t kv_heads;      /* grouped-query / multi-query attention (Appendix C, last paragraph):
+                            * key/value heads; 0 = heads.  Must divide heads; query head h reads
+                            * key/value head h / (heads / kv_heads).  Then K, V, K_eff, centroids,
+                            * dK, dV and dK_eff are [b,kv_heads,..], conv_w and dconv_w
+                            * [kv_heads,d,W]; Q, O, lse, dO, dQ and the routing stay [b,heads,..];
+                            * dK and dV are summed over the query heads that share the head. */
 } moba_shape;
 
 /* Host-only helpers.  R and the byte counts are written to host memory. */

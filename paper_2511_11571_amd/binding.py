@@ -31,7 +31,8 @@ class _CShape(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("seqlen", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("block", ctypes.c_int32), ("topk", ctypes.c_int32),
                 ("conv_width", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("softmax_scale", ctypes.c_float), ("flags", ctypes.c_uint32)]
+                ("softmax_scale", ctypes.c_float), ("flags", ctypes.c_uint32),
+                ("kv_heads", ctypes.c_int32)]
 
 
 @dataclass(frozen=True)
@@ -46,10 +47,15 @@ class Shape:
     dtype: int = BF16
     softmax_scale: float = 0.0
     flags: int = 0
+    kv_heads: int = 0          # grouped-query attention: key/value heads (0 = heads)
 
     def c(self):
         return _CShape(self.batch, self.heads, self.seqlen, self.head_dim, self.block, self.topk,
-                       self.conv_width, self.dtype, self.softmax_scale, self.flags)
+                       self.conv_width, self.dtype, self.softmax_scale, self.flags, self.kv_heads)
+
+    @property
+    def hkv(self):
+        return self.kv_heads if self.kv_heads > 0 else self.heads
 
     @property
     def n(self):
@@ -119,7 +125,7 @@ def centroids(shape: Shape, K, conv_w=None, K_eff=None, out=None):
     if shape.conv_width > 0 and K_eff is None:
         K_eff = torch.empty_like(K)
     if out is None:
-        out = torch.empty((shape.batch, shape.heads, shape.n, shape.head_dim), dtype=torch.float32,
+        out = torch.empty((shape.batch, shape.hkv, shape.n, shape.head_dim), dtype=torch.float32,
                           device=K.device)
     _check(lib().moba_centroids(ctypes.byref(shape.c()), _p(K), _p(conv_w), _p(K_eff), _p(out),
                                 _stream()), "moba_centroids")
@@ -204,8 +210,8 @@ def backward(shape: Shape, Q, K_eff, V, O, lse, dO, idx, lists, ws=None, out=Non
     off, ql = lists
     for t in (Q, K_eff, V, O, dO):
         assert t.is_contiguous() and t.dtype == shape.torch_dtype
-    dQ, dK, dV = out if out is not None else (torch.empty_like(Q), torch.empty_like(Q),
-                                              torch.empty_like(Q))
+    dQ, dK, dV = out if out is not None else (torch.empty_like(Q), torch.empty_like(K_eff),
+                                              torch.empty_like(V))
     if ws is None:
         ws = _ws(workspace_bytes(shape)[2], Q)
     if parts is None:

@@ -59,7 +59,8 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ Dv,
     const int32_t* __restrict__ off, const int32_t* __restrict__ ql, bf16_t* __restrict__ dK,
-    bf16_t* __restrict__ dV, int N, int B, int n, float scale, int64_t R, int groups_per_slice, int bh)
+    bf16_t* __restrict__ dV, int N, int B, int n, float scale, int64_t R, int groups_per_slice, int bhk,
+    int G)
 {
     using C = DkvCfg<D>;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -71,19 +72,13 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
     float* Ds = ls + 32;
     float* red = reinterpret_cast<float*>(smem + C::NW * (C::STAGE + 256));    // [2][32][RSTRIDE]
 
-    int s, kap;                                             // slice, 32-key group inside the slice
-    if (!schedule(blockIdx.x, bh, groups_per_slice, s, kap)) return;
+    int skv, kap;                                           // key/value slice, 32-key group inside it
+    if (!schedule(blockIdx.x, bhk, groups_per_slice, skv, kap)) return;
     const int NG = B / 32;
     const int j = kap / NG;
-    const int64_t sbase = (int64_t)s * N;
+    const int64_t kvbase = (int64_t)skv * N;
     const float c2 = scale * kLog2e;
-    const int32_t* os = off + (int64_t)s * (n + 1);
-    const int32_t* qs = ql + (int64_t)s * R;
-    const int lo = os[j], nlist = os[j + 1] - lo;
     const int own0 = 32 * kap;                              // first own query that sees this group
-    const int total = nlist + (j + 1) * B - own0;
-    const char* Qg = reinterpret_cast<const char*>(Q + sbase * D);
-    const char* Gg = reinterpret_cast<const char*>(dO + sbase * D);
 
     // B operands: the group's keys and values (lane = key m16 of tile nt)
     Frag kb[2][C::KS], vb[2][C::KS];
@@ -91,7 +86,7 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
     for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) {
-            const int64_t o = (sbase + 32 * kap + 16 * nt + m16) * D + 8 * g + 32 * ks;
+            const int64_t o = (kvbase + 32 * kap + 16 * nt + m16) * D + 8 * g + 32 * ks;
             kb[nt][ks].q = *reinterpret_cast<const uint4*>(K + o);
             vb[nt][ks].q = *reinterpret_cast<const uint4*>(V + o);
         }
@@ -103,6 +98,18 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
             dKT[mt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             dVT[mt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         }
+
+    // The G query heads that share this key/value head (grouped-query attention, Appendix C, last
+    // paragraph), one after the other: each has its own list for the block; dK and dV add up in
+    // the same accumulators.
+    for (int s = skv * G; s < (skv + 1) * G; ++s) {
+    const int64_t sbase = (int64_t)s * N;
+    const int32_t* os = off + (int64_t)s * (n + 1);
+    const int32_t* qs = ql + (int64_t)s * R;
+    const int lo = os[j], nlist = os[j + 1] - lo;
+    const int total = nlist + (j + 1) * B - own0;
+    const char* Qg = reinterpret_cast<const char*>(Q + sbase * D);
+    const char* Gg = reinterpret_cast<const char*>(dO + sbase * D);
 
     // position a of the walk -> query: the block's list, then its own queries from this group on;
     // positions past the end read as the first own query (a valid row; its P is forced to 0).
@@ -245,6 +252,7 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
     int a0 = 32 * wave;
     for (; a0 + 2 * stride + 32 <= nlist; a0 += stride) step(a0, std::true_type());
     for (; a0 < total; a0 += stride) step(a0, std::false_type());
+    }
 
     // sum the four waves' accumulators through LDS: red[tensor][key][channel]
     for (int w = 0; w < C::NW; ++w) {
@@ -274,7 +282,7 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
         float v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = src[e] * mul;
-        bf16_t* dst = (which == 0 ? dK : dV) + (sbase + 32 * kap + key) * D + 8 * c;
+        bf16_t* dst = (which == 0 ? dK : dV) + (kvbase + 32 * kap + key) * D + 8 * c;
         Vec8<bf16_t>::store(dst, v);
     }
 }
@@ -291,9 +299,9 @@ static hipError_t dkdv_launch(const Dims& s, const void* Q, const void* K, const
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
     if (e != hipSuccess) return e;
     ProfileScope timing(MOBA_PROFILE_DKDV, st);
-    hipLaunchKernelGGL((dkdv_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, gps)), dim3(C::NT), C::LDS, st,
+    hipLaunchKernelGGL((dkdv_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bhk, gps)), dim3(C::NT), C::LDS, st,
                        (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, Dv,
-                       off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, gps, s.bh);
+                       off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, gps, s.bhk, s.G);
     return hipGetLastError();
 }
 

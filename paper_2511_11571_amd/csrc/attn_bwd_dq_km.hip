@@ -46,7 +46,7 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kt, const float* __restrict__ lse,
     const float* __restrict__ Dv, const int32_t* __restrict__ idx, const int32_t* __restrict__ off,
     const int32_t* __restrict__ ql, bf16_t* __restrict__ PdQ, int N, int B, int n, int k, int nsub,
-    float scale, int64_t R, int bh)
+    float scale, int64_t R, int bh, int G)
 {
     using C = DqKmCfg<D>;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -64,6 +64,7 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     const int j = u / nsub, c = u - j * nsub;
     const int own_first = c * (32 * NG);                    // first key of the part inside the block
     const int64_t sbase = (int64_t)s * N;
+    const int64_t kvbase = (int64_t)(s / G) * N;            // G query heads share a key/value head
     const float c2 = scale * kLog2e;
     const int32_t* os = off + (int64_t)s * (n + 1);
     const int32_t* qs = ql + (int64_t)s * R;
@@ -83,8 +84,8 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     // room for one wave per SIMD only, and the walk needs a second one to fill the waits of the
     // first.)
     {
-        const char* Kg = reinterpret_cast<const char*>(K + (sbase + own0) * D);
-        const char* Vg = reinterpret_cast<const char*>(V + (sbase + own0) * D);
+        const char* Kg = reinterpret_cast<const char*>(K + (kvbase + own0) * D);
+        const char* Vg = reinterpret_cast<const char*>(V + (kvbase + own0) * D);
         for (int ch = tid; ch < NG * 32 * C::CPR; ch += C::NT) {
             const int row = ch / C::CPR, col = ch % C::CPR;             // key of the part, 16-byte piece
             const int gi = row >> 5, mt = (row >> 4) & 1, m = row & 15, ks = col >> 2, gg = col & 3;
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     }
     Frag kt[NG][C::MT];
     {
-        const char* Ktg = reinterpret_cast<const char*>(Kt + (sbase + own0) * D);
+        const char* Ktg = reinterpret_cast<const char*>(Kt + (kvbase + own0) * D);
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
@@ -289,7 +290,7 @@ static size_t km_partials(const Dims& s)
 
 size_t backward_km_ws_bytes(const Dims& s)
 {
-    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
+    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bhk * s.N * s.D);
     return a256(sizeof(float) * (size_t)s.bh * s.N) + tensor + a256(sizeof(bf16_t) * km_partials(s) * s.D);
 }
 
@@ -308,7 +309,7 @@ static hipError_t dq_launch3(const Dims& s, const void* Q, const void* dO, const
         hipLaunchKernelGGL((dq_km_kernel<D, NG, KC>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
                            dim3(C::NT), C::lds(NG), st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)K,
                            (const bf16_t*)V, (const bf16_t*)Kt, lse, Dv, idx, off, ql, PdQ, s.N, s.B, s.n,
-                           s.k, nsub, s.scale, s.R, s.bh);
+                           s.k, nsub, s.scale, s.R, s.bh, s.G);
     }
     const int64_t rows = (int64_t)s.bh * s.N;
     const int rpw = 256 / (D / 8);
@@ -344,14 +345,14 @@ hipError_t launch_dq_km(const Dims& s, const void* Q, const void* K, const void*
 {
     if (s.bh == 0 || s.N == 0) return hipSuccess;
     if (!key_major_shape(s)) return hipErrorInvalidValue;
-    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
+    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bhk * s.N * s.D);
     char* p = static_cast<char*>(ws);
     const float* Dv = reinterpret_cast<const float*>(p);
     p += a256(sizeof(float) * (size_t)s.bh * s.N);
     void* Kt = p;
     p += tensor;
     bf16_t* PdQ = reinterpret_cast<bf16_t*>(p);
-    hipError_t e = launch_slot_major_copy(s, K, Kt, nullptr, st);
+    hipError_t e = launch_slot_major_copy(kv_view(s), K, Kt, nullptr, st);
     if (e != hipSuccess) return e;
     return s.D == 64 ? dq_launch<64>(s, Q, dO, K, V, Kt, lse, Dv, idx, off, ql, PdQ, dQ, st)
                      : dq_launch<128>(s, Q, dO, K, V, Kt, lse, Dv, idx, off, ql, PdQ, dQ, st);

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
     const bf16_t* __restrict__ Kt, const uint32_t* __restrict__ kmax,
     const uint32_t* __restrict__ vmax, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ Dv, const int32_t* __restrict__ idx, bf16_t* __restrict__ dQ, int N,
-    int B, int k, float scale, int ntiles, int bh)
+    int B, int k, float scale, int ntiles, int bh, int G)
 {
     using C = DqCfg<D>;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -75,9 +75,10 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
     const int NG = B / 32;
     const float c2 = scale * kLog2e;
     const int64_t sbase = (int64_t)s * N;
-    const char* Kag = reinterpret_cast<const char*>(Ka + sbase * D);
-    const char* Vag = reinterpret_cast<const char*>(Va + sbase * D);
-    const char* Ktg = reinterpret_cast<const char*>(Kt + sbase * D);
+    const int skv = s / G;                             // G query heads share a key/value head
+    const char* Kag = reinterpret_cast<const char*>(Ka + (int64_t)skv * N * D);
+    const char* Vag = reinterpret_cast<const char*>(Va + (int64_t)skv * N * D);
+    const char* Ktg = reinterpret_cast<const char*>(Kt + (int64_t)skv * N * D);
     const uint32_t vlane = (uint32_t)lane * 16u;       // this lane's bytes inside an operand
 
     // 0. Q and dO tiles -> LDS (chunk c of row r at chunk c ^ (r & 7)); clear the accumulators
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
             for (int c = 0; c < D; ++c) {
                 const bf16_t gv = *reinterpret_cast<const bf16_t*>(
                     Gs + (uint32_t)r * C::ROWB + ((((c >> 3) ^ (r & 7)) << 4) | ((c & 7) << 1)));
-                bound += fabsf(bf16_to_f32(gv)) * ldexpf(1.f, scale_exponent(vmax[s * D + c]));
+                bound += fabsf(bf16_to_f32(gv)) * ldexpf(1.f, scale_exponent(vmax[skv * D + c]));
             }
             Dt = Dv[sbase + t0 + r];
             L = lse[sbase + t0 + r];
@@ -262,7 +263,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
         float v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            v[e] = scale * ldexpf((float)acc[r * C::OSTRIDE + 8 * c + e], et + scale_exponent(kmax[s * D + 8 * c + e]));
+            v[e] = scale * ldexpf((float)acc[r * C::OSTRIDE + 8 * c + e], et + scale_exponent(kmax[skv * D + 8 * c + e]));
         Vec8<bf16_t>::store(dQg + (int64_t)r * D + 8 * c, v);
     }
 }
@@ -282,7 +283,7 @@ static hipError_t dq_launch(const Dims& s, const void* Q, const void* Ka, const 
     hipLaunchKernelGGL((dq_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, ntiles)), dim3(C::NT), C::LDS, st,
                        (const bf16_t*)Q, (const bf16_t*)Ka, (const bf16_t*)Va, (const bf16_t*)Kt, kmax,
                        vmax, (const bf16_t*)dO, lse, Dv, idx, (bf16_t*)dQ, s.N, s.B, s.k, s.scale,
-                       ntiles, s.bh);
+                       ntiles, s.bh, s.G);
     return hipGetLastError();
 }
 
@@ -313,15 +314,16 @@ hipError_t launch_dq_mfma(const Dims& s, const void* Q, const void* K, const voi
     uint32_t* kmax = (uint32_t*)p;
     p += a256(sizeof(uint32_t) * (size_t)s.bh * s.D);
     uint32_t* vmax = (uint32_t*)p;
-    hipError_t e = launch_absmax(s, K, kmax, st);
+    const Dims kv = kv_view(s);      // K and V: one slice per key/value head (the parts stay sized for bh)
+    hipError_t e = launch_absmax(kv, K, kmax, st);
     if (e != hipSuccess) return e;
-    e = launch_absmax(s, V, vmax, st);
+    e = launch_absmax(kv, V, vmax, st);
     if (e != hipSuccess) return e;
-    e = launch_slot_major_copy(s, K, Kt, kmax, st);
+    e = launch_slot_major_copy(kv, K, Kt, kmax, st);
     if (e != hipSuccess) return e;
-    e = launch_operand_copy(s, K, Ka, st);
+    e = launch_operand_copy(kv, K, Ka, st);
     if (e != hipSuccess) return e;
-    e = launch_operand_copy(s, V, Va, st);
+    e = launch_operand_copy(kv, V, Va, st);
     if (e != hipSuccess) return e;
     return s.D == 64 ? dq_launch<64>(s, Q, Ka, Va, Kt, kmax, vmax, dO, lse, Dv, idx, dQ, st)
                      : dq_launch<128>(s, Q, Ka, Va, Kt, kmax, vmax, dO, lse, Dv, idx, dQ, st);

@@ -45,7 +45,7 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ off, const int32_t* __restrict__ ql,
     bf16_t* __restrict__ PO, float* __restrict__ Pml, int N, int B, int n, int k, int nsub,
-    float scale, int64_t R, int bh)
+    float scale, int64_t R, int bh, int G)
 {
     using C = KmCfg<D>;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -59,6 +59,7 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
     const int j = u / nsub, c = u - j * nsub;
     const int own_first = c * (32 * NG);                    // first key of the part inside the block
     const int64_t sbase = (int64_t)s * N;
+    const int64_t kvbase = (int64_t)(s / G) * N;            // G query heads share a key/value head
     const float c2 = scale * kLog2e;
     const int32_t* os = off + (int64_t)s * (n + 1);
     const int32_t* qs = ql + (int64_t)s * R;
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
     // as well would leave room for one wave per SIMD only, and the walk needs a second one to
     // fill the waits of the first.)
     {
-        const char* Kg = reinterpret_cast<const char*>(K + (sbase + own0) * D);
+        const char* Kg = reinterpret_cast<const char*>(K + (kvbase + own0) * D);
         for (int ch = tid; ch < NG * 32 * C::CPR; ch += C::NT) {
             const int row = ch / C::CPR, col = ch % C::CPR;             // key of the part, 16-byte piece
             const int gi = row >> 5, mt = (row >> 4) & 1, m = row & 15, ks = col >> 2, gg = col & 3;
@@ -85,7 +86,7 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
     }
     Frag va[NG][C::MT];
     {
-        const char* Vtg = reinterpret_cast<const char*>(Vt + (sbase + own0) * D);
+        const char* Vtg = reinterpret_cast<const char*>(Vt + (kvbase + own0) * D);
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
@@ -310,7 +311,7 @@ static size_t km_partials(const Dims& s)
 
 size_t forward_km_ws_bytes(const Dims& s)
 {
-    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
+    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bhk * s.N * s.D);
     return tensor + a256(sizeof(bf16_t) * km_partials(s) * s.D) + a256(sizeof(float) * km_partials(s) * 2);
 }
 
@@ -328,7 +329,7 @@ static hipError_t km_launch3(const Dims& s, const void* Q, const void* K, const 
         ProfileScope timing(MOBA_PROFILE_FORWARD, st);
         hipLaunchKernelGGL((fwd_km_kernel<D, NG, KC>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
                            dim3(C::NT), C::lds(NG), st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)Vt,
-                           idx, off, ql, PO, Pml, s.N, s.B, s.n, s.k, nsub, s.scale, s.R, s.bh);
+                           idx, off, ql, PO, Pml, s.N, s.B, s.n, s.k, nsub, s.scale, s.R, s.bh, s.G);
     }
     const int64_t rows = (int64_t)s.bh * s.N;
     const int rpw = 256 / (D / 8);
@@ -364,14 +365,14 @@ hipError_t launch_forward_km(const Dims& s, const void* Q, const void* K, const 
 {
     if (s.bh == 0 || s.N == 0) return hipSuccess;
     if (!key_major_shape(s)) return hipErrorInvalidValue;
-    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
+    const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bhk * s.N * s.D);
     char* p = static_cast<char*>(ws);
     void* Vt = p;
     p += tensor;
     bf16_t* PO = reinterpret_cast<bf16_t*>(p);
     p += a256(sizeof(bf16_t) * km_partials(s) * s.D);
     float* Pml = reinterpret_cast<float*>(p);
-    hipError_t e = launch_slot_major_copy(s, V, Vt, nullptr, st);
+    hipError_t e = launch_slot_major_copy(kv_view(s), V, Vt, nullptr, st);
     if (e != hipSuccess) return e;
     return s.D == 64 ? km_launch<64>(s, Q, K, Vt, idx, off, ql, PO, Pml, O, lse, st)
                      : km_launch<128>(s, Q, K, Vt, idx, off, ql, PO, Pml, O, lse, st);

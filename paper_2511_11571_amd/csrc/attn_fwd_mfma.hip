@@ -202,7 +202,7 @@ template <int D>
 __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Ka, const bf16_t* __restrict__ Vt,
     const uint32_t* __restrict__ vmax, const int32_t* __restrict__ idx, bf16_t* __restrict__ O,
-    float* __restrict__ lse, int N, int B, int k, float scale, int ntiles, int bh)
+    float* __restrict__ lse, int N, int B, int k, float scale, int ntiles, int bh, int G)
 {
     using C = FwdCfg<D>;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -230,8 +230,9 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
     const float c2 = scale * kLog2e;
     const int64_t sbase = (int64_t)s * N;
     const bf16_t* Qg = Q + (sbase + t0) * D;
-    const char* Kg = reinterpret_cast<const char*>(Ka + sbase * D);
-    const char* Vtg = reinterpret_cast<const char*>(Vt + sbase * D);
+    const int skv = s / G;                                  // G query heads share a key/value head
+    const char* Kg = reinterpret_cast<const char*>(Ka + (int64_t)skv * N * D);
+    const char* Vtg = reinterpret_cast<const char*>(Vt + (int64_t)skv * N * D);
     const uint32_t vlane = (uint32_t)lane * 16u;   // this lane's bytes inside a K or V operand
     const uint32_t qlane = 16u * g;
 
@@ -435,7 +436,7 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
         float v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            v[e] = ldexpf((float)Os[r * C::OSTRIDE + 8 * c + e] * inv, scale_exponent(vmax[s * D + 8 * c + e]));
+            v[e] = ldexpf((float)Os[r * C::OSTRIDE + 8 * c + e] * inv, scale_exponent(vmax[skv * D + 8 * c + e]));
         Vec8<bf16_t>::store(Og + (int64_t)r * D + 8 * c, v);
         if (c == 0) lse[sbase + t0 + r] = (__int_as_float(mkey[r]) + fast_log2(lf)) * kLn2;
     }
@@ -454,29 +455,30 @@ static hipError_t fwd_launch(const Dims& s, const void* Q, const void* K, const 
     ProfileScope timing(MOBA_PROFILE_FORWARD, st);
     hipLaunchKernelGGL((forward_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, ntiles)), dim3(C::NT), C::LDS,
                        st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)Vt, vmax, idx,
-                       (bf16_t*)O, lse, s.N, s.B, s.k, s.scale, ntiles, s.bh);
+                       (bf16_t*)O, lse, s.N, s.B, s.k, s.scale, ntiles, s.bh, s.G);
     return hipGetLastError();
 }
 
 size_t forward_mfma_ws_bytes(const Dims& s)
 {
-    return 2 * (sizeof(bf16_t) * (size_t)s.bh * s.N * s.D + 256) + sizeof(uint32_t) * (size_t)s.bh * s.D;
+    return 2 * (sizeof(bf16_t) * (size_t)s.bhk * s.N * s.D + 256) + sizeof(uint32_t) * (size_t)s.bhk * s.D;
 }
 
-// ws: [bh*N*D bf16 slot-ordered scaled V][pad to 256][bh*N*D bf16 operand-ordered K][pad to 256]
-//     [bh*D fp32 bits: channel maxima of V]
+// ws (per key/value slice): [N*D bf16 slot-ordered scaled V][pad to 256][N*D bf16 operand-ordered K]
+//     [pad to 256][D fp32 bits: channel maxima of V]
 hipError_t launch_forward_mfma(const Dims& s, const void* Q, const void* K, const void* V,
                                void* ws, const int32_t* idx, const int32_t* off, const int32_t* ql,
                                void* O, float* lse, hipStream_t st)
 {
-    const size_t vt_bytes = (sizeof(bf16_t) * (size_t)s.bh * s.N * s.D + 255) & ~(size_t)255;
+    const size_t vt_bytes = (sizeof(bf16_t) * (size_t)s.bhk * s.N * s.D + 255) & ~(size_t)255;
     void* Ka = (char*)ws + vt_bytes;
     uint32_t* vmax = reinterpret_cast<uint32_t*>((char*)ws + 2 * vt_bytes);
-    hipError_t e = launch_absmax(s, V, vmax, st);
+    const Dims kv = kv_view(s);                              // K and V: one slice per key/value head
+    hipError_t e = launch_absmax(kv, V, vmax, st);
     if (e != hipSuccess) return e;
-    e = launch_slot_major_copy(s, V, ws, vmax, st);
+    e = launch_slot_major_copy(kv, V, ws, vmax, st);
     if (e != hipSuccess) return e;
-    e = launch_operand_copy(s, K, Ka, st);
+    e = launch_operand_copy(kv, K, Ka, st);
     if (e != hipSuccess) return e;
     return s.D == 64 ? fwd_launch<64>(s, Q, Ka, ws, vmax, idx, O, lse, st)
                      : fwd_launch<128>(s, Q, Ka, ws, vmax, idx, O, lse, st);

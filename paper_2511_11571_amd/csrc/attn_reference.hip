@@ -62,7 +62,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void forward_reference_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, T* __restrict__ O, float* __restrict__ lse,
-    int N, int B, int k, float scale, int64_t total_rows)
+    int N, int B, int k, float scale, int64_t total_rows, int G)
 {
     extern __shared__ float smem[];
     constexpr int DP = D / kWave;                 // channels per lane
@@ -75,8 +75,8 @@ __global__ __launch_bounds__(256) void forward_reference_kernel(
     if (row >= total_rows) return;
     const int64_t s = row / N;
     const int t = (int)(row % N);
-    const T* Ks = K + s * N * D;
-    const T* Vs = V + s * N * D;
+    const T* Ks = K + (s / G) * N * D;            // G query heads share a key/value head
+    const T* Vs = V + (s / G) * N * D;
 
     for (int c = lane; c < D; c += kWave) qs[c] = to_f32<T>(Q[row * D + c]);
     KeyWalk kw;
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void dq_reference_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ Dv,
     const int32_t* __restrict__ idx, T* __restrict__ dQ, int N, int B, int k, float scale,
-    int64_t total_rows)
+    int64_t total_rows, int G)
 {
     extern __shared__ float smem[];
     constexpr int DP = D / kWave;
@@ -162,8 +162,8 @@ __global__ __launch_bounds__(256) void dq_reference_kernel(
     if (row >= total_rows) return;
     const int64_t s = row / N;
     const int t = (int)(row % N);
-    const T* Ks = K + s * N * D;
-    const T* Vs = V + s * N * D;
+    const T* Ks = K + (s / G) * N * D;            // G query heads share a key/value head
+    const T* Vs = V + (s / G) * N * D;
     for (int c = lane; c < D; c += kWave) {
         qs[c] = to_f32<T>(Q[row * D + c]);
         gs[c] = to_f32<T>(dO[row * D + c]);
@@ -213,24 +213,27 @@ __global__ __launch_bounds__(256) void dkdv_reference_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ Dv,
     const int32_t* __restrict__ off, const int32_t* __restrict__ ql,
-    T* __restrict__ dK, T* __restrict__ dV, int N, int B, int n, float scale, int64_t R)
+    T* __restrict__ dK, T* __restrict__ dV, int N, int B, int n, float scale, int64_t R, int G)
 {
     constexpr int C = D / 8;                       // channels per thread
-    const int s = blockIdx.z, j = blockIdx.x, sub = blockIdx.y;
+    const int skv = blockIdx.z, j = blockIdx.x, sub = blockIdx.y;   // key/value slice
     const int ul = sub * 32 + threadIdx.x / 8;     // key inside the block
     const int part = threadIdx.x % 8;
     const bool live = ul < B;
     const int u = j * B + (live ? ul : 0);
-    const int64_t base = (int64_t)s * N;
+    const int64_t kbase = (int64_t)skv * N;
     float kr[C], vr[C], dk[C], dv[C];
 #pragma unroll
     for (int c = 0; c < C; c += 8) {
         float a[8], b[8];
-        Vec8<T>::load(K + (base + u) * D + part * C + c, a);
-        Vec8<T>::load(V + (base + u) * D + part * C + c, b);
+        Vec8<T>::load(K + (kbase + u) * D + part * C + c, a);
+        Vec8<T>::load(V + (kbase + u) * D + part * C + c, b);
 #pragma unroll
         for (int e = 0; e < 8; ++e) { kr[c + e] = a[e]; vr[c + e] = b[e]; dk[c + e] = 0.f; dv[c + e] = 0.f; }
     }
+    // the query heads that share this key/value head, one after the other (fixed order)
+    for (int s = skv * G; s < (skv + 1) * G; ++s) {
+    const int64_t base = (int64_t)s * N;
     const int32_t* os = off + (int64_t)s * (n + 1);
     const int32_t* qs = ql + (int64_t)s * R;
     const int lo = os[j], nlist = os[j + 1] - lo;
@@ -256,14 +259,15 @@ __global__ __launch_bounds__(256) void dkdv_reference_kernel(
 #pragma unroll
         for (int e = 0; e < C; ++e) { dv[e] = fmaf(p, g[e], dv[e]); dk[e] = fmaf(dS, q[e], dk[e]); }
     }
+    }
     if (live) {
 #pragma unroll
         for (int c = 0; c < C; c += 8) {
             float a[8], b[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) { a[e] = scale * dk[c + e]; b[e] = dv[c + e]; }
-            Vec8<T>::store(dK + (base + u) * D + part * C + c, a);
-            Vec8<T>::store(dV + (base + u) * D + part * C + c, b);
+            Vec8<T>::store(dK + (kbase + u) * D + part * C + c, a);
+            Vec8<T>::store(dV + (kbase + u) * D + part * C + c, b);
         }
     }
 }
@@ -278,7 +282,7 @@ static hipError_t fwd_t(const Dims& s, const void* Q, const void* K, const void*
     const size_t lds = sizeof(float) * 4 * (D + 2 * kWave) + sizeof(int32_t) * 4 * (size_t)s.k;
     hipLaunchKernelGGL((forward_reference_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)), dim3(256),
                        lds, st, (const T*)Q, (const T*)K, (const T*)V, idx, (T*)O, lse, s.N, s.B, s.k,
-                       s.scale, rows);
+                       s.scale, rows, s.G);
     return hipGetLastError();
 }
 
@@ -298,11 +302,11 @@ static hipError_t bwd_t(const Dims& s, const void* Q, const void* K, const void*
     if (parts & MOBA_BWD_DQ)
     hipLaunchKernelGGL((dq_reference_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)), dim3(256), lds,
                        st, (const T*)Q, (const T*)K, (const T*)V, (const T*)dO, lse, Dvec, idx,
-                       (T*)dQ, s.N, s.B, s.k, s.scale, rows);
+                       (T*)dQ, s.N, s.B, s.k, s.scale, rows, s.G);
     if (parts & MOBA_BWD_DKDV)
-    hipLaunchKernelGGL((dkdv_reference_kernel<T, D>), dim3(s.n, (s.B + 31) / 32, s.bh), dim3(256), 0,
+    hipLaunchKernelGGL((dkdv_reference_kernel<T, D>), dim3(s.n, (s.B + 31) / 32, s.bhk), dim3(256), 0,
                        st, (const T*)Q, (const T*)K, (const T*)V, (const T*)dO, lse, Dvec, off, ql,
-                       (T*)dK, (T*)dV, s.N, s.B, s.n, s.scale, s.R);
+                       (T*)dK, (T*)dV, s.N, s.B, s.n, s.scale, s.R, s.G);
     return hipGetLastError();
 }
 

@@ -153,13 +153,26 @@ __device__ __forceinline__ bool schedule(int bid, int bh, int npos, int& s, int&
 
 // ---- host-side view of a validated shape ------------------------------------------
 struct Dims {
+    // bh, heads: query heads.  G query heads share a key/value head (slice s reads key/value
+    // slice s / G); bhk = bh / G key/value slices of hkv heads.
     int bh, heads, N, D, B, n, k, W;
+    int G, bhk, hkv;
     int dtype;
     uint32_t flags;
     float scale;
     int64_t R;          // routes per slice
     int nchunk;         // ceil(N / kChunkQ)
 };
+
+// the same shape as seen by kernels that walk key/value-shaped tensors only
+inline Dims kv_view(const Dims& d)
+{
+    Dims v = d;
+    v.bh = d.bhk;
+    v.heads = d.hkv;
+    v.G = 1;
+    return v;
+}
 
 // kernel timing hooks (see moba_profile_begin): no-ops unless a session is open
 void profile_mark(int kernel, bool start, hipStream_t st);

@@ -37,8 +37,12 @@ int make_dims(const moba_shape* sh, Dims& d)
     if (sh->conv_width > 8) return MOBA_EUNSUPPORTED;
     if (sh->topk > kMaxTopk) return MOBA_EUNSUPPORTED;
     if ((int64_t)sh->batch * sh->heads > 65535) return MOBA_EUNSUPPORTED;
+    if (sh->kv_heads < 0 || (sh->kv_heads > 0 && sh->heads % sh->kv_heads != 0)) return MOBA_EINVAL;
     d.bh = sh->batch * sh->heads;
     d.heads = sh->heads;
+    d.hkv = sh->kv_heads > 0 ? sh->kv_heads : sh->heads;
+    d.G = d.heads / d.hkv;
+    d.bhk = sh->batch * d.hkv;
     d.N = sh->seqlen;
     d.D = sh->head_dim;
     d.B = sh->block;
@@ -191,7 +195,7 @@ int moba_centroids(const moba_shape* shape, const void* K, const float* conv_w, 
     if (!K || !centroids) return MOBA_EINVAL;
     if ((d.W > 0) != (conv_w != nullptr)) return MOBA_EINVAL;
     if (d.W > 0 && !K_eff) return MOBA_EINVAL;
-    return hip_status(launch_centroids(d, K, conv_w, K_eff, centroids, (hipStream_t)stream));
+    return hip_status(launch_centroids(kv_view(d), K, conv_w, K_eff, centroids, (hipStream_t)stream));
 }
 
 int moba_key_conv_backward_workspace(const moba_shape* shape, size_t* ws_bytes)
@@ -200,7 +204,7 @@ int moba_key_conv_backward_workspace(const moba_shape* shape, size_t* ws_bytes)
     const int st = make_dims(shape, d);
     if (st != MOBA_OK) return st;
     if (!ws_bytes || d.W < 1) return MOBA_EINVAL;
-    *ws_bytes = align256(conv_bwd_ws_bytes(d)) + 256;
+    *ws_bytes = align256(conv_bwd_ws_bytes(kv_view(d))) + 256;
     return MOBA_OK;
 }
 
@@ -212,8 +216,8 @@ int moba_key_conv_backward(const moba_shape* shape, const void* K, const float* 
     const int st = make_dims(shape, d);
     if (st != MOBA_OK) return st;
     if (d.W < 1 || !K || !conv_w || !dK_eff || !dK || !dconv_w || dK == dK_eff) return MOBA_EINVAL;
-    if (!ws || ws_bytes < align256(conv_bwd_ws_bytes(d)) + 256) return MOBA_EWORKSPACE;
-    return hip_status(launch_conv_backward(d, K, conv_w, dK_eff, dK, dconv_w, ws, (hipStream_t)stream));
+    if (!ws || ws_bytes < align256(conv_bwd_ws_bytes(kv_view(d))) + 256) return MOBA_EWORKSPACE;
+    return hip_status(launch_conv_backward(kv_view(d), K, conv_w, dK_eff, dK, dconv_w, ws, (hipStream_t)stream));
 }
 
 int moba_build_lists(const moba_shape* shape, const int32_t* topk_idx, int32_t* blk_off,

@@ -111,7 +111,7 @@ template <int D>
 __global__ __launch_bounds__(kTopkWaves * kWave) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2)))
 void topk_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ c3, int ntile_all,
-    int32_t* __restrict__ idx, int N, int B, int n, int k, int strips_per_slice, int Wn)
+    int32_t* __restrict__ idx, int N, int B, int n, int k, int strips_per_slice, int Wn, int G)
 {
     extern __shared__ uint32_t smem[];
     constexpr int KS = D / 32;
@@ -133,7 +133,7 @@ void topk_mfma_kernel(
     const int s = strip / strips_per_slice;
     const int t0 = (strip % strips_per_slice) * 64;
     const int rows_here = min(64, N - t0);
-    const char* c3s = reinterpret_cast<const char*>(c3) + (int64_t)s * ntile_all * (3 * KS * 1024);
+    const char* c3s = reinterpret_cast<const char*>(c3) + (int64_t)(s / G) * ntile_all * (3 * KS * 1024);   // G query heads share the centroids
     int32_t* out = idx + ((int64_t)s * N + t0) * k;
 
     if (wave == 0) {   // lane = query: initial state
@@ -375,7 +375,7 @@ void topk_mfma_kernel(
 
 size_t topk_mfma_ws_bytes(const Dims& s)
 {
-    return 3 * sizeof(bf16_t) * (size_t)s.bh * ((s.n + 15) / 16 * 16) * s.D;
+    return 3 * sizeof(bf16_t) * (size_t)s.bhk * ((s.n + 15) / 16 * 16) * s.D;
 }
 
 bool topk_mfma_supported(const Dims& s)
@@ -397,7 +397,7 @@ static hipError_t topk_launch(const Dims& s, const void* Q, const bf16_t* c3, in
     if (e != hipSuccess) return e;
     ProfileScope timing(MOBA_PROFILE_TOPK, st);
     hipLaunchKernelGGL((topk_mfma_kernel<D>), dim3((unsigned)strips), dim3(kTopkWaves * kWave), lds, st,
-                       (const bf16_t*)Q, c3, (s.n + 15) / 16, idx, s.N, s.B, s.n, s.k, sps, Wn);
+                       (const bf16_t*)Q, c3, (s.n + 15) / 16, idx, s.N, s.B, s.n, s.k, sps, Wn, s.G);
     return hipGetLastError();
 }
 
@@ -405,7 +405,7 @@ hipError_t launch_topk_mfma(const Dims& s, const void* Q, const float* cent, int
                             hipStream_t st)
 {
     const int ntile = (s.n + 15) / 16;
-    const int64_t chunks = (int64_t)s.bh * ntile * 3 * (s.D / 32) * 64;
+    const int64_t chunks = (int64_t)s.bhk * ntile * 3 * (s.D / 32) * 64;     // centroids: per key/value head
     if (chunks == 0) return hipSuccess;
     bf16_t* c3 = (bf16_t*)ws;
     const unsigned grid = (unsigned)((chunks + 255) / 256);

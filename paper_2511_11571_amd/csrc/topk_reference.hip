@@ -13,7 +13,7 @@ constexpr int kTopkMaxBlocks = 4096;   // LDS row length per wave
 template <typename T, int D>
 __global__ __launch_bounds__(256) void topk_reference_kernel(
     const T* __restrict__ Q, const float* __restrict__ cent, int32_t* __restrict__ idx,
-    int N, int B, int n, int k, int64_t total_rows, int lds_row)
+    int N, int B, int n, int k, int64_t total_rows, int lds_row, int G)
 {
     extern __shared__ uint32_t smem[];
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void topk_reference_kernel(
     for (int c = lane; c < D; c += kWave) qs[c] = to_f32<T>(Q[row * D + c]);
     __builtin_amdgcn_wave_barrier();
 
-    const float* cs = cent + s * n * D;
+    const float* cs = cent + (s / G) * n * D;        // G query heads share the centroids
     for (int j = lane; j < past; j += kWave) {
         const float4* cj = reinterpret_cast<const float4*>(cs + (int64_t)j * D);
         float acc = 0.f;
@@ -89,7 +89,7 @@ static hipError_t launch_t(const Dims& s, const void* Q, const float* cent, int3
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((topk_reference_kernel<T, D>), grid, block, lds, st, (const T*)Q, cent, idx,
-                       s.N, s.B, s.n, s.k, rows, lds_row);
+                       s.N, s.B, s.n, s.k, rows, lds_row, s.G);
     return hipGetLastError();
 }
 

@@ -34,6 +34,15 @@ def _shape(**kw):
     return binding.Shape(**base)
 
 
+def test_grouped_query_shapes_are_accepted(lib):
+    R = ctypes.c_int64(0)
+    for kv in (0, 1, 2, 4):
+        sh = _shape(heads=4, kv_heads=kv).c()
+        assert lib.moba_routes_per_slice(ctypes.byref(sh), ctypes.byref(R)) == 0
+    # sharing key/value heads shrinks the copies of K and V in the forward workspace
+    assert moba.workspace_bytes(_shape(heads=4, kv_heads=1))[1] < moba.workspace_bytes(_shape(heads=4))[1]
+
+
 def test_routes_and_workspace(lib):
     sh = _shape()
     n = 32
@@ -49,6 +58,8 @@ def test_routes_and_workspace(lib):
     (dict(seqlen=1000), -1),            # not a multiple of the block
     (dict(topk=-1), -1), (dict(dtype=7), -1), (dict(conv_width=-2), -1), (dict(flags=8), -1),
     (dict(head_dim=96), -2), (dict(conv_width=9), -2), (dict(topk=5000), -2),
+    (dict(heads=6, kv_heads=4), -1),    # key/value heads must divide the query heads
+    (dict(kv_heads=-1), -1), (dict(heads=2, kv_heads=4), -1),
 ])
 def test_bad_shapes_are_rejected(lib, kw, status):
     sh = _shape(**kw).c()

@@ -22,7 +22,7 @@ ATTN_FLAGS = FLAGS + [pytest.param(binding.FLAG_KEY_MAJOR, id="keymajor"),
 
 def shape_of(w, flags=0):
     return moba.Shape(w.batch, w.heads, w.N, w.d, w.B, w.k, w.conv_width,
-                      binding.BF16 if w.dtype == "bf16" else binding.F32, 0.0, flags)
+                      binding.BF16 if w.dtype == "bf16" else binding.F32, 0.0, flags, w.kv_heads)
 
 
 def dev(t):
@@ -44,7 +44,7 @@ def oracle_inputs(orc, w, t):
     mode = orc.ROUND_BF16 if w.dtype == "bf16" else orc.ROUND_F32
     Kp = K
     if w.conv_width:
-        Kp = orc.key_conv(K, t["conv_w"].double().numpy(), w.heads, mode)
+        Kp = orc.key_conv(K, t["conv_w"].double().numpy(), w.hkv, mode)
     return Q, K, Kp, V, dO
 
 
@@ -271,6 +271,61 @@ def test_key_major_variants(oracle, w):
     assert parity.rel_l2(np64(dQ), rQ) < tol
     assert parity.rel_l2(np64(dK), rK) < tol
     assert parity.rel_l2(np64(dV), rV) < tol
+
+
+# ------------------------------------------------------------------ grouped-query / multi-query attention
+
+GQA = [
+    W("gqa_G4_B32", 1, 8, 1024, 64, 32, 4, kv_heads=2, seed=81),
+    W("mqa_d128_B64", 2, 4, 768, 128, 64, 3, kv_heads=1, seed=82),
+    W("gqa_f32", 1, 4, 512, 64, 32, 3, dtype="f32", kv_heads=2, seed=83),
+    W("gqa_B128", 2, 4, 1024, 64, 128, 2, kv_heads=2, seed=84),
+    W("gqa_conv", 1, 4, 640, 64, 32, 2, kv_heads=2, conv_width=3, seed=85),
+    W("gqa_B16", 1, 6, 320, 64, 16, 5, kv_heads=3, seed=86),               # plain kernels for bf16 too
+]
+
+
+@pytest.mark.parametrize("flags", ATTN_FLAGS)
+@pytest.mark.parametrize("w", GQA, ids=[w.name for w in GQA])
+def test_grouped_query_heads(oracle, w, flags):
+    """Query head h reads key/value head h // G; dK and dV are summed over the sharing heads
+    (Appendix C, last paragraph).  The oracle computes on copies of the shared heads."""
+    t = workloads.generate(w)
+    Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)          # K, Kp, V: [b*kv_heads, N, d]
+    sh = shape_of(w, flags)
+    d = dev(t)
+    C = oracle.centroids(Kp, w.B)
+    Keff, cent = moba.centroids(sh, d["K"], d["conv_w"])
+    assert tuple(cent.shape) == (w.batch, w.hkv, w.n, w.d)
+    assert parity.max_abs(np64(cent), C) < (2e-6 if not w.conv_width else 1e-3)
+    Ke, Ve, Ce = (oracle.gqa_expand(x, w.heads, w.hkv) for x in (Kp, V, C))
+    ref_idx, kth = oracle.topk(Q, Ce, w.B, w.k)
+    cent_ref = torch.from_numpy(C).float().reshape(w.batch, w.hkv, w.n, w.d).cuda()
+    idx, (off, ql) = moba.topk(sh, d["Q"], cent_ref)
+    exact, exempt = parity.routing_check(oracle, npi(idx).reshape(w.bh * w.N, w.k),
+                                         ref_idx.reshape(w.bh * w.N, w.k), kth.reshape(-1), Q, Ce, w.B)
+    assert exempt < 0.02
+    # attention at the oracle's routing
+    idx = torch.from_numpy(ref_idx).reshape(w.batch, w.heads, w.N, w.k).cuda()
+    lists = moba.build_lists(sh, idx)
+    Kdev = to_io(w, Kp, t["K"])
+    O, lse = moba.forward(sh, d["Q"], Kdev, d["V"], idx, lists)
+    rO, rlse = oracle.attn_fwd(Q, Ke, Ve, ref_idx, w.B, w.scale)
+    assert parity.max_abs(np64(O), rO) < parity.O_TOL[w.dtype]
+    assert parity.max_abs(np64(lse), rlse) < parity.LSE_TOL[w.dtype]
+    dQ, dK, dV = moba.backward(sh, d["Q"], Kdev, d["V"], O, lse, d["dO"], idx, lists)
+    assert dK.shape == t["K"].shape and dV.shape == t["V"].shape
+    rQ, rKe, rVe = oracle.attn_bwd(Q, Ke, Ve, ref_idx, dO, w.B, w.scale)
+    tol = parity.GRAD_TOL[w.dtype]
+    assert parity.rel_l2(np64(dQ), rQ) < tol
+    assert parity.rel_l2(np64(dK), oracle.gqa_reduce(rKe, w.heads, w.hkv)) < tol
+    assert parity.rel_l2(np64(dV), oracle.gqa_reduce(rVe, w.heads, w.hkv)) < tol
+    if w.conv_width:
+        # the convolution and its backward run per key/value head
+        gK, gw = moba.key_conv_backward(sh, d["K"], d["conv_w"], dK)
+        rgK, rgw = oracle.key_conv_bwd(K, t["conv_w"].double().numpy(), np64(dK), w.hkv)
+        assert parity.rel_l2(np64(gK), rgK) < 1e-2
+        assert parity.rel_l2(gw.double().cpu().numpy(), rgw) < 1e-4
 
 
 # ------------------------------------------------------------------ the whole chain on its own routing

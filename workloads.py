@@ -30,10 +30,15 @@ class Workload:
     backward: bool = False
     skew: bool = False         # planted hot blocks (load imbalance)
     seed: int = 0
+    kv_heads: int = 0          # grouped-query attention: key/value heads (0 = heads)
 
     @property
     def bh(self):
         return self.batch * self.heads
+
+    @property
+    def hkv(self):
+        return self.kv_heads if self.kv_heads > 0 else self.heads
 
     @property
     def n(self):
@@ -74,19 +79,21 @@ def attended_pairs_per_slice(N, B, k):
 
 
 def generate(w: Workload, device="cpu"):
-    """Returns a dict of CPU tensors: Q,K,V,dO [batch,heads,N,d] in the I/O type,
-    conv_w [heads,d,W] fp32 (or None)."""
+    """Returns a dict of CPU tensors: Q,dO [batch,heads,N,d] and K,V [batch,kv_heads,N,d] in
+    the I/O type, conv_w [kv_heads,d,W] fp32 (or None)."""
     g = torch.Generator().manual_seed(w.seed)
     shape = (w.batch, w.heads, w.N, w.d)
+    kv_shape = (w.batch, w.hkv, w.N, w.d)
     Q = torch.randn(shape, generator=g, dtype=torch.float32)
-    K = torch.randn(shape, generator=g, dtype=torch.float32)
-    V = torch.randn(shape, generator=g, dtype=torch.float32)
+    K = torch.randn(kv_shape, generator=g, dtype=torch.float32)
+    V = torch.randn(kv_shape, generator=g, dtype=torch.float32)
     dO = torch.randn(shape, generator=g, dtype=torch.float32)
     conv_w = None
     if w.conv_width > 0:
         # weights ~ N(0, variance 1/4), one filter per (head, channel), last axis = lag
-        conv_w = 0.5 * torch.randn((w.heads, w.d, w.conv_width), generator=g, dtype=torch.float32)
+        conv_w = 0.5 * torch.randn((w.hkv, w.d, w.conv_width), generator=g, dtype=torch.float32)
     if w.skew:
+        assert w.hkv == w.heads, "the planted hot blocks are defined per head"
         # per head a direction u with |u| = 3; per (batch, head) 1% of the blocks are hot:
         # u is added to all their keys; every query gets 0.5*u.
         u = torch.randn((w.heads, w.d), generator=g, dtype=torch.float32)
