@@ -252,28 +252,48 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
 }
 
 // dQ_t = sum of the query's partials, in the order [kept block][part], then the parts of its
-// own block up to its own key.  D / 8 lanes per query.
+// own block up to its own key.  D / 8 lanes per query; the partials of a query are consecutive
+// and are loaded nine at a time, unconditionally (past the end: the last one again, ignored).
+constexpr int kDqMergeChunk = 9;
+
 template <int D>
 __global__ __launch_bounds__(256) void dq_km_merge_kernel(
     const int32_t* __restrict__ idx, const bf16_t* __restrict__ PdQ, bf16_t* __restrict__ dQ, int N,
     int B, int k, int nsub, int64_t rows_total)
 {
-    constexpr int G = D / 8;
+    constexpr int G = D / 8, CH = kDqMergeChunk;
     const int64_t row = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;      // s * N + t
     const int part = threadIdx.x % G;
     if (row >= rows_total) return;
     const int t = (int)(row % N);
     const int own_parts = (t % B) / km_part_keys(B, D) + 1;
-    const int32_t* irow = idx + row * k;
-    const int64_t p0 = row * (k + 1) * nsub;
+    const int slots = (k + 1) * nsub, klast = max(k - 1, 0);
+    const int64_t p0 = row * slots;
+    const char* orow = reinterpret_cast<const char*>(PdQ + p0 * D + part * 8);
+    // (with k = 0 there is no row of kept blocks: any readable address serves the unused loads)
+    const int32_t* irow = k > 0 ? idx + row * k : reinterpret_cast<const int32_t*>(orow);
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int e = 0; e <= k; ++e) {
-        const int np = e == k ? own_parts : (irow[e] < 0 ? 0 : nsub);
-        for (int c = 0; c < np; ++c) {
-            float v[8];
-            Vec8<bf16_t>::load(PdQ + (p0 + e * nsub + c) * D + part * 8, v);
+    for (int i0 = 0, e0 = 0, c0 = 0; i0 < slots; i0 += CH) {
+        int jj[CH];
+        dqvec4_t raw[CH];
 #pragma unroll
-            for (int ch = 0; ch < 8; ++ch) acc[ch] += v[ch];
+        for (int i = 0, e = e0, c = c0; i < CH; ++i) {
+            jj[i] = irow[min(e, klast)];
+            raw[i] = *reinterpret_cast<const dqvec4_t*>(orow + (int64_t)min(i0 + i, slots - 1) * (2 * D));
+            if (++c == nsub) { c = 0; ++e; }
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            // the partial counts if it exists and its block was kept (own block: the parts up to
+            // the query's own key); an unused slot holds whatever the workspace held
+            const bool ok = i0 + i < slots && (e0 == k ? c0 < own_parts : jj[i] >= 0);
+            if (++c0 == nsub) { c0 = 0; ++e0; }
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                const float lo = __uint_as_float(raw[i][h] << 16), hi = __uint_as_float(raw[i][h] & 0xffff0000u);
+                acc[2 * h] += ok ? lo : 0.f;
+                acc[2 * h + 1] += ok ? hi : 0.f;
+            }
         }
     }
     Vec8<bf16_t>::store(dQ + row * D + part * 8, acc);

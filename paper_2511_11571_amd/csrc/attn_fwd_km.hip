@@ -259,38 +259,80 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
 
 // O_t = sum w O_p, w = l_p 2^(m_p - M) / L over the query's partials: all parts of its kept
 // blocks, and the parts of its own block up to its own key; lse_t = (M + log2 L) ln 2.
-// D / 8 lanes per query.
+// D / 8 lanes per query.  A query's partials are consecutive in memory; they are loaded nine at a
+// time, every load unconditional (past the end: the last one again, ignored), so that a lane has
+// up to nine independent 16-byte loads in flight.
+constexpr int kMergeChunk = 9;
+
+__device__ __forceinline__ void unpack_bf16x8(const kmvec4_t& r, float (&v)[8])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(r[i] << 16);
+        v[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void fwd_km_merge_kernel(
     const int32_t* __restrict__ idx, const bf16_t* __restrict__ PO, const float* __restrict__ Pml,
     bf16_t* __restrict__ O, float* __restrict__ lse, int N, int B, int k, int nsub, int64_t rows_total)
 {
-    constexpr int G = D / 8;
+    constexpr int G = D / 8, CH = kMergeChunk;
     const int64_t row = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;      // s * N + t
     const int part = threadIdx.x % G;
     if (row >= rows_total) return;
     const int t = (int)(row % N);
     const int own_parts = (t % B) / km_part_keys(B, D) + 1;
-    const int32_t* irow = idx + row * k;
-    const int64_t p0 = row * (k + 1) * nsub;
-    auto parts_of = [&](int e) { return e == k ? own_parts : (irow[e] < 0 ? 0 : nsub); };
+    const int slots = (k + 1) * nsub, klast = max(k - 1, 0);
+    const int64_t p0 = row * slots;
+    // (with k = 0 there is no row of kept blocks: any readable address serves the unused loads)
+    const int32_t* irow = k > 0 ? idx + row * k : reinterpret_cast<const int32_t*>(Pml + p0 * 2);
+    const float2* mlrow = reinterpret_cast<const float2*>(Pml) + p0;
+    const char* orow = reinterpret_cast<const char*>(PO + p0 * D + part * 8);
+    // slot i0 + i is partial (e, c); it counts if it exists and its block was kept (own block:
+    // the parts up to the query's own key)
+    auto counts = [&](int si, int e, int c, int j) { return si < slots && (e == k ? c < own_parts : j >= 0); };
     float M = -INFINITY;
-    for (int e = 0; e <= k; ++e) {
-        const int np = parts_of(e);
-        for (int c = 0; c < np; ++c) M = fmaxf(M, Pml[(p0 + e * nsub + c) * 2]);
+    for (int i0 = 0, e0 = 0, c0 = 0; i0 < slots; i0 += CH) {
+        float m[CH];
+        int jj[CH];
+#pragma unroll
+        for (int i = 0, e = e0, c = c0; i < CH; ++i) {
+            jj[i] = irow[min(e, klast)];
+            m[i] = mlrow[min(i0 + i, slots - 1)].x;
+            if (++c == nsub) { c = 0; ++e; }
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            if (counts(i0 + i, e0, c0, jj[i])) M = fmaxf(M, m[i]);
+            if (++c0 == nsub) { c0 = 0; ++e0; }
+        }
     }
     float L = 0.f, acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int e = 0; e <= k; ++e) {
-        const int np = parts_of(e);
-        for (int c = 0; c < np; ++c) {
-            const int64_t pr = p0 + e * nsub + c;
-            const float2 ml = *reinterpret_cast<const float2*>(Pml + pr * 2);
-            const float wgt = ml.y * fast_exp2(ml.x - M);
+    for (int i0 = 0, e0 = 0, c0 = 0; i0 < slots; i0 += CH) {
+        float2 ml[CH];
+        int jj[CH];
+        kmvec4_t raw[CH];
+#pragma unroll
+        for (int i = 0, e = e0, c = c0; i < CH; ++i) {
+            const int si = min(i0 + i, slots - 1);
+            jj[i] = irow[min(e, klast)];
+            ml[i] = mlrow[si];
+            raw[i] = *reinterpret_cast<const kmvec4_t*>(orow + (int64_t)si * (2 * D));
+            if (++c == nsub) { c = 0; ++e; }
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const bool ok = counts(i0 + i, e0, c0, jj[i]);
+            if (++c0 == nsub) { c0 = 0; ++e0; }
+            // (an unused slot holds whatever the workspace held: select, do not multiply by 0)
+            const float wgt = ok ? ml[i].y * fast_exp2(ml[i].x - M) : 0.f;
             float v[8];
-            Vec8<bf16_t>::load(PO + pr * D + part * 8, v);
+            unpack_bf16x8(raw[i], v);
             L += wgt;
 #pragma unroll
-            for (int ch = 0; ch < 8; ++ch) acc[ch] = fmaf(wgt, v[ch], acc[ch]);
+            for (int ch = 0; ch < 8; ++ch) acc[ch] = fmaf(wgt, ok ? v[ch] : 0.f, acc[ch]);
         }
     }
     const float inv = 1.f / L;
