@@ -183,6 +183,17 @@ def test_config4_conv_long_sequence(oracle):
         print(w.name, s, check_slice(oracle, w, t, out, s, 512, [], rng), flush=True)
 
 
+def test_latency_sweep_shape_key_major(oracle):
+    """The paper's latency-sweep shape at N = 65536 (batch 2, 16 heads, B = 128, top-k 8), where
+    the library picks the key-block-major forward and dQ kernels by itself."""
+    w = workloads.Workload("sweep_N65536", 2, 16, 65536, 64, 128, 8, backward=True, seed=9100)
+    t, out = run_gpu(w)
+    rng = np.random.default_rng(6)
+    print(w.name, 21, check_slice(oracle, w, t, out, 21, 768, [0, 1, 7, 8, 200, 511], rng), flush=True)
+    for s in (0, 31):
+        print(w.name, s, check_slice(oracle, w, t, out, s, 1024, [], rng), flush=True)
+
+
 def test_config4_conv_backward(oracle):
     """Backward of the key convolution at the config-4 shape (1024 chunks of 128 rows per slice,
     row offsets beyond 2^31 bytes): two whole slices against the oracle.  The weights are per
