@@ -62,6 +62,10 @@ def parse():
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="grouped-query attention: key/value heads of the workload (0 = as many as "
                          "query heads)")
+    ap.add_argument("--decode", type=int, default=0, metavar="Q_LEN",
+                    help="instead of a training-shaped step: time the decode-shaped forward for the "
+                         "last Q_LEN positions of the workload's sequence plus 37 tokens (a ragged "
+                         "last block); prints one JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB device to device once (a kernel of "
@@ -184,6 +188,44 @@ def measure(w, a, moba, binding, workloads, torch):
             "kernel_ms": kernel_ms, "stages": stages}
 
 
+def decode_bench(w, a, moba, binding, torch):
+    """Latency of moba_decode_forward: q_len queries at the end of N = w.N + 37 keys (so that the
+    own block is ragged), centroids of the complete blocks resident as a caller's cache would
+    hold them.  HBM-side work per call: the centroids, and k + 1 blocks of K and V per query."""
+    q_len, N = a.decode, w.N + 37
+    dt = w.torch_dtype
+    es = 2 if w.dtype == "bf16" else 4
+    g = torch.Generator(device="cuda").manual_seed(w.seed)
+    Q = torch.randn((w.batch, w.heads, q_len, w.d), generator=g, device="cuda").to(dt)
+    K = torch.randn((w.batch, w.hkv, N, w.d), generator=g, device="cuda").to(dt)
+    V = torch.randn((w.batch, w.hkv, N, w.d), generator=g, device="cuda").to(dt)
+    npast = (N - 1) // w.B
+    cent = K[:, :, :npast * w.B].float().reshape(w.batch, w.hkv, npast, w.B, w.d).mean(3).contiguous()
+    sh = moba.Shape(w.batch, w.heads, N, w.d, w.B, w.k, 0,
+                    binding.BF16 if w.dtype == "bf16" else binding.F32, 0.0, 0, w.kv_heads)
+    for _ in range(max(a.warmup, 1)):
+        moba.decode_forward(sh, q_len, Q, K, V, cent, want_idx=False)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(a.steps, 1) * 20
+    e0.record()
+    for _ in range(reps):
+        moba.decode_forward(sh, q_len, Q, K, V, cent, want_idx=False)
+    e1.record()
+    torch.cuda.synchronize()
+    us = 1e3 * e0.elapsed_time(e1) / reps
+    bytes_call = w.bh * q_len * (npast * w.d * 4 + 2 * (min(w.k, npast) + 1) * w.B * w.d * es)
+    print(json.dumps({
+        "metric": "moba_decode_forward_latency", "value": us, "unit": "us", "n_gpus": 1, "steps": reps,
+        "warmup": max(a.warmup, 1), "higher_is_better": False, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "decode: batch %d, heads %d (%d key/value heads), %d queries at the end of "
+                               "%d keys, d %d, B %d, top-k %d, I/O %s" % (
+                                   w.batch, w.heads, w.hkv, q_len, N, w.d, w.B, w.k, w.dtype)},
+        "roofline": {"kernel": "decode", "bound": "hbm", "achieved": bytes_call / (us * 1e-6) / 1e9,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": bytes_call / (us * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                     "bytes_per_launch": bytes_call, "traffic": None}}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -235,6 +277,9 @@ def main():
     if a.kv_heads:
         w = w.scaled(kv_heads=a.kv_heads, name=w.name + "_kv%d" % a.kv_heads)
         a.config = 0
+    if a.decode:
+        decode_bench(w, a, moba, binding, torch)
+        return
     m = measure(w, a, moba, binding, workloads, torch)
     t, d, sh, R, dev = m["t"], m["d"], m["sh"], m["R"], m["dev"]
     ms_step, stage_ms, kernel_ms, stages = m["ms_step"], m["stage_ms"], m["kernel_ms"], m["stages"]

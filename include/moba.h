@@ -170,6 +170,27 @@ int moba_backward(const moba_shape* shape, const void* Q, const void* K_eff, con
                   void* stream);
 
 /*
+ * Decode-shaped forward (inference): the operator of Section 2 for the LAST q_len positions of a
+ * sequence of seqlen keys -- query r stands at position t = seqlen - q_len + r, is scored against
+ * the centroids of the complete blocks before its own block (j < t / B), keeps the topk best
+ * (ties: lower block), and attends those blocks plus its own block up to itself.  Here seqlen
+ * need NOT be a multiple of the block: the own block of a query may be the ragged last block
+ * (Appendix C.1 treats the tail block of the centroid computation the same way; its centroid is
+ * never used, the own block not being a candidate).  One kernel, no workspace, fp32 arithmetic.
+ *   Q          in   [b,heads,q_len,d] dtype
+ *   K_eff, V   in   [b,kv_heads,seqlen,d] dtype (key convolution, if any, already applied)
+ *   centroids  in   [b,kv_heads,centroid_blocks,d] fp32: means of the complete blocks, e.g. a
+ *                   cache kept by the caller; centroid_blocks >= (seqlen - 1) / B; may be NULL
+ *                   when that is 0 or topk == 0
+ *   O          out  [b,heads,q_len,d] dtype;  lse out [b,heads,q_len] fp32
+ *   topk_idx   out  [b,heads,q_len,topk] int32 ascending, -1 padded; may be NULL
+ * conv_width and flags of the shape are ignored.  At most 4096 complete blocks.
+ */
+int moba_decode_forward(const moba_shape* shape, int32_t q_len, const void* Q, const void* K_eff,
+                        const void* V, const float* centroids, int32_t centroid_blocks, void* O,
+                        float* lse, int32_t* topk_idx, void* stream);
+
+/*
  * moba_backward split into its kernels, for callers that time or overlap them:
  * `parts` is a bit set of MOBA_BWD_PREPROCESS (D = rowsum(dO o O) into the workspace),
  * MOBA_BWD_DQ and MOBA_BWD_DKDV (both read D from the workspace, so PREPROCESS must have

@@ -82,6 +82,7 @@ def lib():
         L.moba_last_hip_error.restype = ctypes.c_int
         for name in ("moba_routes_per_slice", "moba_workspace_bytes", "moba_centroids", "moba_topk",
                      "moba_build_lists", "moba_forward", "moba_backward", "moba_backward_parts",
+                     "moba_decode_forward",
                      "moba_profile_begin", "moba_profile_end", "moba_key_conv_backward",
                      "moba_key_conv_backward_workspace"):
             getattr(L, name).restype = ctypes.c_int
@@ -224,6 +225,26 @@ def backward(shape: Shape, Q, K_eff, V, O, lse, dO, idx, lists, ws=None, out=Non
                                          _p(dK), _p(dV), _p(ws), ctypes.c_size_t(ws.numel()), _stream(),
                                          ctypes.c_uint32(parts)), "moba_backward_parts")
     return dQ, dK, dV
+
+
+def decode_forward(shape: Shape, q_len, Q, K_eff, V, cent, want_idx=True):
+    """Decode-shaped forward for the last q_len positions of shape.seqlen keys (any length).
+    -> (O [b,h,q_len,d], lse [b,h,q_len] fp32, topk_idx [b,h,q_len,k] int32 or None)."""
+    for t in (Q, K_eff, V):
+        assert t.is_contiguous() and t.dtype == shape.torch_dtype
+    assert Q.shape[2] == q_len and K_eff.shape[2] == shape.seqlen
+    blocks = 0
+    if cent is not None:
+        assert cent.is_contiguous() and cent.dtype == torch.float32
+        blocks = cent.shape[2]
+    O = torch.empty_like(Q)
+    lse = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    idx = (torch.empty((shape.batch, shape.heads, q_len, shape.topk), dtype=torch.int32, device=Q.device)
+           if want_idx else None)
+    _check(lib().moba_decode_forward(ctypes.byref(shape.c()), ctypes.c_int32(q_len), _p(Q), _p(K_eff),
+                                     _p(V), _p(cent), ctypes.c_int32(blocks), _p(O), _p(lse), _p(idx),
+                                     _stream()), "moba_decode_forward")
+    return O, lse, idx
 
 
 PROFILE_KERNELS = ("topk", "forward", "bwd_dq", "bwd_dkdv")

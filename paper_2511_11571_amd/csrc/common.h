@@ -186,6 +186,8 @@ struct ProfileScope {
 // launchers (one translation unit each); every one returns a hipError_t
 hipError_t launch_centroids(const Dims& s, const void* K, const float* w, void* Keff,
                             float* cent, hipStream_t st);
+hipError_t launch_decode(const Dims& s, int q_len, const void* Q, const void* K, const void* V,
+                         const float* cent, int cblocks, void* O, float* lse, int32_t* idx, hipStream_t st);
 hipError_t launch_conv_backward(const Dims& s, const void* K, const float* w, const void* G, void* dK,
                                 float* dw, void* ws, hipStream_t st);
 size_t conv_bwd_ws_bytes(const Dims& s);

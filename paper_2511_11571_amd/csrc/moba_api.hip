@@ -22,12 +22,12 @@ constexpr int kMaxBlocks = 4096;   // key blocks per head the scoring kernels ke
 constexpr int kMaxTopk = 4096;
 
 // Fills `d` from `shape`; returns MOBA_OK or the status to hand back.
-int make_dims(const moba_shape* sh, Dims& d)
+int make_dims(const moba_shape* sh, Dims& d, bool ragged_ok = false)
 {
     if (!sh) return MOBA_EINVAL;
     if (sh->batch <= 0 || sh->heads <= 0 || sh->seqlen <= 0 || sh->head_dim <= 0) return MOBA_EINVAL;
     if (sh->block <= 0 || sh->topk < 0 || sh->conv_width < 0) return MOBA_EINVAL;
-    if (sh->seqlen % sh->block != 0) return MOBA_EINVAL;
+    if (!ragged_ok && sh->seqlen % sh->block != 0) return MOBA_EINVAL;
     if (sh->dtype != MOBA_F32 && sh->dtype != MOBA_BF16) return MOBA_EINVAL;
     if (sh->flags & ~(uint32_t)(MOBA_FLAG_REFERENCE_KERNELS | MOBA_FLAG_KEY_MAJOR | MOBA_FLAG_QUERY_TILES))
         return MOBA_EINVAL;
@@ -270,6 +270,22 @@ int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, cons
                                               (hipStream_t)stream));
     return hip_status(
         launch_forward_reference(d, Q, K_eff, V, topk_idx, O, lse, (hipStream_t)stream));
+}
+
+int moba_decode_forward(const moba_shape* shape, int32_t q_len, const void* Q, const void* K_eff,
+                        const void* V, const float* centroids, int32_t centroid_blocks, void* O,
+                        float* lse, int32_t* topk_idx, void* stream)
+{
+    Dims d;
+    const int st = make_dims(shape, d, true);              // any seqlen: the last block may be ragged
+    if (st != MOBA_OK) return st;
+    if (q_len <= 0 || q_len > d.N || centroid_blocks < 0) return MOBA_EINVAL;
+    if (!Q || !K_eff || !V || !O || !lse) return MOBA_EINVAL;
+    const int past_max = (d.N - 1) / d.B;                  // complete blocks before the last query's own
+    if (d.k > 0 && past_max > 0 && (!centroids || centroid_blocks < past_max)) return MOBA_EINVAL;
+    if (past_max > kMaxBlocks) return MOBA_EUNSUPPORTED;
+    return hip_status(launch_decode(d, q_len, Q, K_eff, V, centroids, centroid_blocks, O, lse, topk_idx,
+                                    (hipStream_t)stream));
 }
 
 int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,

@@ -34,6 +34,20 @@ def _shape(**kw):
     return binding.Shape(**base)
 
 
+def test_decode_forward_rejects_bad_arguments(lib):
+    """Host-side checks only: every call returns before anything is launched."""
+    one = ctypes.c_void_p(256)                 # never dereferenced on these paths
+    sh = _shape(seqlen=1000).c()               # any length: the last block may be ragged
+    f = lib.moba_decode_forward
+    assert f(ctypes.byref(sh), 0, one, one, one, one, 31, one, one, None, None) == -1      # q_len
+    assert f(ctypes.byref(sh), 1001, one, one, one, one, 31, one, one, None, None) == -1
+    assert f(ctypes.byref(sh), 4, None, one, one, one, 31, one, one, None, None) == -1     # Q
+    assert f(ctypes.byref(sh), 4, one, one, one, one, 30, one, one, None, None) == -1      # too few centroids
+    assert f(ctypes.byref(sh), 4, one, one, one, None, 0, one, one, None, None) == -1
+    big = _shape(seqlen=4098 * 32 + 5).c()     # more than 4096 complete blocks
+    assert f(ctypes.byref(big), 1, one, one, one, one, 5000, one, one, None, None) == -2
+
+
 def test_grouped_query_shapes_are_accepted(lib):
     R = ctypes.c_int64(0)
     for kv in (0, 1, 2, 4):
