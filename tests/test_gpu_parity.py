@@ -328,6 +328,58 @@ def test_grouped_query_heads(oracle, w, flags):
         assert parity.rel_l2(gw.double().cpu().numpy(), rgw) < 1e-4
 
 
+# ------------------------------------------------------------------ ragged sequence by zero padding
+
+def test_ragged_sequence_by_zero_padding():
+    """N % B != 0 in a training-shaped call: pad Q, K, V and dO with zero rows to the next
+    multiple of B.  A query never sees a later key, the padded block is never a routing
+    candidate of a real query (candidates are blocks before the query's own), and zero dO rows
+    add nothing to dK and dV -- so the real rows are exact.  Checked against a dense fp64
+    evaluation of the ragged sequence itself (tail block shorter than B), not of the padded one."""
+    from tests import brute
+    N, B, k, d, heads = 1000, 32, 4, 64, 2
+    Np = -(-N // B) * B
+    g = torch.Generator().manual_seed(91)
+    Q, K, V, dO = (torch.randn((1, heads, N, d), generator=g).to(torch.bfloat16) for _ in range(4))
+    pad = lambda x: torch.cat([x, torch.zeros((1, heads, Np - N, d), dtype=x.dtype)], dim=2).cuda()
+    sh = moba.Shape(1, heads, Np, d, B, k, 0, binding.BF16)
+    Keff, cent = moba.centroids(sh, pad(K))
+    idx, lists = moba.topk(sh, pad(Q), cent)
+    O, lse = moba.forward(sh, pad(Q), Keff, pad(V), idx, lists)
+    dQ, dK, dV = moba.backward(sh, pad(Q), Keff, pad(V), O, lse, pad(dO), idx, lists)
+    scale = 1.0 / np.sqrt(d)
+    for h in range(heads):
+        q, kk, v, go = (x[0, h].double().numpy() for x in (Q, K, V, dO))
+        # the ragged definition: complete past blocks are the candidates, own block up to t
+        nfull = N // B
+        cen = kk[:nfull * B].reshape(nfull, B, d).mean(1).astype(np.float32).astype(np.float64)
+        mask = np.zeros((N, N), dtype=bool)
+        for t in range(N):
+            own = t // B
+            cand = sorted(range(own), key=lambda j: (-float(q[t] @ cen[j]), j))[:k]
+            for j in cand:
+                mask[t, j * B:(j + 1) * B] = True
+            mask[t, own * B:t + 1] = True
+        rO, rlse, _ = brute.dense_attention(q, kk, v, mask, scale)
+        rQ, rK, rV = brute.dense_backward(q, kk, v, mask, scale, go)
+        got = lambda x: x[0, h, :N].double().cpu().numpy()
+        same = np.ones(N, bool)
+        gi = idx[0, h, :N].cpu().numpy()
+        for t in range(N):       # rows whose routing matches (fp32 near-ties aside) compare one by one
+            own = t // B
+            ref = sorted(sorted(range(own), key=lambda j: (-float(q[t] @ cen[j]), j))[:k])
+            same[t] = ref == sorted(int(x) for x in gi[t] if x >= 0)
+        assert same.mean() > 0.99
+        assert np.abs(got(O) - rO)[same].max() < parity.O_TOL["bf16"]
+        assert np.abs(lse[0, h, :N].double().cpu().numpy() - rlse)[same].max() < parity.LSE_TOL["bf16"]
+        assert parity.rel_l2(got(dQ)[same], rQ[same]) < parity.GRAD_TOL["bf16"]
+        if same.all():
+            assert parity.rel_l2(got(dK), rK) < parity.GRAD_TOL["bf16"]
+            assert parity.rel_l2(got(dV), rV) < parity.GRAD_TOL["bf16"]
+        # the padded rows take nothing and give nothing
+        assert float(dK[0, h, N:].abs().max()) == 0.0 and float(dV[0, h, N:].abs().max()) == 0.0
+
+
 # ------------------------------------------------------------------ the whole chain on its own routing
 
 @pytest.mark.parametrize("flags", FLAGS)
