@@ -301,12 +301,6 @@ __global__ __launch_bounds__(256) void dq_km_merge_kernel(
 
 // ---- workspace: [D: bh*N fp32][slot-ordered K][partial dQ: bh*N*(k+1)*parts*D bf16], each
 // 256-byte aligned
-static size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
-
-static size_t km_partials(const Dims& s)
-{
-    return (size_t)s.bh * s.N * (size_t)(s.k + 1) * (size_t)(s.B / km_part_keys(s.B, s.D));
-}
 
 size_t backward_km_ws_bytes(const Dims& s)
 {

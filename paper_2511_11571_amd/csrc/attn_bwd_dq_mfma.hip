@@ -290,7 +290,6 @@ static hipError_t dq_launch(const Dims& s, const void* Q, const void* Ka, const 
 // Workspace of the MFMA backward: [D vector: bh*N fp32][slot-ordered scaled K: bh*N*D bf16]
 // [operand-ordered K: bh*N*D bf16][operand-ordered V: bh*N*D bf16][kmax: bh*D words]
 // [vmax: bh*D words], each part 256-byte aligned.
-static size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 size_t backward_mfma_ws_bytes(const Dims& s)
 {

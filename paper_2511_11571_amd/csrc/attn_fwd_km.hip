@@ -344,12 +344,6 @@ __global__ __launch_bounds__(256) void fwd_km_merge_kernel(
 
 // ---- workspace: [slot-ordered V][partial O: bh*N*(k+1)*parts*D bf16][partial (m, l):
 // bh*N*(k+1)*parts*2 fp32], each 256-byte aligned
-static size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
-
-static size_t km_partials(const Dims& s)
-{
-    return (size_t)s.bh * s.N * (size_t)(s.k + 1) * (size_t)(s.B / km_part_keys(s.B, s.D));
-}
 
 size_t forward_km_ws_bytes(const Dims& s)
 {

@@ -230,6 +230,16 @@ __host__ __device__ inline int km_part_keys(int B, int D)
     return B <= cap ? B : cap;
 }
 
+// workspace parts start on 256-byte boundaries
+inline size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// (query, kept block or own block, part of the block) triples: the partial results of the
+// key-major kernels, [bh][N][k+1][parts]
+inline size_t km_partials(const Dims& s)
+{
+    return (size_t)s.bh * s.N * (size_t)(s.k + 1) * (size_t)(s.B / km_part_keys(s.B, s.D));
+}
+
 // shapes the MFMA kernels cover: bf16 I/O and key blocks made of whole 32-key groups
 inline bool mfma_path(const Dims& s)
 {
