@@ -282,6 +282,7 @@ GQA = [
     W("gqa_B128", 2, 4, 1024, 64, 128, 2, kv_heads=2, seed=84),
     W("gqa_conv", 1, 4, 640, 64, 32, 2, kv_heads=2, conv_width=3, seed=85),
     W("gqa_B16", 1, 6, 320, 64, 16, 5, kv_heads=3, seed=86),               # plain kernels for bf16 too
+    W("gqa_B256_parts", 1, 4, 2048, 64, 256, 2, kv_heads=2, seed=87),      # key-major: two parts per block
 ]
 
 
