@@ -108,7 +108,7 @@ __device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int ti
 constexpr int kTopkWaves = 2;             // waves per 64-query strip (= per workgroup)
 
 template <int D>
-__global__ __launch_bounds__(kTopkWaves * kWave) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2)))
+__global__ __launch_bounds__(kTopkWaves * kWave) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 3)))
 void topk_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ c3, int ntile_all,
     int32_t* __restrict__ idx, int N, int B, int n, int k, int strips_per_slice, int Wn, int G)
