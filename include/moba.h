@@ -77,6 +77,9 @@ typedef struct moba_shape {
                             * dK and dV are summed over the query heads that share the head. */
 } moba_shape;
 
+/* In the argument tables below h stands for the query heads (shape.heads) and kv for the key/value
+ * heads (shape.kv_heads, or heads when that is 0). */
+
 /* Host-only helpers.  R and the byte counts are written to host memory. */
 int moba_routes_per_slice(const moba_shape* shape, int64_t* R);
 int moba_workspace_bytes(const moba_shape* shape, size_t* topk_ws, size_t* fwd_ws, size_t* bwd_ws);
@@ -85,11 +88,11 @@ int moba_workspace_bytes(const moba_shape* shape, size_t* topk_ws, size_t* fwd_w
  * Key convolution (Appendix B, k'_t = k_t + SiLU(sum_l W_l * k_{t-l}), terms with
  * t-l < 0 dropped) followed by the block centroids (Section 2; Appendix C.1,
  * centroid algorithm).
- *   K         in   [b,h,N,d] dtype
- *   conv_w    in   [heads,d,W] fp32, last axis = lag l; must be NULL iff conv_width == 0
- *   K_eff     out  [b,h,N,d] dtype: the convolved keys rounded to dtype; required iff
+ *   K         in   [b,kv,N,d] dtype
+ *   conv_w    in   [kv,d,W] fp32, last axis = lag l; must be NULL iff conv_width == 0
+ *   K_eff     out  [b,kv,N,d] dtype: the convolved keys rounded to dtype; required iff
  *                  conv_width > 0 (with conv_width == 0 it may be NULL; if given, K is copied)
- *   centroids out  [b,h,n,d] fp32: mean over each block of the (rounded) K_eff rows
+ *   centroids out  [b,kv,n,d] fp32: mean over each block of the (rounded) K_eff rows
  */
 int moba_centroids(const moba_shape* shape, const void* K, const float* conv_w,
                    void* K_eff, float* centroids, void* stream);
@@ -99,11 +102,11 @@ int moba_centroids(const moba_shape* shape, const void* K, const float* conv_w,
  * convolution to the token-level keys and to the kernel weights).  The rounding of K_eff to
  * dtype is taken as the identity.  With a_t = sum_l W_l * k_{t-l}, g_t = dK_eff_t * SiLU'(a_t):
  *   dK_t = dK_eff_t + sum_{l, t+l<N} W_l * g_{t+l},   dconv_w[h][c][l] = sum_{batch, t>=l} g_t k_{t-l}
- *   K        in   [b,h,N,d] dtype: the keys the convolution was applied to
- *   conv_w   in   [heads,d,W] fp32
- *   dK_eff   in   [b,h,N,d] dtype: gradient with respect to K_eff (dK of moba_backward)
- *   dK       out  [b,h,N,d] dtype: gradient with respect to K; must not overlap dK_eff
- *   dconv_w  out  [heads,d,W] fp32, summed over the batch in a fixed order
+ *   K        in   [b,kv,N,d] dtype: the keys the convolution was applied to
+ *   conv_w   in   [kv,d,W] fp32
+ *   dK_eff   in   [b,kv,N,d] dtype: gradient with respect to K_eff (dK of moba_backward)
+ *   dK       out  [b,kv,N,d] dtype: gradient with respect to K; must not overlap dK_eff
+ *   dconv_w  out  [kv,d,W] fp32, summed over the batch in a fixed order
  *   ws            at least moba_key_conv_backward_workspace bytes
  * conv_width must be at least 1.
  */
@@ -117,7 +120,7 @@ int moba_key_conv_backward(const moba_shape* shape, const void* K, const float* 
  * followed by the key-block-major query lists (Appendix C.1, varlen reformatting).
  * The N x n score matrix is never written to memory.
  *   Q         in   [b,h,N,d] dtype
- *   centroids in   [b,h,n,d] fp32
+ *   centroids in   [b,kv,n,d] fp32
  *   topk_idx  out  [b,h,N,topk] int32: kept past blocks of each query in ascending
  *                  block order, -1 in unused trailing slots
  *   blk_off   out  [b,h,n+1] int32: exclusive prefix sums of the per-block list lengths
@@ -143,7 +146,8 @@ int moba_build_lists(const moba_shape* shape, const int32_t* topk_idx,
 /*
  * Attention over the kept blocks plus the causally masked own block
  * (Section 2; Section 4.2 forward algorithm).  Routing is an input.
- *   Q, K_eff, V   in   [b,h,N,d] dtype (K_eff = K when there is no convolution)
+ *   Q             in   [b,h,N,d] dtype
+ *   K_eff, V      in   [b,kv,N,d] dtype (K_eff = K when there is no convolution)
  *   topk_idx, blk_off, blk_q   in   as produced by moba_topk / moba_build_lists
  *   O         out  [b,h,N,d] dtype
  *   lse       out  [b,h,N] fp32: natural log of sum_u exp(scale * q.k_u) over the kept keys
@@ -159,8 +163,10 @@ int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, cons
  * D = rowsum(dO o O), P = exp(S - lse), dV = P^T dO, dS = P o (dO V^T - D),
  * dQ = scale * dS K, dK = scale * dS^T Q.  dK is the gradient with respect to K_eff.
  * No gradient flows through the gate (centroids / top-k).
- *   Q, K_eff, V, O, dO   in   [b,h,N,d] dtype;   lse in [b,h,N] fp32 (from moba_forward)
- *   dQ, dK, dV           out  [b,h,N,d] dtype
+ *   Q, O, dO             in   [b,h,N,d] dtype;   lse in [b,h,N] fp32 (from moba_forward)
+ *   K_eff, V             in   [b,kv,N,d] dtype
+ *   dQ                   out  [b,h,N,d] dtype
+ *   dK, dV               out  [b,kv,N,d] dtype, summed over the query heads that share the head
  *   ws                        at least bwd_ws bytes
  */
 int moba_backward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
