@@ -106,8 +106,12 @@ __device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int ti
 }
 
 constexpr int kTopkWaves = 2;             // waves per 64-query strip (= per workgroup)
+// The kept blocks of a query are collected in LDS either as a bit row over the n blocks or, for
+// small top-k, as a list of at most kKeptList block ids (2 KB per strip instead of 8 n bytes:
+// with thousands of blocks the bit rows would cap the workgroups per CU).
+constexpr int kKeptList = 16;
 
-template <int D>
+template <int D, bool LISTS>
 __global__ __launch_bounds__(kTopkWaves * kWave) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 3)))
 void topk_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ c3, int ntile_all,
@@ -128,7 +132,27 @@ void topk_mfma_kernel(
     uint32_t* st_state = st_need + 64;
     uint32_t* st_past = st_state + 64;
     uint32_t* st_hi = st_past + 64;                // the current interval is [lo, hi): at most 64 bins of 2^sh keys
-    uint32_t* selm = st_hi + 64;                   // [64][Wn] kept-block bits
+    uint32_t* selm = st_hi + 64;                   // [64][Wn] kept-block bits, or:
+    uint16_t* lst = reinterpret_cast<uint16_t*>(selm);      // [64][kKeptList] kept blocks, any order
+    uint32_t* lcnt = selm + 64 * kKeptList / 2;             // [64] their number
+    const int sel_words = LISTS ? 64 * kKeptList / 2 + 64 : 64 * Wn;
+    // one more kept block of query q (concurrent callers) / (only caller for q)
+    auto keep_atomic = [&](int q, int blk) {
+        if constexpr (LISTS) {
+            const uint32_t slot = atomicAdd(&lcnt[q], 1u);
+            if (slot < (uint32_t)kKeptList) lst[q * kKeptList + slot] = (uint16_t)blk;
+        } else {
+            atomicOr(&selm[q * Wn + (blk >> 5)], 1u << (blk & 31));
+        }
+    };
+    auto keep_plain = [&](int q, int blk) {
+        if constexpr (LISTS) {
+            const uint32_t slot = lcnt[q]++;
+            if (slot < (uint32_t)kKeptList) lst[q * kKeptList + slot] = (uint16_t)blk;
+        } else {
+            selm[q * Wn + (blk >> 5)] |= 1u << (blk & 31);
+        }
+    };
 
     const int s = strip / strips_per_slice;
     const int t0 = (strip % strips_per_slice) * 64;
@@ -145,7 +169,7 @@ void topk_mfma_kernel(
         st_need[lane] = (uint32_t)min(k, past);
         st_state[lane] = past <= k ? 1u : 0u;      // few candidates: keep them all (every key >= 0)
     }
-    for (int i = tid; i < 64 * Wn; i += kTopkWaves * kWave) selm[i] = 0u;
+    for (int i = tid; i < sel_words; i += kTopkWaves * kWave) selm[i] = 0u;
     const int pmax = (t0 + rows_here - 1) / B;
     const int ntile = (pmax + 15) / 16;
 
@@ -304,7 +328,14 @@ void topk_mfma_kernel(
                 }
                 if (keep && ok) bits |= 1u << i;
             }
-            if (bits) atomicOr(&selm[(16 * qt + m16) * Wn + (j0 >> 5)], bits << (j0 & 31));
+            if constexpr (LISTS) {
+                while (bits) {
+                    keep_atomic(16 * qt + m16, j0 + __ffs(bits) - 1);
+                    bits &= bits - 1;
+                }
+            } else {
+                if (bits) atomicOr(&selm[(16 * qt + m16) * Wn + (j0 >> 5)], bits << (j0 & 31));
+            }
         });
         __syncthreads();
         if (wave == 0 && st_state[lane] == 3u) {     // lane = query: the best `need` candidates
@@ -321,7 +352,7 @@ void topk_mfma_kernel(
                 }
                 if (best < 0) break;
                 used |= 1u << best;
-                selm[lane * Wn + (bj >> 5)] |= 1u << (bj & 31);
+                keep_plain(lane, (int)bj);
             }
         }
         // ties at the threshold: the lowest block indices among the equal scores, 1024 blocks at a time
@@ -344,7 +375,7 @@ void topk_mfma_kernel(
                         uint32_t word = hist[lane * kHistStride + w];
                         while (word && need > 0) {
                             const int b = __ffs(word) - 1;
-                            selm[lane * Wn + (r0 >> 5) + w] |= 1u << b;
+                            keep_plain(lane, r0 + 32 * w + b);
                             word &= word - 1;
                             --need;
                         }
@@ -360,13 +391,25 @@ void topk_mfma_kernel(
     if (wave == 0 && lane < rows_here) {
         int32_t* row = out + (int64_t)lane * k;
         int pos = 0;
-        for (int w = 0; w < Wn; ++w) {
-            uint32_t word = selm[lane * Wn + w];
-            while (word) {
-                const int b = __ffs(word) - 1;
-                if (pos < k) row[pos] = 32 * w + b;
-                ++pos;
-                word &= word - 1;
+        if constexpr (LISTS) {
+            uint16_t* mine = lst + lane * kKeptList;
+            const int c = min((int)lcnt[lane], min(k, kKeptList));
+            for (int a = 1; a < c; ++a) {                 // insertion sort, ascending
+                const uint16_t v = mine[a];
+                int b = a - 1;
+                for (; b >= 0 && mine[b] > v; --b) mine[b + 1] = mine[b];
+                mine[b + 1] = v;
+            }
+            for (; pos < c; ++pos) row[pos] = mine[pos];
+        } else {
+            for (int w = 0; w < Wn; ++w) {
+                uint32_t word = selm[lane * Wn + w];
+                while (word) {
+                    const int b = __ffs(word) - 1;
+                    if (pos < k) row[pos] = 32 * w + b;
+                    ++pos;
+                    word &= word - 1;
+                }
             }
         }
         for (; pos < k; ++pos) row[pos] = -1;
@@ -384,21 +427,30 @@ bool topk_mfma_supported(const Dims& s)
            s.n <= kTopkMfmaMaxBlocks && s.k > 0;
 }
 
-template <int D>
-static hipError_t topk_launch(const Dims& s, const void* Q, const bf16_t* c3, int32_t* idx,
-                              hipStream_t st)
+template <int D, bool LISTS>
+static hipError_t topk_launch2(const Dims& s, const void* Q, const bf16_t* c3, int32_t* idx,
+                               hipStream_t st)
 {
     const int sps = (s.N + 63) / 64;
     const int64_t strips = (int64_t)sps * s.bh;
     const int Wn = ((s.n + 31) / 32) | 1;      // words per bit row, odd for the same reason
-    const size_t lds = sizeof(uint32_t) * (size_t)(64 * kHistStride + 6 * 64 + 64 * Wn);
-    hipError_t e = hipFuncSetAttribute((const void*)topk_mfma_kernel<D>,
+    const size_t lds = sizeof(uint32_t) * (size_t)(64 * kHistStride + 6 * 64 +
+                                                   (LISTS ? 64 * kKeptList / 2 + 64 : 64 * Wn));
+    hipError_t e = hipFuncSetAttribute((const void*)topk_mfma_kernel<D, LISTS>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     ProfileScope timing(MOBA_PROFILE_TOPK, st);
-    hipLaunchKernelGGL((topk_mfma_kernel<D>), dim3((unsigned)strips), dim3(kTopkWaves * kWave), lds, st,
+    hipLaunchKernelGGL((topk_mfma_kernel<D, LISTS>), dim3((unsigned)strips), dim3(kTopkWaves * kWave), lds, st,
                        (const bf16_t*)Q, c3, (s.n + 15) / 16, idx, s.N, s.B, s.n, s.k, sps, Wn, s.G);
     return hipGetLastError();
+}
+
+template <int D>
+static hipError_t topk_launch(const Dims& s, const void* Q, const bf16_t* c3, int32_t* idx,
+                              hipStream_t st)
+{
+    return s.k <= kKeptList ? topk_launch2<D, true>(s, Q, c3, idx, st)
+                            : topk_launch2<D, false>(s, Q, c3, idx, st);
 }
 
 hipError_t launch_topk_mfma(const Dims& s, const void* Q, const float* cent, int32_t* idx, void* ws,
