@@ -42,6 +42,11 @@ struct DkvCfg {
     static constexpr int RSTRIDE = D + 4;              // floats per key row of the reduction buffer
     static constexpr size_t STAGE = (size_t)2 * 32 * SB;                   // Q and dO, bytes per wave
     static constexpr size_t LDS = NW * (STAGE + 2 * 32 * 4) + (size_t)2 * 32 * RSTRIDE * 4;
+    // wide variant: two sets of four slots (the waves park one slot each, all read all four); at
+    // the end every wave turns its accumulators over in 2 * 32 * RSTRIDE floats of its own
+    static constexpr size_t WIDE_PARK = (size_t)2 * NW * (STAGE + 2 * 32 * 4);
+    static constexpr size_t WIDE_OUT = (size_t)NW * 2 * 32 * RSTRIDE * 4;
+    static constexpr size_t LDS_WIDE = WIDE_PARK > WIDE_OUT ? WIDE_PARK : WIDE_OUT;
 };
 
 // LDS transpose read: within each group of 16 lanes, lane i receives as element e the 16-bit
@@ -54,8 +59,14 @@ __device__ __forceinline__ uint2 lds_read_tr16(const unsigned char* p)
     return *reinterpret_cast<const uint2*>(&r);
 }
 
-template <int D>
-__global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
+// WIDE (key blocks of whole 128-key parts): a workgroup owns four consecutive 32-key groups, one
+// per wave; a step covers 128 positions of the walk -- every wave gathers and parks 32 of them,
+// and after a barrier every wave works through all four slots with its own keys.  The block's
+// list is then gathered once per 128 keys instead of once per 32, and nothing has to be summed
+// over the waves.
+template <int D, bool WIDE>
+__global__ __launch_bounds__(DkvCfg<D>::NT) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1)))
+void dkdv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ Dv,
     const int32_t* __restrict__ off, const int32_t* __restrict__ ql, bf16_t* __restrict__ dK,
@@ -66,19 +77,20 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int m16 = lane & 15, g = lane >> 4;
-    unsigned char* stQ = smem + wave * (C::STAGE + 256);
-    unsigned char* stG = stQ + 32 * C::SB;
-    float* ls = reinterpret_cast<float*>(stQ + C::STAGE);
-    float* Ds = ls + 32;
-    float* red = reinterpret_cast<float*>(smem + C::NW * (C::STAGE + 256));    // [2][32][RSTRIDE]
+    constexpr size_t SLOT = C::STAGE + 256;                 // parked Q rows, dO rows, lse, -D of 32 positions
+    float* red = reinterpret_cast<float*>(WIDE ? smem + (size_t)wave * 2 * 32 * C::RSTRIDE * 4
+                                               : smem + C::NW * SLOT);        // [2][32][RSTRIDE]
 
-    int skv, kap;                                           // key/value slice, 32-key group inside it
-    if (!schedule(blockIdx.x, bhk, groups_per_slice, skv, kap)) return;
+    int skv, unit;                                          // key/value slice; 32-key group or 128-key part
+    if (!schedule(blockIdx.x, bhk, groups_per_slice, skv, unit)) return;
+    const int kap = WIDE ? 4 * unit + wave : unit;          // this wave's 32-key group inside the slice
     const int NG = B / 32;
     const int j = kap / NG;
     const int64_t kvbase = (int64_t)skv * N;
     const float c2 = scale * kLog2e;
-    const int own0 = 32 * kap;                              // first own query that sees this group
+    const int own0 = WIDE ? 128 * unit : 32 * kap;          // first own query that sees the workgroup's keys
+    const int kfirst = WIDE ? 32 * wave : 0;                // this wave's first key, counted from there
+    int parity = 0;                                         // WIDE: which set of slots the next step parks in
 
     // B operands: the group's keys and values (lane = key m16 of tile nt)
     Frag kb[2][C::KS], vb[2][C::KS];
@@ -170,17 +182,11 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
     const int te = (lane >> 2) & 3, ta = lane & 3;
     const uint32_t tr0 = (uint32_t)slot_key(g, te) * C::SB + 8u * ta;
     const uint32_t tr1 = (uint32_t)slot_key(g, te + 4) * C::SB + 8u * ta;
-    auto step = [&](int a0, auto inside) {
-        // park this step's rows, then put the next step's loads in flight
-#pragma unroll
-        for (int i = 0; i < C::NI; ++i) {
-            *reinterpret_cast<u32x4_t*>(stQ + park + i * C::RPI * C::SB) = qr[i];
-            *reinterpret_cast<u32x4_t*>(stG + park + i * C::RPI * C::SB) = gr[i];
-        }
-        if (lane < 32) { ls[lane] = lv; Ds[lane] = dv; }
-        fetch(a0 + stride, tN, tlN, qr, gr, lv, dv, inside);
-        ids(a0 + 2 * stride, tN, tlN, inside);
-        __builtin_amdgcn_wave_barrier();
+    // the arithmetic of 32 parked positions (walk positions p0 .. p0 + 31) against this wave's keys
+    auto work = [&](unsigned char* stQ, int p0, auto inside) {
+        unsigned char* stG = stQ + 32 * C::SB;
+        const float* ls = reinterpret_cast<const float*>(stQ + C::STAGE);
+        const float* Ds = ls + 32;
         // S and dP
         f32x4_t sc[2][2], dp[2][2];
 #pragma unroll
@@ -203,8 +209,9 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
                 }
             }
         }
-        // own queries of this very group are causal: key (16 nt + m16) must not exceed the query
-        const bool causal = !decltype(inside)::value && a0 + 32 > nlist && a0 < nlist + 32;    // the step touches own rows 0..31
+        // own queries are causal: the wave's key kfirst + 16 nt + m16 (counted from the first own
+        // query's key) must not exceed the query
+        const bool causal = !decltype(inside)::value && p0 + 32 > nlist && p0 < nlist + kfirst + 32;
         Frag pb[2], sb[2];
         f32x4_t l4[2];
 #pragma unroll
@@ -218,8 +225,8 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
                 for (int i = 0; i < 4; ++i) {
                     float pv = fast_exp2(fmaf(sc[qt][nt][i], c2, -l4[qt][i]));
                     if (causal) {
-                        const int a = a0 + 16 * qt + 4 * g + i - nlist;     // own row index, if >= 0
-                        if (a >= 0 && a < 32 && 16 * nt + m16 > a) pv = 0.f;
+                        const int a = p0 + 16 * qt + 4 * g + i - nlist;     // own row index, if >= 0
+                        if (a >= 0 && kfirst + 16 * nt + m16 > a) pv = 0.f;
                     }
                     p[4 * qt + i] = pv;
                     d[4 * qt + i] = pv * dp[qt][nt][i];
@@ -247,13 +254,74 @@ __global__ __launch_bounds__(DkvCfg<D>::NT) void dkdv_mfma_kernel(
         }
         __builtin_amdgcn_wave_barrier();
     };
+    // one step of this wave at walk position a0: park the 32 rows, put the next step's loads in
+    // flight, then the arithmetic -- on the wave's own slot, or (WIDE) on the four slots of the
+    // workgroup's 128 positions
+    auto step = [&](int a0, auto inside) {
+        unsigned char* mine = smem + (WIDE ? (size_t)(4 * parity + wave) * SLOT : (size_t)wave * SLOT);
+#pragma unroll
+        for (int i = 0; i < C::NI; ++i) {
+            *reinterpret_cast<u32x4_t*>(mine + park + i * C::RPI * C::SB) = qr[i];
+            *reinterpret_cast<u32x4_t*>(mine + 32 * C::SB + park + i * C::RPI * C::SB) = gr[i];
+        }
+        if (lane < 32) {
+            float* ls = reinterpret_cast<float*>(mine + C::STAGE);
+            ls[lane] = lv;
+            ls[32 + lane] = dv;
+        }
+        fetch(a0 + stride, tN, tlN, qr, gr, lv, dv, inside);
+        ids(a0 + 2 * stride, tN, tlN, inside);
+        if constexpr (WIDE) {
+            // one barrier per step is enough: a slot set is parked again two steps later, and no
+            // wave gets there before all have passed the barrier of the step in between
+            __syncthreads();
+#pragma unroll 1
+            for (int sl = 0; sl < 4; ++sl) work(smem + (size_t)(4 * parity + sl) * SLOT, a0 - 32 * wave + 32 * sl, inside);
+            parity ^= 1;
+        } else {
+            __builtin_amdgcn_wave_barrier();
+            work(mine, a0, inside);
+        }
+    };
     // the bulk of the walk: this step, the rows fetched in it and the ids looked up in it all lie
-    // inside the block's list; then the general steps (own rows, causal mask, end of the walk)
+    // inside the block's list; then the general steps (own rows, causal mask, end of the walk).
+    // (WIDE: the same number of steps in every wave -- they meet at a barrier in each.)
     int a0 = 32 * wave;
-    for (; a0 + 2 * stride + 32 <= nlist; a0 += stride) step(a0, std::true_type());
-    for (; a0 < total; a0 += stride) step(a0, std::false_type());
+    if constexpr (WIDE) {
+        for (; a0 - 32 * wave + 3 * stride <= nlist; a0 += stride) step(a0, std::true_type());
+        for (; a0 - 32 * wave < total; a0 += stride) step(a0, std::false_type());
+    } else {
+        for (; a0 + 2 * stride + 32 <= nlist; a0 += stride) step(a0, std::true_type());
+        for (; a0 < total; a0 += stride) step(a0, std::false_type());
+    }
     }
 
+    if constexpr (WIDE) {
+        // every wave has the whole sums of its own 32 keys: turn them over in LDS (channels of a
+        // key side by side) and write them out
+        __syncthreads();                                    // the slots are no longer read
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                float* pk = red + (16 * nt + m16) * C::RSTRIDE + 16 * mt + 4 * g;
+                *reinterpret_cast<f32x4_t*>(pk) = dKT[mt][nt];
+                *reinterpret_cast<f32x4_t*>(pk + 32 * C::RSTRIDE) = dVT[mt][nt];
+            }
+        __builtin_amdgcn_wave_barrier();
+        for (int i = lane; i < 2 * 32 * (D / 8); i += kWave) {
+            const int which = i / (32 * (D / 8)), rem = i % (32 * (D / 8));
+            const int key = rem / (D / 8), c = rem % (D / 8);
+            const float* src = red + which * 32 * C::RSTRIDE + key * C::RSTRIDE + 8 * c;
+            const float mul = which == 0 ? scale : 1.f;
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = src[e] * mul;
+            bf16_t* dst = (which == 0 ? dK : dV) + (kvbase + 32 * kap + key) * D + 8 * c;
+            Vec8<bf16_t>::store(dst, v);
+        }
+        return;
+    }
     // sum the four waves' accumulators through LDS: red[tensor][key][channel]
     for (int w = 0; w < C::NW; ++w) {
         if (wave == w) {
@@ -295,13 +363,25 @@ static hipError_t dkdv_launch(const Dims& s, const void* Q, const void* K, const
     using C = DkvCfg<D>;
     const int gps = s.N / 32;
     if (gps == 0) return hipSuccess;
-    hipError_t e = hipFuncSetAttribute((const void*)dkdv_mfma_kernel<D>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+    const bool wide = s.B % 128 == 0;                       // four 32-key groups of one block per workgroup
+    const size_t lds = wide ? C::LDS_WIDE : C::LDS;
+    const int units = wide ? gps / 4 : gps;
+    hipError_t e = wide ? hipFuncSetAttribute((const void*)dkdv_mfma_kernel<D, true>,
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                        : hipFuncSetAttribute((const void*)dkdv_mfma_kernel<D, false>,
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     ProfileScope timing(MOBA_PROFILE_DKDV, st);
-    hipLaunchKernelGGL((dkdv_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bhk, gps)), dim3(C::NT), C::LDS, st,
-                       (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, Dv,
-                       off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, gps, s.bhk, s.G);
+    if (wide)
+        hipLaunchKernelGGL((dkdv_mfma_kernel<D, true>), dim3((unsigned)schedule_grid(s.bhk, units)), dim3(C::NT),
+                           lds, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO,
+                           lse, Dv, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
+                           s.bhk, s.G);
+    else
+        hipLaunchKernelGGL((dkdv_mfma_kernel<D, false>), dim3((unsigned)schedule_grid(s.bhk, units)), dim3(C::NT),
+                           lds, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO,
+                           lse, Dv, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
+                           s.bhk, s.G);
     return hipGetLastError();
 }
 
