@@ -56,10 +56,12 @@ typedef enum moba_dtype { MOBA_F32 = 0, MOBA_BF16 = 1 } moba_dtype;
                                         * up to 128 (d = 64) / 64 (d = 128), or a multiple of that;
                                         * topk <= 64); elsewhere the flag is ignored              */
 #define MOBA_FLAG_QUERY_TILES 4u       /* attention by query tile (suits dense routing): force it   */
-/* With neither of the two the library picks: key blocks if seqlen > 20 * T * topk (T = 256 queries
- * per tile at d = 64, 128 at d = 128), i.e. where a tile would meet a key block with too few of
- * its rows; query tiles otherwise.  KEY_MAJOR and QUERY_TILES together are MOBA_EINVAL.  The
- * workspace sizes depend on the choice: size and call with the same flags. */
+/* With neither of the two the library picks by a cost estimate of both from the shape: key blocks
+ * where a tile of consecutive queries would meet a key block with few of its rows (small topk,
+ * long sequences, large blocks: e.g. topk 8 of B = 128 at any length), query tiles where a query
+ * keeps many blocks (e.g. topk 64 of B = 32 up to a few hundred thousand keys).  KEY_MAJOR and
+ * QUERY_TILES together are MOBA_EINVAL.  The workspace sizes depend on the choice: size and call
+ * with the same flags. */
 
 typedef struct moba_shape {
     int32_t batch, heads, seqlen, head_dim;

@@ -219,7 +219,6 @@ bool topk_mfma_supported(const Dims& s);
 hipError_t launch_topk_mfma(const Dims& s, const void* Q, const float* cent, int32_t* idx, void* ws,
                             hipStream_t st);
 
-constexpr int kKeyMajorAboveRatio = 20;    // N / (T k) above which the key-major kernels win
 constexpr int kKeyMajorMaxTopk = 64;      // longest row of kept blocks the key-major walk searches
 
 // keys a key-major workgroup holds in registers as MFMA operands: the whole block up to 128
@@ -252,17 +251,30 @@ inline bool key_major_shape(const Dims& s)
     return mfma_path(s) && s.B % km_part_keys(s.B, s.D) == 0 && s.k <= kKeyMajorMaxTopk;
 }
 
-// Query-tile or key-major attention?  A tile of T consecutive queries (256 for d = 64, 128 for
-// d = 128) meets a past key block with about T k / n of its rows and pays for at least a
-// 16-row MFMA tile against the block's B keys; the key-major kernels pay a fixed price per
-// (query, block) pair -- the gathered row, the partial result written and read back --
-// whatever B.  Measured, the two meet near B n / (T k) = N / (T k) = 20.
+// Query-tile or key-major attention?  Both are priced per query from fits to measured times (ns
+// per query and slice on the whole chip, forward and dQ averaged; a wrong pick near the line costs
+// 10-20 %):
+//   tiles      c0 + k (B / 32) (g0 + g1 / rows): a tile of T consecutive queries (256 for d = 64,
+//              128 for d = 128) meets a past key block with rows = T k / n of its rows and pays
+//              per 32-key group at least a 16-row MFMA tile and the group's operands;
+//   key-major  c (k + 1) (1 + 0.7 (parts - 1)): the gathered row, the partial result written and
+//              read back per (query, block) pair, whatever B, and again for every further part of
+//              the block.
+// With k = 8 of B = 128 key-major wins from N = 8K on; with k = 64 of B = 32 (many blocks per
+// query, every pair a partial in memory) the tiles win up to N of a few hundred thousand.
 inline bool key_major_path(const Dims& s)
 {
     if (!key_major_shape(s) || (s.flags & MOBA_FLAG_QUERY_TILES)) return false;
     if (s.flags & MOBA_FLAG_KEY_MAJOR) return true;
-    const int T = s.D == 64 ? 256 : 128;
-    return s.k > 0 && (int64_t)s.N > (int64_t)kKeyMajorAboveRatio * T * s.k;
+    if (s.k <= 0) return false;
+    const bool d64 = s.D == 64;
+    const double T = d64 ? 256.0 : 128.0;
+    const double rows = T * s.k * (double)s.B / (double)s.N;
+    const double parts = (double)(s.B / km_part_keys(s.B, s.D));
+    const double tiles = (d64 ? 0.6 : 1.1) + 0.0013 * s.B +
+                         s.k * (s.B / 32.0) * (d64 ? 0.015 + 0.14 / rows : 0.033 + 0.272 / rows);
+    const double keymajor = (d64 ? 0.145 : 0.25) * (s.k + 1) * (1.0 + 0.7 * (parts - 1.0));
+    return keymajor < tiles;
 }
 
 size_t forward_km_ws_bytes(const Dims& s);

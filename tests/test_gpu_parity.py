@@ -245,7 +245,7 @@ KEY_MAJOR = [
     W("km_k40", 1, 1, 4096, 64, 32, 40, seed=65),
     W("km_d128_k20", 1, 1, 2048, 128, 32, 20, seed=66),
     W("km_d128_k40", 1, 1, 4096, 128, 64, 40, seed=67),
-    W("km_sparse_default", 1, 2, 16384, 64, 128, 2, seed=68),   # N > 20 * 256 * k: the library picks key-major
+    W("km_sparse_default", 1, 2, 16384, 64, 128, 2, seed=68),   # sparse enough that the library picks key-major by itself
 ]
 
 
