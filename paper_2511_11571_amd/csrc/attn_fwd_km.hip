@@ -175,7 +175,6 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
 #pragma unroll
             for (int ks = 0; ks < C::KS; ++ks)
                 qb[ks].q = *reinterpret_cast<const uint4*>(stQ + arow + qt * 16 * C::SB + 64 * ks);
-            const int2 te = *reinterpret_cast<const int2*>(stQ + (16 * qt + m16) * C::SB + 2 * D);
             const int av = a0 + 16 * qt + m16;                     // this lane's row of the walk
             // raw scores of the row against the part's keys: x[gi][4 mt + i] is key
             // 32 gi + 16 mt + 4 g + i of the part
@@ -230,22 +229,41 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
             }
             l += __shfl_xor(l, 16, kWave);
             l += __shfl_xor(l, 32, kWave);
-            // the partial: this lane holds D/4 consecutive channels of the row
-            if (av < total) {
-                const int e = min(max(te.y, 0), k);
-                const int64_t prow = (sbase + te.x) * slots + (int64_t)e * nsub + c;
+            // The partial: this lane holds D/4 consecutive channels of the row.  It goes back over
+            // the row's parked bytes (the Q operands of these 16 rows are in registers by now),
+            // (m, l) behind (t, e), and is then written out by whole rows -- CPR neighbouring
+            // lanes store one row's 2 D consecutive bytes, so every line of the partials is
+            // written by one instruction.
+            {
                 const float inv = 1.f / l;
-                uint32_t w[C::MT * 2];
+                unsigned char* prk = stQ + (16 * qt + m16) * C::SB;
 #pragma unroll
-                for (int mt = 0; mt < C::MT; ++mt) {
-                    w[2 * mt] = pack_bf16x2(o[mt][0] * inv, o[mt][1] * inv);
-                    w[2 * mt + 1] = pack_bf16x2(o[mt][2] * inv, o[mt][3] * inv);
+                for (int q4 = 0; q4 < C::MT / 2; ++q4) {
+                    kmvec4_t w;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        w[2 * h] = pack_bf16x2(o[2 * q4 + h][0] * inv, o[2 * q4 + h][1] * inv);
+                        w[2 * h + 1] = pack_bf16x2(o[2 * q4 + h][2] * inv, o[2 * q4 + h][3] * inv);
+                    }
+                    *reinterpret_cast<kmvec4_t*>(prk + g * (D / 2) + 16 * q4) = w;
                 }
-                uint4* dst = reinterpret_cast<uint4*>(PO + prow * D + g * (D / 4));
+                if (g == 0) *reinterpret_cast<float2*>(prk + 2 * D + 8) = make_float2(mref, l);
+            }
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                for (int q4 = 0; q4 < C::MT / 2; ++q4)
-                    dst[q4] = make_uint4(w[4 * q4], w[4 * q4 + 1], w[4 * q4 + 2], w[4 * q4 + 3]);
-                if (g == 0) *reinterpret_cast<float2*>(Pml + prow * 2) = make_float2(mref, l);
+            for (int h = 0; h < 16 / C::RPI; ++h) {
+                const int r = 16 * qt + C::RPI * h + grow;          // parked row of this lane
+                const unsigned char* prk = stQ + r * C::SB;
+                const kmvec4_t v = *reinterpret_cast<const kmvec4_t*>(prk + gcol);
+                const int4 note = *reinterpret_cast<const int4*>(prk + 2 * D);     // t, e, m, l
+                if (a0 + r < total) {
+                    const int e = min(max(note.y, 0), k);
+                    const int64_t prow = (sbase + note.x) * slots + (int64_t)e * nsub + c;
+                    *reinterpret_cast<kmvec4_t*>(reinterpret_cast<char*>(PO + prow * D) + gcol) = v;
+                    if (lcol == 0)
+                        *reinterpret_cast<float2*>(Pml + prow * 2) =
+                            make_float2(__int_as_float(note.z), __int_as_float(note.w));
+                }
             }
         }
         __builtin_amdgcn_wave_barrier();

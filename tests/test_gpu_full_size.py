@@ -15,15 +15,16 @@ import torch
 import paper_2511_11571_amd as moba
 import workloads
 from tests import parity
+from paper_2511_11571_amd import binding
 from tests.test_gpu_parity import dev, np64, npi, shape_of
 
 pytestmark = pytest.mark.gpu
 
 
-def run_gpu(w):
+def run_gpu(w, flags=0):
     t = workloads.generate(w)
     d = dev(t)
-    sh = shape_of(w)
+    sh = shape_of(w, flags)
     Keff, cent = moba.centroids(sh, d["K"], d["conv_w"])
     idx, lists = moba.topk(sh, d["Q"], cent)
     O, lse = moba.forward(sh, d["Q"], Keff, d["V"], idx, lists)
@@ -140,9 +141,12 @@ def test_config1_fp32_forward_full(oracle):
     assert np.abs(np64(out["lse"]).reshape(-1) - rlse.reshape(-1))[exact].max() < 1e-4
 
 
-def test_config2_bf16_forward(oracle):
+@pytest.mark.parametrize("flags", [pytest.param(0, id="default"),
+                                   pytest.param(binding.FLAG_QUERY_TILES, id="tiles")])
+def test_config2_bf16_forward(oracle, flags):
+    """(by default the library runs this shape on the key-block-major kernels)"""
     w = workloads.CONFIGS[2]
-    t, out = run_gpu(w)
+    t, out = run_gpu(w, flags)
     rng = np.random.default_rng(2)
     for s in (0, 9, 15):
         print(w.name, s, check_slice(oracle, w, t, out, s, 1024, [], rng), flush=True)
