@@ -1,9 +1,9 @@
 // dQ of the MoBA backward, key-block major, for sparse routing (paper Section 4.2 backward and
 // Appendix C.3: key blocks outermost, the queries routed to a block gathered into dense tiles,
 // S recomputed, dS = P o (dP - D), dQ += scale dS K).  The companion of attn_fwd_km.hip: a
-// workgroup owns up to 128 (d = 64) or 64 (d = 128) keys of one key block -- K, V and K^T stay
-// in registers as MFMA operands -- and walks the block's query list, then the block's own
-// queries (causally masked), 32 queries per step and wave.
+// workgroup owns up to 128 (d = 64) or 64 (d = 128) keys of one key block -- their MFMA operands
+// stay on chip for the whole walk, K and V in LDS and K^T in registers -- and walks the block's
+// query list, then the block's own queries (causally masked), 32 queries per step and wave.
 //
 // The paper's kernel adds each block's contribution to dQ with atomic additions into a
 // high-precision buffer.  Here the contribution of (query t, kept block e, part c) is written

@@ -3,10 +3,11 @@
 // dense tiles).  The query-tile kernel of attn_fwd_mfma.hip needs a 256-query tile to meet a key
 // block with many of its rows; with few kept blocks out of very many (long sequences) a tile
 // meets a block with one or two rows and the work per (query, block) pair explodes.  Here a
-// workgroup owns up to 128 (d = 64) or 64 (d = 128) keys of one key block -- their K and V MFMA operands stay in
-// registers for the whole walk -- and walks the list of ALL queries that kept the block (then
-// the block's own queries, causally masked), 32 queries per step and wave: the tiles are dense
-// whatever the sequence length, and nothing but the gathered query rows is read in the loop.
+// workgroup owns up to 128 (d = 64) or 64 (d = 128) keys of one key block -- their MFMA operands
+// stay on chip for the whole walk, K in LDS and V^T in registers -- and walks the list of ALL
+// queries that kept the block (then the block's own queries, causally masked), 32 queries per
+// step and wave: the tiles are dense whatever the sequence length, and nothing but the gathered
+// query rows and their rows of kept blocks is read in the loop.
 //
 // A query's softmax spans several key blocks, i.e. several workgroups.  As in the paper's
 // forward each (query, block) pair therefore produces a partial result -- the local softmax

@@ -67,6 +67,27 @@ def test_routes_and_workspace(lib):
     assert a > 0 and b > 0 and c >= 4 * 2 * 1024
 
 
+@pytest.mark.parametrize("kw,key_major", [
+    (dict(heads=16, seqlen=32768, block=32, topk=64), False),                # headline shape: many kept blocks
+    (dict(batch=2, heads=16, seqlen=16384, block=64, topk=32), False),       # skewed-routing shape
+    (dict(heads=16, seqlen=8192, block=128, topk=8), True),                  # few kept blocks of many keys
+    (dict(batch=2, heads=16, seqlen=524288, block=128, topk=8), True),       # the long end of the latency sweep
+    (dict(heads=16, seqlen=131072, head_dim=128, block=64, topk=32, conv_width=4), True),
+    (dict(heads=16, seqlen=16384, block=128, topk=64), False),               # dense routing: tiles
+    (dict(heads=16, seqlen=8192, block=128, topk=0), False),                 # own block only
+])
+def test_default_cut_of_the_attention(kw, key_major):
+    """With neither flag the library sizes (and runs) the forward and backward for the cut it
+    estimates to be cheaper; seen from here through the workspace sizes, which differ."""
+    kw = dict(dict(dtype=binding.BF16), **kw)
+    forced = {f: moba.workspace_bytes(_shape(flags=f, **kw))[1:] for f in (binding.FLAG_KEY_MAJOR,
+                                                                          binding.FLAG_QUERY_TILES)}
+    picked = moba.workspace_bytes(_shape(**kw))[1:]
+    if kw["topk"] > 0:
+        assert forced[binding.FLAG_KEY_MAJOR] != forced[binding.FLAG_QUERY_TILES]
+    assert picked == forced[binding.FLAG_KEY_MAJOR if key_major else binding.FLAG_QUERY_TILES]
+
+
 @pytest.mark.parametrize("kw,status", [
     (dict(batch=0), -1), (dict(heads=-1), -1), (dict(seqlen=0), -1), (dict(block=0), -1),
     (dict(seqlen=1000), -1),            # not a multiple of the block
