@@ -68,7 +68,7 @@ template <int D, bool WIDE>
 __global__ __launch_bounds__(DkvCfg<D>::NT) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1)))
 void dkdv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    const bf16_t* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ Dv,
+    const bf16_t* __restrict__ dO, const float2* __restrict__ ld,
     const int32_t* __restrict__ off, const int32_t* __restrict__ ql, bf16_t* __restrict__ dK,
     bf16_t* __restrict__ dV, int N, int B, int n, float scale, int64_t R, int groups_per_slice, int bhk,
     int G)
@@ -162,9 +162,9 @@ void dkdv_mfma_kernel(
             gr[i] = *reinterpret_cast<const u32x4_t*>(Gg + o);
         }
         const bool live = decltype(inside)::value || a0 + (lane & 31) < total;
-        const float l = lse[sbase + tl], dd = Dv[sbase + tl];
-        lv = live ? l * kLog2e : INFINITY;
-        dv = live ? -dd : 0.f;
+        const float2 x = ld[sbase + tl];                  // (lse log2 e, -D) of the row
+        lv = live ? x.x : INFINITY;
+        dv = live ? x.y : 0.f;
     };
     const int stride = 32 * C::NW;
     int tN[C::NI], tlN;
@@ -357,7 +357,7 @@ void dkdv_mfma_kernel(
 
 template <int D>
 static hipError_t dkdv_launch(const Dims& s, const void* Q, const void* K, const void* V,
-                              const void* dO, const float* lse, const float* Dv, const int32_t* off,
+                              const void* dO, const float2* ld, const int32_t* off,
                               const int32_t* ql, void* dK, void* dV, hipStream_t st)
 {
     using C = DkvCfg<D>;
@@ -375,22 +375,22 @@ static hipError_t dkdv_launch(const Dims& s, const void* Q, const void* K, const
     if (wide)
         hipLaunchKernelGGL((dkdv_mfma_kernel<D, true>), dim3((unsigned)schedule_grid(s.bhk, units)), dim3(C::NT),
                            lds, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO,
-                           lse, Dv, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
+                           ld, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
                            s.bhk, s.G);
     else
         hipLaunchKernelGGL((dkdv_mfma_kernel<D, false>), dim3((unsigned)schedule_grid(s.bhk, units)), dim3(C::NT),
                            lds, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO,
-                           lse, Dv, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
+                           ld, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
                            s.bhk, s.G);
     return hipGetLastError();
 }
 
 hipError_t launch_dkdv_mfma(const Dims& s, const void* Q, const void* K, const void* V,
-                            const void* dO, const float* lse, const float* Dv, const int32_t* off,
+                            const void* dO, const float2* ld, const int32_t* off,
                             const int32_t* ql, void* dK, void* dV, hipStream_t st)
 {
-    return s.D == 64 ? dkdv_launch<64>(s, Q, K, V, dO, lse, Dv, off, ql, dK, dV, st)
-                     : dkdv_launch<128>(s, Q, K, V, dO, lse, Dv, off, ql, dK, dV, st);
+    return s.D == 64 ? dkdv_launch<64>(s, Q, K, V, dO, ld, off, ql, dK, dV, st)
+                     : dkdv_launch<128>(s, Q, K, V, dO, ld, off, ql, dK, dV, st);
 }
 
 }  // namespace moba

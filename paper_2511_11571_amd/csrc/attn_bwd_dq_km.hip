@@ -43,8 +43,8 @@ struct DqKmCfg {
 template <int D, int NG, int KC>
 __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO, const bf16_t* __restrict__ K,
-    const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kt, const float* __restrict__ lse,
-    const float* __restrict__ Dv, const int32_t* __restrict__ idx, const int32_t* __restrict__ off,
+    const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kt, const float2* __restrict__ ld,
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ off,
     const int32_t* __restrict__ ql, bf16_t* __restrict__ PdQ, int N, int B, int n, int k, int nsub,
     float scale, int64_t R, int bh, int G)
 {
@@ -73,8 +73,7 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     const int total = nlist + (B - own_first);
     const char* Qg = reinterpret_cast<const char*>(Q + sbase * D);
     const char* Gg = reinterpret_cast<const char*>(dO + sbase * D);
-    const float* lses = lse + sbase;
-    const float* Dvs = Dv + sbase;
+    const float2* ldq = ld + sbase;                         // per query (lse log2 e, -D)
     const uint32_t vlane = (uint32_t)lane * 16u;
 
     // The part's K and V rows go to LDS in MFMA operand order -- the 16 bytes lane (m, g) feeds as
@@ -139,9 +138,9 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
 #pragma unroll
             for (int cc = 0; cc < KC; ++cc)
                 ev[i][cc] = isrc[(int64_t)t[i] * k + min(lcol + C::CPR * cc, klast)];
-        const float l = lses[tl] * kLog2e;
-        lv = a0 + (lane & 31) < total ? l : INFINITY;
-        dv = -Dvs[tl];
+        const float2 x = ldq[tl];
+        lv = a0 + (lane & 31) < total ? x.x : INFINITY;
+        dv = x.y;
     };
     // The rows of the next step are in flight while one step is worked on; the row ids of the
     // step after that (tN, tlN) are loaded before that gather, so that waiting for them (loads
@@ -310,7 +309,7 @@ size_t backward_km_ws_bytes(const Dims& s)
 
 template <int D, int NG, int KC>
 static hipError_t dq_launch3(const Dims& s, const void* Q, const void* dO, const void* K, const void* V,
-                             const void* Kt, const float* lse, const float* Dv, const int32_t* idx,
+                             const void* Kt, const float2* ld, const int32_t* idx,
                              const int32_t* off, const int32_t* ql, bf16_t* PdQ, void* dQ, hipStream_t st)
 {
     using C = DqKmCfg<D>;
@@ -322,7 +321,7 @@ static hipError_t dq_launch3(const Dims& s, const void* Q, const void* dO, const
         ProfileScope timing(MOBA_PROFILE_DQ, st);
         hipLaunchKernelGGL((dq_km_kernel<D, NG, KC>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
                            dim3(C::NT), C::lds(NG), st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)K,
-                           (const bf16_t*)V, (const bf16_t*)Kt, lse, Dv, idx, off, ql, PdQ, s.N, s.B, s.n,
+                           (const bf16_t*)V, (const bf16_t*)Kt, ld, idx, off, ql, PdQ, s.N, s.B, s.n,
                            s.k, nsub, s.scale, s.R, s.bh, s.G);
     }
     const int64_t rows = (int64_t)s.bh * s.N;
@@ -354,22 +353,21 @@ static hipError_t dq_launch(const Dims& s, A... a)
 }
 
 hipError_t launch_dq_km(const Dims& s, const void* Q, const void* K, const void* V, const void* dO,
-                        const float* lse, const int32_t* idx, const int32_t* off, const int32_t* ql,
+                        const float2* ld, const int32_t* idx, const int32_t* off, const int32_t* ql,
                         void* dQ, void* ws, hipStream_t st)
 {
     if (s.bh == 0 || s.N == 0) return hipSuccess;
     if (!key_major_shape(s)) return hipErrorInvalidValue;
     const size_t tensor = a256(sizeof(bf16_t) * (size_t)s.bhk * s.N * s.D);
     char* p = static_cast<char*>(ws);
-    const float* Dv = reinterpret_cast<const float*>(p);
-    p += a256(sizeof(float) * (size_t)s.bh * s.N);
+    p += a256(sizeof(float) * (size_t)s.bh * s.N);         // D (not read here)
     void* Kt = p;
     p += tensor;
     bf16_t* PdQ = reinterpret_cast<bf16_t*>(p);
     hipError_t e = launch_slot_major_copy(kv_view(s), K, Kt, nullptr, st);
     if (e != hipSuccess) return e;
-    return s.D == 64 ? dq_launch<64>(s, Q, dO, K, V, Kt, lse, Dv, idx, off, ql, PdQ, dQ, st)
-                     : dq_launch<128>(s, Q, dO, K, V, Kt, lse, Dv, idx, off, ql, PdQ, dQ, st);
+    return s.D == 64 ? dq_launch<64>(s, Q, dO, K, V, Kt, ld, idx, off, ql, PdQ, dQ, st)
+                     : dq_launch<128>(s, Q, dO, K, V, Kt, ld, idx, off, ql, PdQ, dQ, st);
 }
 
 }  // namespace moba

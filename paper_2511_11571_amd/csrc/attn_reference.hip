@@ -121,10 +121,14 @@ __global__ __launch_bounds__(256) void forward_reference_kernel(
 }
 
 // ---------------------------------------------------------------- D = rowsum(dO o O)
+// packed (may be null): per row (lse log2 e, -D), the two numbers the gathering backward kernels
+// need of a query, side by side -- one 8-byte access per gathered row instead of two
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rowdot_kernel(const T* __restrict__ dO,
                                                      const T* __restrict__ O,
-                                                     float* __restrict__ Dv, int64_t total_rows)
+                                                     float* __restrict__ Dv, int64_t total_rows,
+                                                     const float* __restrict__ lse,
+                                                     float2* __restrict__ packed)
 {
     constexpr int G = D / 8;
     const int64_t row = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
@@ -139,7 +143,10 @@ __global__ __launch_bounds__(256) void rowdot_kernel(const T* __restrict__ dO,
     }
 #pragma unroll
     for (int o = G / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if (row < total_rows && part == 0) Dv[row] = acc;
+    if (row < total_rows && part == 0) {
+        Dv[row] = acc;
+        if (packed) packed[row] = make_float2(lse[row] * 1.4426950408889634f, -acc);
+    }
 }
 
 // ---------------------------------------------------------------- dQ
@@ -290,14 +297,14 @@ template <typename T, int D>
 static hipError_t bwd_t(const Dims& s, const void* Q, const void* K, const void* V, const void* O,
                         const float* lse, const void* dO, const int32_t* idx, const int32_t* off,
                         const int32_t* ql, void* dQ, void* dK, void* dV, float* Dvec, uint32_t parts,
-                        hipStream_t st)
+                        float2* packed, hipStream_t st)
 {
     const int64_t rows = (int64_t)s.bh * s.N;
     if (rows == 0) return hipSuccess;
     constexpr int RPB = 256 / (D / 8);
     if (parts & MOBA_BWD_PREPROCESS)
     hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0,
-                       st, (const T*)dO, (const T*)O, Dvec, rows);
+                       st, (const T*)dO, (const T*)O, Dvec, rows, lse, packed);
     const size_t lds = sizeof(float) * 4 * (2 * D + 2 * kWave) + sizeof(int32_t) * 4 * (size_t)s.k;
     if (parts & MOBA_BWD_DQ)
     hipLaunchKernelGGL((dq_reference_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)), dim3(256), lds,
@@ -324,14 +331,14 @@ hipError_t launch_backward_reference(const Dims& s, const void* Q, const void* K
                                      const void* O, const float* lse, const void* dO,
                                      const int32_t* idx, const int32_t* off, const int32_t* ql,
                                      void* dQ, void* dK, void* dV, float* Dvec, uint32_t parts,
-                                     hipStream_t st)
+                                     float2* packed, hipStream_t st)
 {
     if (s.dtype == MOBA_BF16)
         return s.D == 64
-                   ? bwd_t<bf16_t, 64>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, st)
-                   : bwd_t<bf16_t, 128>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, st);
-    return s.D == 64 ? bwd_t<float, 64>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, st)
-                     : bwd_t<float, 128>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, st);
+                   ? bwd_t<bf16_t, 64>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, packed, st)
+                   : bwd_t<bf16_t, 128>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, packed, st);
+    return s.D == 64 ? bwd_t<float, 64>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, packed, st)
+                     : bwd_t<float, 128>(s, Q, K, V, O, lse, dO, idx, off, ql, dQ, dK, dV, Dvec, parts, packed, st);
 }
 
 }  // namespace moba

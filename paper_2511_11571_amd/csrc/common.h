@@ -201,7 +201,7 @@ hipError_t launch_backward_reference(const Dims& s, const void* Q, const void* K
                                      const void* O, const float* lse, const void* dO,
                                      const int32_t* idx, const int32_t* off, const int32_t* ql,
                                      void* dQ, void* dK, void* dV, float* Dvec, uint32_t parts,
-                                     hipStream_t st);
+                                     float2* packed, hipStream_t st);
 
 
 }  // namespace moba

@@ -210,8 +210,9 @@ hipError_t launch_dq_mfma(const Dims& s, const void* Q, const void* K, const voi
                           const float* lse, const int32_t* idx, const int32_t* off, const int32_t* ql,
                           void* dQ, void* ws, hipStream_t st);
 
+// ld: per query (lse log2 e, -D), as the D kernel packs them
 hipError_t launch_dkdv_mfma(const Dims& s, const void* Q, const void* K, const void* V,
-                            const void* dO, const float* lse, const float* Dv, const int32_t* off,
+                            const void* dO, const float2* ld, const int32_t* off,
                             const int32_t* ql, void* dK, void* dV, hipStream_t st);
 
 size_t topk_mfma_ws_bytes(const Dims& s);
@@ -280,7 +281,7 @@ inline bool key_major_path(const Dims& s)
 size_t forward_km_ws_bytes(const Dims& s);
 size_t backward_km_ws_bytes(const Dims& s);
 hipError_t launch_dq_km(const Dims& s, const void* Q, const void* K, const void* V, const void* dO,
-                        const float* lse, const int32_t* idx, const int32_t* off, const int32_t* ql,
+                        const float2* ld, const int32_t* idx, const int32_t* off, const int32_t* ql,
                         void* dQ, void* ws, hipStream_t st);
 hipError_t launch_forward_km(const Dims& s, const void* Q, const void* K, const void* V, void* ws,
                              const int32_t* idx, const int32_t* off, const int32_t* ql, void* O,

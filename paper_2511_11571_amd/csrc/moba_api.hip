@@ -81,10 +81,16 @@ size_t fwd_ws_bytes(const Dims& d)
     if (!mfma_path(d)) return 256;
     return align256(key_major_path(d) ? forward_km_ws_bytes(d) : forward_mfma_ws_bytes(d));
 }
+// backward: D first in every layout; on the MFMA path the per-query pairs (lse log2 e, -D) of
+// the gathering kernels come last
+size_t bwd_packed_offset(const Dims& d)
+{
+    return align256(key_major_path(d) ? backward_km_ws_bytes(d) : backward_mfma_ws_bytes(d));
+}
 size_t bwd_ws_bytes(const Dims& d)
 {
     if (!mfma_path(d)) return align256(sizeof(float) * (size_t)d.bh * d.N);
-    return align256(key_major_path(d) ? backward_km_ws_bytes(d) : backward_mfma_ws_bytes(d));
+    return bwd_packed_offset(d) + align256(sizeof(float2) * (size_t)d.bh * d.N);
 }
 
 }  // namespace
@@ -309,26 +315,27 @@ int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_ef
     uint32_t plain = parts;
     if (mfma_path(d)) {
         // D first (plain row-dot kernel), then the MFMA kernels that exist; the rest stays plain
+        float2* ld = reinterpret_cast<float2*>(static_cast<char*>(ws) + bwd_packed_offset(d));
         if (parts & MOBA_BWD_PREPROCESS) {
             hipError_t e = launch_backward_reference(d, Q, K_eff, V, O, lse, dO, topk_idx, blk_off, blk_q,
-                                                     dQ, dK, dV, (float*)ws, MOBA_BWD_PREPROCESS, hs);
+                                                     dQ, dK, dV, (float*)ws, MOBA_BWD_PREPROCESS, ld, hs);
             if (e != hipSuccess) return hip_status(e);
         }
         if (parts & MOBA_BWD_DQ) {
             hipError_t e = key_major_path(d)
-                ? launch_dq_km(d, Q, K_eff, V, dO, lse, topk_idx, blk_off, blk_q, dQ, ws, hs)
+                ? launch_dq_km(d, Q, K_eff, V, dO, ld, topk_idx, blk_off, blk_q, dQ, ws, hs)
                 : launch_dq_mfma(d, Q, K_eff, V, dO, lse, topk_idx, blk_off, blk_q, dQ, ws, hs);
             if (e != hipSuccess) return hip_status(e);
         }
         if (parts & MOBA_BWD_DKDV) {
-            hipError_t e = launch_dkdv_mfma(d, Q, K_eff, V, dO, lse, (const float*)ws, blk_off, blk_q,
+            hipError_t e = launch_dkdv_mfma(d, Q, K_eff, V, dO, ld, blk_off, blk_q,
                                             dK, dV, hs);
             if (e != hipSuccess) return hip_status(e);
         }
         return MOBA_OK;
     }
     return hip_status(launch_backward_reference(d, Q, K_eff, V, O, lse, dO, topk_idx, blk_off, blk_q,
-                                                dQ, dK, dV, (float*)ws, plain, hs));
+                                                dQ, dK, dV, (float*)ws, plain, nullptr, hs));
 }
 
 int moba_backward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
