@@ -40,8 +40,8 @@ MEASURED_TRAFFIC = {      # profiles/config3_hbm_traffic.txt: 2.0 * FETCH_SIZE +
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5")
     ap.add_argument("--shape", default="",
                     help="instead of --config: batch,heads,N,d,B,k[,fwd] (bf16, no conv), e.g. the "

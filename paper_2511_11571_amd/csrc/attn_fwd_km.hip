@@ -4,7 +4,7 @@
 // block with many of its rows; with few kept blocks out of very many (long sequences) a tile
 // meets a block with one or two rows and the work per (query, block) pair explodes.  Here a
 // workgroup owns up to 128 (d = 64) or 64 (d = 128) keys of one key block -- their MFMA operands
-// stay on chip for the whole walk, K in LDS and V^T in registers -- and walks the list of ALL
+// stay on chip for the whole walk, K in LDS and V^T in registers (d = 128: in LDS) -- and walks the list of ALL
 // queries that kept the block (then the block's own queries, causally masked), 32 queries per
 // step and wave: the tiles are dense whatever the sequence length, and nothing but the gathered
 // query rows and their rows of kept blocks is read in the loop.
@@ -36,13 +36,16 @@ struct KmCfg {
     static constexpr int RPI = kWave / CPR;            // rows per gather instruction
     static constexpr int NI = 32 / RPI;                // gather instructions per step
     static constexpr size_t PARK = (size_t)NW * 32 * SB;                 // the waves' parked rows
-    static constexpr size_t lds(int ng) { return PARK + (size_t)ng * 64 * D; }   // + the part's keys
+    // d = 128: V^T goes to LDS as well -- in registers it leaves room for one wave per SIMD only
+    static constexpr bool VLDS = D == 128;
+    static constexpr size_t lds(int ng) { return PARK + (size_t)(VLDS ? 2 : 1) * ng * 64 * D; }   // + the part's keys (and values)
 };
 
 // NG: 32-key groups per workgroup; KC: a query's row of kept blocks is searched CPR entries at a
 // time, KC times (k <= KC * CPR)
 template <int D, int NG, int KC>
-__global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
+__global__ __launch_bounds__(KmCfg<D>::NT) __attribute__((amdgpu_waves_per_eu(D == 128 ? 2 : 1)))
+void fwd_km_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ off, const int32_t* __restrict__ ql,
     bf16_t* __restrict__ PO, float* __restrict__ Pml, int N, int B, int n, int k, int nsub,
@@ -85,14 +88,21 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
                 *reinterpret_cast<const kmvec4_t*>(Kg + (size_t)ch * 16);
         }
     }
-    Frag va[NG][C::MT];
+    Frag va[C::VLDS ? 1 : NG][C::MT];
+    unsigned char* sV = sK + (size_t)NG * 64 * D;
     {
         const char* Vtg = reinterpret_cast<const char*>(Vt + (kvbase + own0) * D);
+        if constexpr (C::VLDS) {
+            for (int ch = tid; ch < NG * 4 * D; ch += C::NT)          // NG * 64 * D bytes, as they are
+                *reinterpret_cast<kmvec4_t*>(sV + (size_t)ch * 16) =
+                    *reinterpret_cast<const kmvec4_t*>(Vtg + (size_t)ch * 16);
+        } else {
 #pragma unroll
-        for (int gi = 0; gi < NG; ++gi)
+            for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
-            for (int mt = 0; mt < C::MT; ++mt)
-                va[gi][mt].q = *reinterpret_cast<const uint4*>(Vtg + gi * (64 * D) + vlane + mt * 1024);
+                for (int mt = 0; mt < C::MT; ++mt)
+                    va[gi][mt].q = *reinterpret_cast<const uint4*>(Vtg + gi * (64 * D) + vlane + mt * 1024);
+        }
     }
     __syncthreads();
 
@@ -226,7 +236,11 @@ __global__ __launch_bounds__(KmCfg<D>::NT) void fwd_km_kernel(
 #pragma unroll
                 for (int e = 0; e < 4; ++e) pb.u[e] = pack2(x[gi][2 * e], x[gi][2 * e + 1]);
 #pragma unroll
-                for (int mt = 0; mt < C::MT; ++mt) o[mt] = mfma16(va[gi][mt], pb, o[mt]);
+                for (int mt = 0; mt < C::MT; ++mt) {
+                    if constexpr (C::VLDS)
+                        va[0][mt].q = *reinterpret_cast<const uint4*>(sV + gi * (64 * D) + vlane + mt * 1024);
+                    o[mt] = mfma16(va[C::VLDS ? 0 : gi][mt], pb, o[mt]);
+                }
             }
             l += __shfl_xor(l, 16, kWave);
             l += __shfl_xor(l, 32, kWave);
