@@ -113,8 +113,9 @@ __device__ __forceinline__ int lanes_below(uint64_t mask)
 __device__ __forceinline__ uint32_t order_key(float s)
 {
     s += 0.0f;
-    uint32_t b = __float_as_uint(s);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    const uint32_t b = __float_as_uint(s);
+    // negative: all bits flipped; else: sign bit set
+    return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
 }
 
 // ---- workgroup -> (slice, position) ------------------------------------------------------
