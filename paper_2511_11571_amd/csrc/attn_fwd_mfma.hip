@@ -68,6 +68,7 @@ __global__ __launch_bounds__(256) void absmax_kernel(const bf16_t* __restrict__ 
     const int s = blockIdx.y, part = threadIdx.x % G, rr = threadIdx.x / G;
     const int r0 = blockIdx.x * rows_per_wg, r1 = min(N, r0 + rows_per_wg);
     float mx[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
     for (int r = r0 + rr; r < r1; r += 256 / G) {
         float v[8];
         Vec8<bf16_t>::load(X + ((int64_t)s * N + r) * D + part * 8, v);
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(256) void slot_major_copy_kernel(const bf16_t* __re
 hipError_t launch_absmax(const Dims& s, const void* X, uint32_t* vmax, hipStream_t st)
 {
     if (s.N == 0) return hipSuccess;
-    const int cnt = s.bh * s.D, rows_per_wg = 1024;
+    const int cnt = s.bh * s.D, rows_per_wg = 256;         // enough workgroups to keep all of HBM busy
     hipLaunchKernelGGL(zero_words_kernel, dim3((cnt + 255) / 256), dim3(256), 0, st, vmax, cnt);
     dim3 grid((s.N + rows_per_wg - 1) / rows_per_wg, s.bh);
     if (s.D == 64)
