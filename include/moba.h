@@ -23,7 +23,8 @@
  *   - Return value: MOBA_OK (0) or a negative moba_status.  No exceptions, no abort.
  *   - Supported: head_dim 64 or 128; seqlen a multiple of block; block >= 1;
  *     topk >= 0 (topk >= n-1 is full causal attention); conv_width 0 (none) or 1..8;
- *     at most 4096 key blocks per head for moba_topk.
+ *     at most 4096 key blocks per head for moba_topk; seqlen <= 2^24; batch * heads
+ *     <= 65535; R < 2^31.
  *   - R below is the number of (query, kept past block) pairs of one [N, d]
  *     slice, R = B * sum_{c<n} min(c, topk); it depends on the shape only
  *     (moba_routes_per_slice).
@@ -41,7 +42,7 @@ extern "C" {
 typedef enum moba_status {
     MOBA_OK = 0,
     MOBA_EINVAL = -1,       /* null pointer, non-positive size, N % B != 0, topk < 0, bad dtype */
-    MOBA_EUNSUPPORTED = -2, /* legal but not built: head_dim, conv_width, too many blocks      */
+    MOBA_EUNSUPPORTED = -2, /* legal but not built: head_dim, conv_width, sizes over the limits */
     MOBA_EWORKSPACE = -3,   /* workspace pointer null or smaller than moba_workspace_bytes    */
     MOBA_EHIP = -4          /* a HIP launch failed; see moba_last_hip_error                   */
 } moba_status;

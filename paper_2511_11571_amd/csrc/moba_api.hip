@@ -20,6 +20,7 @@ int hip_status(hipError_t e)
 
 constexpr int kMaxBlocks = 4096;   // key blocks per head the scoring kernels keep in LDS
 constexpr int kMaxTopk = 4096;
+constexpr int kMaxSeqlen = 1 << 24;       // the gathering kernels hold a row's byte offset inside its slice in 32 bits
 
 // Fills `d` from `shape`; returns MOBA_OK or the status to hand back.
 int make_dims(const moba_shape* sh, Dims& d, bool ragged_ok = false)
@@ -36,6 +37,7 @@ int make_dims(const moba_shape* sh, Dims& d, bool ragged_ok = false)
     if (sh->head_dim != 64 && sh->head_dim != 128) return MOBA_EUNSUPPORTED;
     if (sh->conv_width > 8) return MOBA_EUNSUPPORTED;
     if (sh->topk > kMaxTopk) return MOBA_EUNSUPPORTED;
+    if (sh->seqlen > kMaxSeqlen) return MOBA_EUNSUPPORTED;
     if ((int64_t)sh->batch * sh->heads > 65535) return MOBA_EUNSUPPORTED;
     if (sh->kv_heads < 0 || (sh->kv_heads > 0 && sh->heads % sh->kv_heads != 0)) return MOBA_EINVAL;
     d.bh = sh->batch * sh->heads;
