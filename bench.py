@@ -318,6 +318,13 @@ def main():
         roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "bytes_per_launch": amount}
     roofline["ms_per_launch"] = dom_ms
+    # every timed attention kernel against the same peak (algorithmic flop of its products / launch time)
+    kernel_frac = {}
+    if mfma:
+        for kname, kms in timed.items():
+            if work[kname][0] == "flop" and kms > 0:
+                tf = work[kname][1] / (kms * 1e-3) / 1e12
+                kernel_frac[kname] = {"tflops": tf, "frac_of_mfma_peak": tf / PEAK_BF16_TFLOPS}
     roofline["traffic"] = MEASURED_TRAFFIC.get((a.config, dom)) if not a.reference_kernels else None
     # HBM-bound stages, for the record: algorithmic bytes / measured time
     cent_bytes = w.bh * (w.N * w.d * es * (2 if w.conv_width else 1) + w.n * w.d * 4)
@@ -341,6 +348,7 @@ def main():
         "stage_ms": stage_ms,
         "kernel_ms": kernel_ms,
         "roofline": roofline,
+        "attention_kernels": kernel_frac,
         "hbm_stages": hbm,
     }
     if w.conv_width:
