@@ -230,7 +230,7 @@ def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (every (batch, head) slice is independent; "
-              "multi-GPU sharding is described in DESIGN.md but not built). Use --gpus 1.",
+              "sharding them over several GPUs is designed, not built). Use --gpus 1.",
               file=sys.stderr)
         sys.exit(2)
     import torch
