@@ -40,6 +40,10 @@ MEASURED_TRAFFIC = {      # profiles/config3_hbm_traffic.txt: 2.0 * FETCH_SIZE +
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--rotate-inputs", type=int, default=1, metavar="SETS",
+                    help="cycle through SETS copies of the input tensors, one per step, so that a step "
+                         "does not find its inputs in the 256 MB Infinity Cache (for the HBM-bound "
+                         "stage rates; default 1: the same tensors every step)")
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5")
@@ -132,6 +136,8 @@ def measure(w, a, moba, binding, workloads, torch):
     """Times a.steps passes of the whole path over workload w (inputs resident in HBM)."""
     t = workloads.generate(w)
     d = {k: (v.cuda() if v is not None else None) for k, v in t.items()}
+    sets = [d] + [{k: (v.clone() if v is not None else None) for k, v in d.items()}
+                  for _ in range(max(a.rotate_inputs, 1) - 1)]
     flags = binding.FLAG_REFERENCE_KERNELS if a.reference_kernels else 0
     flags |= {"auto": 0, "tiles": binding.FLAG_QUERY_TILES, "keymajor": binding.FLAG_KEY_MAJOR}[a.attention]
     sh = moba.Shape(w.batch, w.heads, w.N, w.d, w.B, w.k, w.conv_width,
@@ -150,7 +156,7 @@ def measure(w, a, moba, binding, workloads, torch):
     if not w.backward:
         stages = stages[:3]
 
-    def step(events=None):
+    def step(events=None, d=d):
         def mark(i):
             if events is not None:
                 events[i].record()
@@ -167,8 +173,8 @@ def measure(w, a, moba, binding, workloads, torch):
                               out=grads, parts=part)
                 mark(4 + i)
 
-    for _ in range(a.warmup):
-        step()
+    for s in range(a.warmup):
+        step(None, sets[s % len(sets)])
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)]
           for _ in range(a.steps)]
@@ -176,7 +182,7 @@ def measure(w, a, moba, binding, workloads, torch):
     moba.profile_begin()          # HIP events around every main kernel, on its launch stream
     t0 = time.perf_counter()
     for s in range(a.steps):
-        step(ev[s])
+        step(ev[s], sets[s % len(sets)])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     kernel_ms = {name: (tot / max(n, 1)) for name, (tot, n) in moba.profile_end().items() if n}
