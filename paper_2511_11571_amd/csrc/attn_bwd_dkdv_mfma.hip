@@ -71,7 +71,7 @@ void dkdv_mfma_kernel(
     const bf16_t* __restrict__ dO, const float2* __restrict__ ld,
     const int32_t* __restrict__ off, const int32_t* __restrict__ ql, bf16_t* __restrict__ dK,
     bf16_t* __restrict__ dV, int N, int B, int n, float scale, int64_t R, int groups_per_slice, int bhk,
-    int G)
+    int G, float* __restrict__ part)
 {
     using C = DkvCfg<D>;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -81,8 +81,17 @@ void dkdv_mfma_kernel(
     float* red = reinterpret_cast<float*>(WIDE ? smem + (size_t)wave * 2 * 32 * C::RSTRIDE * 4
                                                : smem + C::NW * SLOT);        // [2][32][RSTRIDE]
 
-    int skv, unit;                                          // key/value slice; 32-key group or 128-key part
-    if (!schedule(blockIdx.x, bhk, groups_per_slice, skv, unit)) return;
+    // part == nullptr: a workgroup per key/value slice and unit, the G query heads that share the
+    // slice one after the other.  Otherwise (G > 1) a workgroup per QUERY head and unit, which
+    // leaves its sums as fp32 in part[dK | dV][query slice][N][D] for dkdv_heads_kernel to add up:
+    // the workgroups of an XCD then gather from one head's Q and dO at a time, as without sharing
+    // (walking all G heads in every workgroup, the L2 hit rate of the gathers fell from 80 % to
+    // 15 % with 16 heads on one key/value head).
+    const int slices = part ? bhk * G : bhk;
+    int slice, unit;                                        // slice; 32-key group or 128-key part
+    if (!schedule(blockIdx.x, slices, groups_per_slice, slice, unit)) return;
+    const int skv = part ? slice / G : slice;               // key/value slice
+    const int s_first = part ? slice : skv * G, s_last = part ? slice + 1 : (skv + 1) * G;
     const int kap = WIDE ? 4 * unit + wave : unit;          // this wave's 32-key group inside the slice
     const int NG = B / 32;
     const int j = kap / NG;
@@ -114,7 +123,7 @@ void dkdv_mfma_kernel(
     // The G query heads that share this key/value head (grouped-query attention, Appendix C, last
     // paragraph), one after the other: each has its own list for the block; dK and dV add up in
     // the same accumulators.
-    for (int s = skv * G; s < (skv + 1) * G; ++s) {
+    for (int s = s_first; s < s_last; ++s) {
     const int64_t sbase = (int64_t)s * N;
     const int32_t* os = off + (int64_t)s * (n + 1);
     const int32_t* qs = ql + (int64_t)s * R;
@@ -317,8 +326,12 @@ void dkdv_mfma_kernel(
             float v[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = src[e] * mul;
-            bf16_t* dst = (which == 0 ? dK : dV) + (kvbase + 32 * kap + key) * D + 8 * c;
-            Vec8<bf16_t>::store(dst, v);
+            if (part) {
+                Vec8<float>::store(part + (((int64_t)which * slices + slice) * N + 32 * kap + key) * D + 8 * c, v);
+            } else {
+                bf16_t* dst = (which == 0 ? dK : dV) + (kvbase + 32 * kap + key) * D + 8 * c;
+                Vec8<bf16_t>::store(dst, v);
+            }
         }
         return;
     }
@@ -350,15 +363,40 @@ void dkdv_mfma_kernel(
         float v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = src[e] * mul;
-        bf16_t* dst = (which == 0 ? dK : dV) + (kvbase + 32 * kap + key) * D + 8 * c;
-        Vec8<bf16_t>::store(dst, v);
+        if (part) {
+            Vec8<float>::store(part + (((int64_t)which * slices + slice) * N + 32 * kap + key) * D + 8 * c, v);
+        } else {
+            bf16_t* dst = (which == 0 ? dK : dV) + (kvbase + 32 * kap + key) * D + 8 * c;
+            Vec8<bf16_t>::store(dst, v);
+        }
     }
+}
+
+// dK, dV of a key/value head = the sums over the G query heads that share it, added in head order
+// (fixed: bit-reproducible); eight channels per thread
+__global__ __launch_bounds__(256) void dkdv_heads_kernel(const float* __restrict__ part,
+                                                         bf16_t* __restrict__ dK, bf16_t* __restrict__ dV,
+                                                         int64_t chunks_per_slice, int bhk, int G)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;     // (tensor, key/value slice, 8-channel chunk)
+    const int64_t per_tensor = chunks_per_slice * bhk;
+    if (i >= 2 * per_tensor) return;
+    const int which = (int)(i / per_tensor);
+    const int64_t r = i % per_tensor, skv = r / chunks_per_slice, ch = r % chunks_per_slice;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int gq = 0; gq < G; ++gq) {
+        float v[8];
+        Vec8<float>::load(part + ((((int64_t)which * bhk + skv) * G + gq) * chunks_per_slice + ch) * 8, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += v[e];
+    }
+    Vec8<bf16_t>::store((which == 0 ? dK : dV) + (skv * chunks_per_slice + ch) * 8, acc);
 }
 
 template <int D>
 static hipError_t dkdv_launch(const Dims& s, const void* Q, const void* K, const void* V,
                               const void* dO, const float2* ld, const int32_t* off,
-                              const int32_t* ql, void* dK, void* dV, hipStream_t st)
+                              const int32_t* ql, void* dK, void* dV, float* part, hipStream_t st)
 {
     using C = DkvCfg<D>;
     const int gps = s.N / 32;
@@ -371,26 +409,38 @@ static hipError_t dkdv_launch(const Dims& s, const void* Q, const void* K, const
                         : hipFuncSetAttribute((const void*)dkdv_mfma_kernel<D, false>,
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
+    const int slices = part ? s.bh : s.bhk;
     ProfileScope timing(MOBA_PROFILE_DKDV, st);
     if (wide)
-        hipLaunchKernelGGL((dkdv_mfma_kernel<D, true>), dim3((unsigned)schedule_grid(s.bhk, units)), dim3(C::NT),
+        hipLaunchKernelGGL((dkdv_mfma_kernel<D, true>), dim3((unsigned)schedule_grid(slices, units)), dim3(C::NT),
                            lds, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO,
                            ld, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
-                           s.bhk, s.G);
+                           s.bhk, s.G, part);
     else
-        hipLaunchKernelGGL((dkdv_mfma_kernel<D, false>), dim3((unsigned)schedule_grid(s.bhk, units)), dim3(C::NT),
+        hipLaunchKernelGGL((dkdv_mfma_kernel<D, false>), dim3((unsigned)schedule_grid(slices, units)), dim3(C::NT),
                            lds, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO,
                            ld, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
-                           s.bhk, s.G);
+                           s.bhk, s.G, part);
+    if (part) {
+        const int64_t cps = (int64_t)s.N * D / 8, total = 2 * cps * s.bhk;
+        hipLaunchKernelGGL(dkdv_heads_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, part,
+                           (bf16_t*)dK, (bf16_t*)dV, cps, s.bhk, s.G);
+    }
     return hipGetLastError();
+}
+
+size_t dkdv_heads_ws_bytes(const Dims& s)
+{
+    return s.G > 1 ? a256(2 * sizeof(float) * (size_t)s.bh * s.N * s.D) : 0;
 }
 
 hipError_t launch_dkdv_mfma(const Dims& s, const void* Q, const void* K, const void* V,
                             const void* dO, const float2* ld, const int32_t* off,
-                            const int32_t* ql, void* dK, void* dV, hipStream_t st)
+                            const int32_t* ql, void* dK, void* dV, float* part, hipStream_t st)
 {
-    return s.D == 64 ? dkdv_launch<64>(s, Q, K, V, dO, ld, off, ql, dK, dV, st)
-                     : dkdv_launch<128>(s, Q, K, V, dO, ld, off, ql, dK, dV, st);
+    if (s.G == 1) part = nullptr;
+    return s.D == 64 ? dkdv_launch<64>(s, Q, K, V, dO, ld, off, ql, dK, dV, part, st)
+                     : dkdv_launch<128>(s, Q, K, V, dO, ld, off, ql, dK, dV, part, st);
 }
 
 }  // namespace moba

@@ -210,10 +210,12 @@ hipError_t launch_dq_mfma(const Dims& s, const void* Q, const void* K, const voi
                           const float* lse, const int32_t* idx, const int32_t* off, const int32_t* ql,
                           void* dQ, void* ws, hipStream_t st);
 
-// ld: per query (lse log2 e, -D), as the D kernel packs them
+// ld: per query (lse log2 e, -D), as the D kernel packs them; part: dkdv_heads_ws_bytes() of
+// scratch for the per-query-head sums when key/value heads are shared (unused otherwise)
+size_t dkdv_heads_ws_bytes(const Dims& s);
 hipError_t launch_dkdv_mfma(const Dims& s, const void* Q, const void* K, const void* V,
                             const void* dO, const float2* ld, const int32_t* off,
-                            const int32_t* ql, void* dK, void* dV, hipStream_t st);
+                            const int32_t* ql, void* dK, void* dV, float* part, hipStream_t st);
 
 size_t topk_mfma_ws_bytes(const Dims& s);
 bool topk_mfma_supported(const Dims& s);

@@ -84,7 +84,8 @@ size_t fwd_ws_bytes(const Dims& d)
     return align256(key_major_path(d) ? forward_km_ws_bytes(d) : forward_mfma_ws_bytes(d));
 }
 // backward: D first in every layout; on the MFMA path the per-query pairs (lse log2 e, -D) of
-// the gathering kernels come last
+// the gathering kernels follow the layout, and with shared key/value heads the per-query-head sums
+// of dK and dV come last
 size_t bwd_packed_offset(const Dims& d)
 {
     return align256(key_major_path(d) ? backward_km_ws_bytes(d) : backward_mfma_ws_bytes(d));
@@ -92,7 +93,7 @@ size_t bwd_packed_offset(const Dims& d)
 size_t bwd_ws_bytes(const Dims& d)
 {
     if (!mfma_path(d)) return align256(sizeof(float) * (size_t)d.bh * d.N);
-    return bwd_packed_offset(d) + align256(sizeof(float2) * (size_t)d.bh * d.N);
+    return bwd_packed_offset(d) + align256(sizeof(float2) * (size_t)d.bh * d.N) + dkdv_heads_ws_bytes(d);
 }
 
 }  // namespace
@@ -330,8 +331,10 @@ int moba_backward_parts(const moba_shape* shape, const void* Q, const void* K_ef
             if (e != hipSuccess) return hip_status(e);
         }
         if (parts & MOBA_BWD_DKDV) {
+            float* part = reinterpret_cast<float*>(reinterpret_cast<char*>(ld) +
+                                                   align256(sizeof(float2) * (size_t)d.bh * d.N));
             hipError_t e = launch_dkdv_mfma(d, Q, K_eff, V, dO, ld, blk_off, blk_q,
-                                            dK, dV, hs);
+                                            dK, dV, part, hs);
             if (e != hipSuccess) return hip_status(e);
         }
         return MOBA_OK;
