@@ -66,7 +66,9 @@ __device__ __forceinline__ float key_score(uint32_t key, float none)
 // One wave's share (tiles tile_lo, tile_lo + step, ...) of a sweep over the centroid tiles of a
 // 64-query strip.  f(qt, sc, j0): sc[i] is the score of
 // query 16*qt + m16 against block j0 + i (j0 = 16*tile + 4*g).
-template <int D, typename F>
+// TOP = 2: the fp32-accurate score from all three terms; TOP = 0: the hi term alone, a third of the
+// loads and MFMAs, within about 1 % of the score (enough to say where to look first).
+template <int D, int TOP, typename F>
 __device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int tile_lo, int tile_hi,
                                             int step, const Frag (&qb)[4][D / 32], int lane, int g, F f)
 {
@@ -83,7 +85,7 @@ __device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int ti
     int jt = tile_lo;
     if (jt >= tile_hi) return;
 #pragma unroll
-    for (int term = 2; term >= 0; --term) load(jt, term);
+    for (int term = TOP; term >= 0; --term) load(jt, term);
     while (jt < tile_hi) {
         const int nx = jt + step, ld = nx < tile_hi ? nx : jt;
         // the four 16-query tiles are independent accumulation chains: issue them interleaved so
@@ -92,7 +94,7 @@ __device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int ti
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) sc[qt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int term = 2; term >= 0; --term) {         // smallest terms first
+        for (int term = TOP; term >= 0; --term) {       // smallest terms first
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -188,31 +190,32 @@ void topk_mfma_kernel(
     const int ntile_int = min(ntile, (t0 / B) / 16);
     auto sweep = [&](int tlo, int thi, auto f) {
         const int mid = min(max(ntile_int, tlo), thi);
-        sweep_tiles<D>(c3s, tlo + wave, mid, kTopkWaves, qb, lane, g,
-                       [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::false_type()); });
+        sweep_tiles<D, 2>(c3s, tlo + wave, mid, kTopkWaves, qb, lane, g,
+                          [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::false_type()); });
         // first tail tile of this wave: same parity as its interior tiles
         const int tail0 = mid + ((wave - (mid - tlo)) & (kTopkWaves - 1));
-        sweep_tiles<D>(c3s, tail0, thi, kTopkWaves, qb, lane, g,
-                       [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::true_type()); });
+        sweep_tiles<D, 2>(c3s, tail0, thi, kTopkWaves, qb, lane, g,
+                          [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::true_type()); });
     };
-    // every sm-th tile only (tiles 0, sm, 2 sm, ..., alternating between the waves)
+    // every sm-th tile only (tiles 0, sm, 2 sm, ..., alternating between the waves), scores from
+    // the hi term alone
     auto sweep_sample = [&](int sm, auto f) {
         const int step = kTopkWaves * sm;
         const int mid = min(ntile_int, ntile);
-        sweep_tiles<D>(c3s, sm * wave, mid, step, qb, lane, g,
-                       [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::false_type()); });
+        sweep_tiles<D, 0>(c3s, sm * wave, mid, step, qb, lane, g,
+                          [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::false_type()); });
         int tail0 = sm * wave;
         if (tail0 < mid) tail0 += (mid - tail0 + step - 1) / step * step;
-        sweep_tiles<D>(c3s, tail0, ntile, step, qb, lane, g,
-                       [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::true_type()); });
+        sweep_tiles<D, 0>(c3s, tail0, ntile, step, qb, lane, g,
+                          [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::true_type()); });
     };
 
-    // ---- where to look first: the largest key of every undecided query -- over all its blocks
-    // when there are few tiles, over every sm-th tile otherwise (a sweep costs as much as any
-    // other, and the search below does not depend on the guess being right).  The first interval
-    // of the search is 2^24 keys (two binades of the score), 64 bins of 2^18 keys: ending at the
-    // largest key if that is exact; otherwise reaching half a binade above the sampled one, and
-    // open at the top (its last bin also takes whatever lies above).
+    // ---- where to look first: about the largest key of every undecided query -- from hi-term
+    // scores, over all its blocks when there are few tiles, over every sm-th tile otherwise (the
+    // search below does not depend on the guess being right).  The first interval of the search
+    // is 2^24 keys (two binades of the score), 64 bins of 2^18 keys, reaching two bins (6 %) above
+    // the largest approximate key, half a binade above a sampled one, and open at the top (its
+    // last bin also takes whatever lies above).
     // (sampling pays with a small top-k; with top-k 64 of 1024 blocks it measured 10 % slower)
     const int sm = LISTS ? min(max(ntile / 8, 1), 8) : 1;
     if (__syncthreads_or(st_state[lane] == 0u)) {
@@ -235,10 +238,10 @@ void topk_mfma_kernel(
         __syncthreads();
         if (wave == 0 && st_state[lane] == 0u) {
             const uint32_t kmax = hist[lane * kHistStride];
-            uint32_t top = kmax == 0xffffffffu ? kmax : kmax + 1u;            // one past the largest key
-            if (sm > 1) top = (uint32_t)min((uint64_t)top + (1ull << 22), 0xffffffffull);
+            const uint64_t above = sm > 1 ? (1ull << 22) : (1ull << 19);
+            const uint32_t top = (uint32_t)min((uint64_t)kmax + 1u + above, 0xffffffffull);
             st_lo[lane] = top > (1u << 24) ? top - (1u << 24) : 0u;
-            st_hi[lane] = sm > 1 ? 0xffffffffu : top;
+            st_hi[lane] = 0xffffffffu;
             st_sh[lane] = 18u;
         }
     }
