@@ -127,9 +127,14 @@ int moba_key_conv_backward(const moba_shape* shape, const void* K, const float* 
  *   topk_idx  out  [b,h,N,topk] int32: kept past blocks of each query in ascending
  *                  block order, -1 in unused trailing slots
  *   blk_off   out  [b,h,n+1] int32: exclusive prefix sums of the per-block list lengths
- *   blk_q     out  [b,h,R] int32: for each key block the ids of the queries that kept
- *                  it, ascending (deterministic); block j's list is
- *                  blk_q[blk_off[j] .. blk_off[j+1])
+ *   blk_q     out  [b,h,R] int32: for each key block the queries that kept it,
+ *                  ascending (deterministic); block j's list is
+ *                  blk_q[blk_off[j] .. blk_off[j+1]).  Bits 0..23 of an entry are the
+ *                  query's position in the sequence.  Bits 24..31 are for the library's
+ *                  own use: where the shape and flags select the key-block-major
+ *                  attention kernels they hold the position of block j in that query's
+ *                  row of topk_idx, otherwise zero.  Lists are therefore built (here or
+ *                  by moba_build_lists) with the shape and flags they are used with.
  *   ws             at least topk_ws bytes from moba_workspace_bytes
  */
 int moba_topk(const moba_shape* shape, const void* Q, const float* centroids,

@@ -140,7 +140,7 @@ void dkdv_mfma_kernel(
     const int32_t* lsrc = nlist > 0 ? qs + lo : os;          // an empty list reads os[0] and ignores it
     const int llast = max(nlist - 1, 0);
     auto query_at = [&](int a) {
-        const int listed = lsrc[min(a, llast)];
+        const int listed = list_query(lsrc[min(a, llast)]);
         const int t = a < nlist ? listed : own0 + (a - nlist);
         return a >= total ? own0 : t;
     };
@@ -153,8 +153,8 @@ void dkdv_mfma_kernel(
     auto ids = [&](int a0, int (&t)[C::NI], int& tl, auto inside) {
         if constexpr (decltype(inside)::value) {
 #pragma unroll
-            for (int i = 0; i < C::NI; ++i) t[i] = lsrc[a0 + C::RPI * i + grow];
-            tl = lsrc[a0 + (lane & 31)];
+            for (int i = 0; i < C::NI; ++i) t[i] = list_query(lsrc[a0 + C::RPI * i + grow]);
+            tl = list_query(lsrc[a0 + (lane & 31)]);
         } else {
 #pragma unroll
             for (int i = 0; i < C::NI; ++i) t[i] = query_at(a0 + C::RPI * i + grow);

@@ -38,9 +38,8 @@ struct DqKmCfg {
     static constexpr size_t lds(int ng) { return PARK + (size_t)2 * ng * 64 * D; }   // + the part's K and V
 };
 
-// NG: 32-key groups per workgroup; KC: a query's row of kept blocks is searched CPR entries at a
-// time, KC times (k <= KC * CPR)
-template <int D, int NG, int KC>
+// NG: 32-key groups per workgroup
+template <int D, int NG>
 __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kt, const float2* __restrict__ ld,
@@ -108,36 +107,34 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     // inside a branch is waited for at the end of the branch)
     const int32_t* lsrc = nlist > 0 ? qs + lo : os;
     const int llast = max(nlist - 1, 0);
+    // position a of the walk -> list entry (query, e: the place of this block in the query's row
+    // of kept blocks, filed in the entry's high byte by the list builder); own rows and rows past
+    // the end: e = k
+    const int own_e = k << 24;
     auto query_at = [&](int a) {
         const int listed = lsrc[min(a, llast)];
-        const int t = a < nlist ? listed : own0 + (a - nlist);
-        return a >= total ? own0 : t;
+        const int t = a < nlist ? listed : (own0 + (a - nlist)) | own_e;
+        return a >= total ? own0 | own_e : t;
     };
     const int grow = lane / C::CPR, lcol = lane % C::CPR;
     const uint32_t gcol = (uint32_t)lcol * 16u;
-    // t: the rows this lane gathers a piece of; tl: the row whose lse and D lane (lane & 31) brings
+    // t: the entries of the rows this lane gathers a piece of; tl: the row whose lse and D lane
+    // (lane & 31) brings
     auto ids = [&](int a0, int (&t)[C::NI], int& tl) {
 #pragma unroll
         for (int i = 0; i < C::NI; ++i) t[i] = query_at(a0 + C::RPI * i + grow);
-        tl = query_at(a0 + (lane & 31));
+        tl = list_query(query_at(a0 + (lane & 31)));
     };
-    const int32_t* isrc = k > 0 ? idx + sbase * k : os;
-    const int klast = max(k - 1, 0);
-    // one step's loads: the pieces of the Q and dO rows, the rows' kept blocks (CPR entries per
-    // row and instruction), lse in log2 units (+inf past the end: P = 0) and -D
+    // one step's loads: the pieces of the Q and dO rows, lse in log2 units (+inf past the end:
+    // P = 0) and -D
     auto fetch = [&](int a0, const int (&t)[C::NI], int tl, dqvec4_t (&qr)[C::NI], dqvec4_t (&gr)[C::NI],
-                     int (&ev)[C::NI][KC], float& lv, float& dv) {
+                     float& lv, float& dv) {
 #pragma unroll
         for (int i = 0; i < C::NI; ++i) {
-            const uint32_t o = (uint32_t)t[i] * (uint32_t)(2 * D) + gcol;
+            const uint32_t o = (uint32_t)list_query(t[i]) * (uint32_t)(2 * D) + gcol;
             qr[i] = *reinterpret_cast<const dqvec4_t*>(Qg + o);
             gr[i] = *reinterpret_cast<const dqvec4_t*>(Gg + o);
         }
-#pragma unroll
-        for (int i = 0; i < C::NI; ++i)
-#pragma unroll
-            for (int cc = 0; cc < KC; ++cc)
-                ev[i][cc] = isrc[(int64_t)t[i] * k + min(lcol + C::CPR * cc, klast)];
         const float2 x = ldq[tl];
         lv = a0 + (lane & 31) < total ? x.x : INFINITY;
         dv = x.y;
@@ -146,43 +143,31 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     // step after that (tN, tlN) are loaded before that gather, so that waiting for them (loads
     // complete in order) leaves the gather in flight.
     const int stride = 32 * C::NW;
-    int t0[C::NI], tN[C::NI], tl0, tlN, ev0[C::NI][KC];
+    int t0[C::NI], tN[C::NI], tl0, tlN;
     dqvec4_t qr0[C::NI], gr0[C::NI];
     float lv0, dv0;
     ids(32 * wave, t0, tl0);
     ids(32 * wave + stride, tN, tlN);
-    fetch(32 * wave, t0, tl0, qr0, gr0, ev0, lv0, dv0);
+    fetch(32 * wave, t0, tl0, qr0, gr0, lv0, dv0);
     const uint32_t park = (uint32_t)grow * C::SB + gcol;
     const uint32_t arow = (uint32_t)m16 * C::SB + 16u * g;
     const int64_t slots = (int64_t)(k + 1) * nsub;          // partials per query
 
     auto step = [&](int a0, int (&tA)[C::NI], int& tlA, dqvec4_t (&qr)[C::NI], dqvec4_t (&gr)[C::NI],
-                    int (&ev)[C::NI][KC], float& lv, float& dv) {
-        // park the gathered rows, t behind each Q row, and e from the lane that finds j in the
-        // query's row of kept blocks (own rows: e = k)
+                    float& lv, float& dv) {
+        // park the gathered rows, the list entry (t, e) behind each Q row
 #pragma unroll
         for (int i = 0; i < C::NI; ++i) {
             *reinterpret_cast<dqvec4_t*>(stQ + park + i * C::RPI * C::SB) = qr[i];
             *reinterpret_cast<dqvec4_t*>(stG + park + i * C::RPI * C::SB) = gr[i];
-            int e = -1;
-#pragma unroll
-            for (int cc = 0; cc < KC; ++cc) {
-                const int ent = lcol + C::CPR * cc;
-                if (ev[i][cc] == j && ent < k) e = ent;
-            }
-            if (a0 + C::RPI * i + grow >= nlist) e = lcol == 0 ? k : -1;
-            // t always, e where found: lists that do not match the rows of kept blocks give a
-            // wrong result, never an address outside the query's partials
-            unsigned char* note = stQ + (grow + i * C::RPI) * C::SB + 2 * D;
-            if (lcol == 0) *reinterpret_cast<int*>(note) = tA[i];
-            if (e >= 0) *reinterpret_cast<int*>(note + 4) = e;
+            if (lcol == 0) *reinterpret_cast<int*>(stQ + (grow + i * C::RPI) * C::SB + 2 * D) = tA[i];
         }
         if (lane < 32) { ls[lane] = lv; Ds[lane] = dv; }
 #pragma unroll
         for (int i = 0; i < C::NI; ++i) tA[i] = tN[i];
         tlA = tlN;
         ids(a0 + 2 * stride, tN, tlN);
-        fetch(a0 + stride, tA, tlA, qr, gr, ev, lv, dv);
+        fetch(a0 + stride, tA, tlA, qr, gr, lv, dv);
         __builtin_amdgcn_wave_barrier();
         const bool masked = a0 + 32 > nlist;                       // the step holds own rows
 #pragma unroll
@@ -193,7 +178,7 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
                 qb[ks].q = *reinterpret_cast<const uint4*>(stQ + arow + qt * 16 * C::SB + 64 * ks);
                 gb[ks].q = *reinterpret_cast<const uint4*>(stG + arow + qt * 16 * C::SB + 64 * ks);
             }
-            const int2 te = *reinterpret_cast<const int2*>(stQ + (16 * qt + m16) * C::SB + 2 * D);
+            const int te = *reinterpret_cast<const int*>(stQ + (16 * qt + m16) * C::SB + 2 * D);
             const float lq = ls[16 * qt + m16], nd = Ds[16 * qt + m16];
             const int av = a0 + 16 * qt + m16;                     // this lane's row of the walk
             const int r = av - nlist;                              // own row r sees keys 0 .. r of the part
@@ -231,8 +216,10 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
             }
             // the partial: this lane holds D/4 consecutive channels of the row
             if (av < total) {
-                const int e = min(max(te.y, 0), k);
-                const int64_t prow = (sbase + te.x) * slots + (int64_t)e * nsub + c;
+                // clamped: lists that do not match the rows of kept blocks give a wrong result,
+                // never an address outside the partials
+                const int e = min(list_slot(te), k);
+                const int64_t prow = (sbase + min(list_query(te), N - 1)) * slots + (int64_t)e * nsub + c;
                 uint32_t w[C::MT * 2];
 #pragma unroll
                 for (int mt = 0; mt < C::MT; ++mt) {
@@ -247,7 +234,7 @@ __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
         }
         __builtin_amdgcn_wave_barrier();
     };
-    for (int a0 = 32 * wave; a0 < total; a0 += stride) step(a0, t0, tl0, qr0, gr0, ev0, lv0, dv0);
+    for (int a0 = 32 * wave; a0 < total; a0 += stride) step(a0, t0, tl0, qr0, gr0, lv0, dv0);
 }
 
 // dQ_t = sum of the query's partials, in the order [kept block][part], then the parts of its
@@ -307,19 +294,19 @@ size_t backward_km_ws_bytes(const Dims& s)
     return a256(sizeof(float) * (size_t)s.bh * s.N) + tensor + a256(sizeof(bf16_t) * km_partials(s) * s.D);
 }
 
-template <int D, int NG, int KC>
-static hipError_t dq_launch3(const Dims& s, const void* Q, const void* dO, const void* K, const void* V,
+template <int D, int NG>
+static hipError_t dq_launch2(const Dims& s, const void* Q, const void* dO, const void* K, const void* V,
                              const void* Kt, const float2* ld, const int32_t* idx,
                              const int32_t* off, const int32_t* ql, bf16_t* PdQ, void* dQ, hipStream_t st)
 {
     using C = DqKmCfg<D>;
     const int nsub = s.B / km_part_keys(s.B, s.D);
-    hipError_t e = hipFuncSetAttribute((const void*)dq_km_kernel<D, NG, KC>,
+    hipError_t e = hipFuncSetAttribute((const void*)dq_km_kernel<D, NG>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::lds(NG));
     if (e != hipSuccess) return e;
     {
         ProfileScope timing(MOBA_PROFILE_DQ, st);
-        hipLaunchKernelGGL((dq_km_kernel<D, NG, KC>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
+        hipLaunchKernelGGL((dq_km_kernel<D, NG>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
                            dim3(C::NT), C::lds(NG), st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)K,
                            (const bf16_t*)V, (const bf16_t*)Kt, ld, idx, off, ql, PdQ, s.N, s.B, s.n,
                            s.k, nsub, s.scale, s.R, s.bh, s.G);
@@ -329,15 +316,6 @@ static hipError_t dq_launch3(const Dims& s, const void* Q, const void* dO, const
     hipLaunchKernelGGL((dq_km_merge_kernel<D>), dim3((unsigned)((rows + rpw - 1) / rpw)), dim3(256), 0, st,
                        idx, PdQ, (bf16_t*)dQ, s.N, s.B, s.k, nsub, rows);
     return hipGetLastError();
-}
-
-template <int D, int NG, typename... A>
-static hipError_t dq_launch2(const Dims& s, A... a)
-{
-    constexpr int CPR = DqKmCfg<D>::CPR, KCMAX = kKeyMajorMaxTopk / CPR;
-    if (s.k <= CPR) return dq_launch3<D, NG, 1>(s, a...);
-    if (s.k <= 2 * CPR) return dq_launch3<D, NG, 2>(s, a...);
-    return dq_launch3<D, NG, KCMAX>(s, a...);
 }
 
 template <int D, typename... A>

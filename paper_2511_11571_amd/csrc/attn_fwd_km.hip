@@ -14,8 +14,8 @@
 // reference m, the sum l of exp(s - m), and sum p v / l rounded to bf16 -- and a second kernel
 // merges a query's partials (Section 4.2: the partial outputs are combined with the
 // log-sum-exp weights).  The partials of query t lie together, [t][e][c] for its e-th kept
-// block (e = k: own block) and part c of the block's keys, so the merge streams them; the walk finds e by
-// looking j up in the query's (ascending) row of kept blocks.  No atomics anywhere; results are
+// block (e = k: own block) and part c of the block's keys, so the merge streams them; e comes with
+// the query in the block's list (the list builder files it in the entry's high byte).  No atomics anywhere; results are
 // bit-reproducible.
 #include <type_traits>
 
@@ -41,9 +41,8 @@ struct KmCfg {
     static constexpr size_t lds(int ng) { return PARK + (size_t)(VLDS ? 2 : 1) * ng * 64 * D; }   // + the part's keys (and values)
 };
 
-// NG: 32-key groups per workgroup; KC: a query's row of kept blocks is searched CPR entries at a
-// time, KC times (k <= KC * CPR)
-template <int D, int NG, int KC>
+// NG: 32-key groups per workgroup
+template <int D, int NG>
 __global__ __launch_bounds__(KmCfg<D>::NT) __attribute__((amdgpu_waves_per_eu(D == 128 ? 2 : 1)))
 void fwd_km_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt,
@@ -110,10 +109,12 @@ void fwd_km_kernel(
     // inside a branch is waited for at the end of the branch)
     const int32_t* lsrc = nlist > 0 ? qs + lo : os;
     const int llast = max(nlist - 1, 0);
+    // position a of the walk -> list entry (query, e); own rows and rows past the end: e = k
+    const int own_e = k << 24;
     auto query_at = [&](int a) {
         const int listed = lsrc[min(a, llast)];
-        const int t = a < nlist ? listed : own0 + (a - nlist);
-        return a >= total ? own0 : t;
+        const int t = a < nlist ? listed : (own0 + (a - nlist)) | own_e;
+        return a >= total ? own0 | own_e : t;
     };
     const int grow = lane / C::CPR, lcol = lane % C::CPR;
     const uint32_t gcol = (uint32_t)lcol * 16u;
@@ -124,60 +125,35 @@ void fwd_km_kernel(
     auto fetch = [&](const int (&t)[C::NI], kmvec4_t (&qr)[C::NI]) {
 #pragma unroll
         for (int i = 0; i < C::NI; ++i)
-            qr[i] = *reinterpret_cast<const kmvec4_t*>(Qg + (uint32_t)t[i] * (uint32_t)(2 * D) + gcol);
+            qr[i] = *reinterpret_cast<const kmvec4_t*>(Qg + (uint32_t)list_query(t[i]) * (uint32_t)(2 * D) + gcol);
     };
-    // the kept blocks of the gathered queries, CPR entries per row and instruction
-    const int32_t* isrc = k > 0 ? idx + sbase * k : os;
-    const int klast = max(k - 1, 0);
-    auto lookup = [&](const int (&t)[C::NI], int (&ev)[C::NI][KC]) {
-#pragma unroll
-        for (int i = 0; i < C::NI; ++i)
-#pragma unroll
-            for (int cc = 0; cc < KC; ++cc)
-                ev[i][cc] = isrc[(int64_t)t[i] * k + min(lcol + C::CPR * cc, klast)];
-    };
-    // Two steps of gathered rows are in flight while a third is worked on: t (the rows), qr
-    // (their 16-byte pieces) and ev (their kept blocks) of step i sit in buffer i % 2, the rows
-    // of step i + 2 in tN.  The loads for tN go out before the gather of the step before it, so
+    // Two steps of gathered rows are in flight while a third is worked on: t (the list entries)
+    // and qr (the rows' 16-byte pieces) of step i sit in buffer i % 2, the entries of step i + 2
+    // in tN.  The loads for tN go out before the gather of the step before it, so
     // that waiting for them (loads complete in order) leaves that gather in flight.
     const int stride = 32 * C::NW;
-    int t0[C::NI], t1[C::NI], tN[C::NI], ev0[C::NI][KC], ev1[C::NI][KC];
+    int t0[C::NI], t1[C::NI], tN[C::NI];
     kmvec4_t qr0[C::NI], qr1[C::NI];
     ids(32 * wave, t0);
     ids(32 * wave + stride, t1);
     ids(32 * wave + 2 * stride, tN);
     fetch(t0, qr0);
-    lookup(t0, ev0);
     fetch(t1, qr1);
-    lookup(t1, ev1);
     const uint32_t park = (uint32_t)grow * C::SB + gcol;
     const uint32_t arow = (uint32_t)m16 * C::SB + 16u * g;
     const int64_t slots = (int64_t)(k + 1) * nsub;          // partials per query
 
-    auto step = [&](int a0, int (&tA)[C::NI], kmvec4_t (&qr)[C::NI], int (&ev)[C::NI][KC]) {
-        // park the gathered rows, t behind each, and e from the lane that finds j in the query's
-        // row of kept blocks (own rows: e = k)
+    auto step = [&](int a0, int (&tA)[C::NI], kmvec4_t (&qr)[C::NI]) {
+        // park the gathered rows, the list entry (t, e) behind each
 #pragma unroll
         for (int i = 0; i < C::NI; ++i) {
             *reinterpret_cast<kmvec4_t*>(stQ + park + i * C::RPI * C::SB) = qr[i];
-            int e = -1;
-#pragma unroll
-            for (int cc = 0; cc < KC; ++cc) {
-                const int ent = lcol + C::CPR * cc;
-                if (ev[i][cc] == j && ent < k) e = ent;
-            }
-            if (a0 + C::RPI * i + grow >= nlist) e = lcol == 0 ? k : -1;
-            // t always, e where found: lists that do not match the rows of kept blocks give a
-            // wrong result, never an address outside the query's partials
-            unsigned char* note = stQ + (grow + i * C::RPI) * C::SB + 2 * D;
-            if (lcol == 0) *reinterpret_cast<int*>(note) = tA[i];
-            if (e >= 0) *reinterpret_cast<int*>(note + 4) = e;
+            if (lcol == 0) *reinterpret_cast<int*>(stQ + (grow + i * C::RPI) * C::SB + 2 * D) = tA[i];
         }
 #pragma unroll
         for (int i = 0; i < C::NI; ++i) tA[i] = tN[i];
         ids(a0 + 3 * stride, tN);
         fetch(tA, qr);
-        lookup(tA, ev);
         __builtin_amdgcn_wave_barrier();
         const bool masked = a0 + 32 > nlist;                       // the step holds own rows
 #pragma unroll
@@ -270,10 +246,12 @@ void fwd_km_kernel(
                 const int r = 16 * qt + C::RPI * h + grow;          // parked row of this lane
                 const unsigned char* prk = stQ + r * C::SB;
                 const kmvec4_t v = *reinterpret_cast<const kmvec4_t*>(prk + gcol);
-                const int4 note = *reinterpret_cast<const int4*>(prk + 2 * D);     // t, e, m, l
+                const int4 note = *reinterpret_cast<const int4*>(prk + 2 * D);     // (t, e), -, m, l
                 if (a0 + r < total) {
-                    const int e = min(max(note.y, 0), k);
-                    const int64_t prow = (sbase + note.x) * slots + (int64_t)e * nsub + c;
+                    // clamped: lists that do not match the rows of kept blocks give a wrong result,
+                    // never an address outside the partials
+                    const int e = min(list_slot(note.x), k);
+                    const int64_t prow = (sbase + min(list_query(note.x), N - 1)) * slots + (int64_t)e * nsub + c;
                     *reinterpret_cast<kmvec4_t*>(reinterpret_cast<char*>(PO + prow * D) + gcol) = v;
                     if (lcol == 0)
                         *reinterpret_cast<float2*>(Pml + prow * 2) =
@@ -284,9 +262,9 @@ void fwd_km_kernel(
         __builtin_amdgcn_wave_barrier();
     };
     for (int a0 = 32 * wave; a0 < total; a0 += 2 * stride) {
-        step(a0, t0, qr0, ev0);
+        step(a0, t0, qr0);
         if (a0 + stride >= total) break;
-        step(a0 + stride, t1, qr1, ev1);
+        step(a0 + stride, t1, qr1);
     }
 }
 
@@ -384,19 +362,19 @@ size_t forward_km_ws_bytes(const Dims& s)
     return tensor + a256(sizeof(bf16_t) * km_partials(s) * s.D) + a256(sizeof(float) * km_partials(s) * 2);
 }
 
-template <int D, int NG, int KC>
-static hipError_t km_launch3(const Dims& s, const void* Q, const void* K, const void* Vt,
+template <int D, int NG>
+static hipError_t km_launch2(const Dims& s, const void* Q, const void* K, const void* Vt,
                              const int32_t* idx, const int32_t* off, const int32_t* ql, bf16_t* PO,
                              float* Pml, void* O, float* lse, hipStream_t st)
 {
     using C = KmCfg<D>;
     const int nsub = s.B / km_part_keys(s.B, s.D);
-    hipError_t e = hipFuncSetAttribute((const void*)fwd_km_kernel<D, NG, KC>,
+    hipError_t e = hipFuncSetAttribute((const void*)fwd_km_kernel<D, NG>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::lds(NG));
     if (e != hipSuccess) return e;
     {
         ProfileScope timing(MOBA_PROFILE_FORWARD, st);
-        hipLaunchKernelGGL((fwd_km_kernel<D, NG, KC>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
+        hipLaunchKernelGGL((fwd_km_kernel<D, NG>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
                            dim3(C::NT), C::lds(NG), st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)Vt,
                            idx, off, ql, PO, Pml, s.N, s.B, s.n, s.k, nsub, s.scale, s.R, s.bh, s.G);
     }
@@ -405,15 +383,6 @@ static hipError_t km_launch3(const Dims& s, const void* Q, const void* K, const 
     hipLaunchKernelGGL((fwd_km_merge_kernel<D>), dim3((unsigned)((rows + rpw - 1) / rpw)), dim3(256), 0, st,
                        idx, PO, Pml, (bf16_t*)O, lse, s.N, s.B, s.k, nsub, rows);
     return hipGetLastError();
-}
-
-template <int D, int NG, typename... A>
-static hipError_t km_launch2(const Dims& s, A... a)
-{
-    constexpr int CPR = KmCfg<D>::CPR, KCMAX = kKeyMajorMaxTopk / CPR;
-    if (s.k <= CPR) return km_launch3<D, NG, 1>(s, a...);
-    if (s.k <= 2 * CPR) return km_launch3<D, NG, 2>(s, a...);
-    return km_launch3<D, NG, KCMAX>(s, a...);
 }
 
 template <int D, typename... A>

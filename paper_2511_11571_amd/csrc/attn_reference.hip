@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void dkdv_reference_kernel(
     const int32_t* qs = ql + (int64_t)s * R;
     const int lo = os[j], nlist = os[j + 1] - lo;
     for (int a = 0; a < nlist + B; ++a) {
-        const int t = a < nlist ? qs[lo + a] : j * B + (a - nlist);
+        const int t = a < nlist ? list_query(qs[lo + a]) : j * B + (a - nlist);
         const bool seen = live && (a < nlist || ul <= a - nlist);   // own block: keys <= query
         float q[C], g[C];
 #pragma unroll

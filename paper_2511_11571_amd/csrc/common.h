@@ -118,6 +118,13 @@ __device__ __forceinline__ uint32_t order_key(float s)
     return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
 }
 
+// ---- entries of the key-block-major query lists ------------------------------------------
+// low 24 bits: the query; high byte: the position of the block in the query's row of kept blocks
+// (filled in for top-k up to 64, see lists.hip)
+constexpr int kListQueryMask = 0xffffff;
+__device__ __forceinline__ int list_query(int entry) { return entry & kListQueryMask; }
+__device__ __forceinline__ int list_slot(int entry) { return (int)((uint32_t)entry >> 24); }
+
 // ---- workgroup -> (slice, position) ------------------------------------------------------
 // Workgroups are dealt to the chip's 8 XCDs round robin (workgroup i runs on XCD i % 8) and
 // every XCD has an L2 of its own.  The workgroups resident on one XCD at a time should

@@ -10,13 +10,22 @@
 //   3. fill: the bit matrix is rebuilt and its rows are written out in ascending order at
 //      blk_off[j] + chunk start, eight lanes per row.
 // The bit matrix lives in LDS only and covers 1024 key blocks at a time.
-#include "common.h"
+//
+// A list entry holds the query in its low 24 bits (sequences are at most 2^24 long).  Where the
+// key-block-major attention kernels will run (key_major_path() of the shape and its flags) the
+// high byte holds the position e of the block in the query's row of kept blocks: those kernels
+// file the partial result of (query, block) under (query, e) and would otherwise have to search
+// the row for the block (10-15 % of their time); elsewhere it is zero.  The fill pass gets e by walking the
+// routing rows a second time: entry e of row r names block b, whose place in b's run of this
+// workgroup is the number of set bits below r in b's row of the bit matrix.
+#include "mfma.h"
 
 namespace moba {
 
 constexpr int kRange = 1024;                    // key blocks per LDS bit matrix (32 KB)
 constexpr int kListQ = 2 * kChunkQ;              // queries per workgroup: two chunks of 128
 constexpr int kWords = kListQ / 32;             // 8 words of 32 query bits per block
+constexpr int kQueryBits = 24;                  // low bits of a list entry: the query
 
 // f(r, b) for every entry b of the routing rows r = 0 .. rows-1 of this workgroup (k entries per
 // row, rows contiguous in memory), all 256 threads, 16-byte loads when the row length allows
@@ -44,13 +53,43 @@ __device__ __forceinline__ void for_each_entry(const int32_t* __restrict__ rows0
     }
 }
 
-template <bool FILL>
+// the same with the position of every entry in its row: f(r, b, e)
+template <typename F>
+__device__ __forceinline__ void for_each_entry_slot(const int32_t* __restrict__ rows0, int rows, int k,
+                                                    int tid, F f)
+{
+    const int total = rows * k;
+    if ((k & 3) == 0) {
+        const int4* p4 = reinterpret_cast<const int4*>(rows0);
+        const int n4 = total >> 2;
+        for (int i0 = tid; i0 < n4; i0 += 4 * 256) {
+            int4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[u] = i0 + u * 256 < n4 ? p4[i0 + u * 256] : make_int4(-1, -1, -1, -1);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = (i0 + u * 256) << 2;
+                const int r = q / k, e = q - r * k;
+                f(r, v[u].x, e); f(r, v[u].y, e + 1); f(r, v[u].z, e + 2); f(r, v[u].w, e + 3);
+            }
+        }
+    } else {
+        for (int i = tid; i < total; i += 256) f(i / k, rows0[i], i % k);
+    }
+}
+
+template <bool FILL, bool SLOTS>
 __global__ __launch_bounds__(256) void lists_chunk_kernel(
     const int32_t* __restrict__ idx, int32_t* __restrict__ cnt2, const int32_t* __restrict__ off,
     int32_t* __restrict__ ql, int N, int B, int n, int k, int nchunk, int64_t R, int bh)
 {
     __shared__ __align__(16) uint32_t mask[kRange * kWords];
     __shared__ int32_t start[FILL ? kRange : 1];         // where this workgroup's queries start in each list
+    __shared__ uint16_t lbase[SLOTS ? kRange : 1];       // where block b's run starts among this workgroup's entries
+    extern __shared__ uint8_t slot[];                    // SLOTS: e of every entry, run by run (kListQ * k bytes)
+    __shared__ int wsum[4];
+    const int slot_last = kListQ * k - 1;
     // consecutive query chunks of a slice go to the same XCD: the 128-byte lines of a block's
     // list are completed by neighbouring chunks and should meet in one L2 before they are written back
     int c, s;
@@ -101,6 +140,48 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
             if (two) crow[n + j] = c1;
         }
     } else {
+        if constexpr (SLOTS) {
+            // runs of the blocks one after the other: exclusive scan of the rows' bit counts
+            // (four consecutive blocks per thread, threads by shuffles, waves through LDS)
+            int c4[4], mine = 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int b = 4 * tid + u;
+                int c = 0;
+                if (b < nblk)
+#pragma unroll
+                    for (int wd = 0; wd < kWords; ++wd) c += __popc(mask[b * kWords + wd]);
+                c4[u] = c;
+                mine += c;
+            }
+            int incl = mine;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const int up = __shfl_up(incl, o, kWave);
+                if ((tid & (kWave - 1)) >= o) incl += up;
+            }
+            if ((tid & (kWave - 1)) == kWave - 1) wsum[tid / kWave] = incl;
+            __syncthreads();
+            int run = incl - mine;
+            for (int wv = 0; wv < tid / kWave; ++wv) run += wsum[wv];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (4 * tid + u < nblk) lbase[4 * tid + u] = (uint16_t)run;
+                run += c4[u];
+            }
+            __syncthreads();
+            // a query keeps at most k blocks, so the runs hold at most kListQ * k entries
+            for_each_entry_slot(rows0, rows, k, tid, [&](int r, int b, int e) {
+                b -= lo;
+                if (b >= 0 && b < nblk && b + lo < (t0 + r) / B) {
+                    const uint32_t* mrow = mask + b * kWords;
+                    int rank = __popc(mrow[r >> 5] & ((1u << (r & 31)) - 1u));
+                    for (int wd = 0; wd < (r >> 5); ++wd) rank += __popc(mrow[wd]);
+                    slot[min((int)lbase[b] + rank, slot_last)] = (uint8_t)e;
+                }
+            });
+            __syncthreads();
+        }
         // Eight lanes per block, one 32-query word each: a lane writes the queries of its word
         // after those of the lanes before it.  The 256 queries of this workgroup are neighbours
         // in every list, so a store instruction touches one short run of addresses per block.
@@ -116,10 +197,13 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
                 if (lane8 >= o) incl += up;
             }
             int64_t pos = (int64_t)start[b] + (incl - cnt);
+            int local = SLOTS ? (int)lbase[b] + (incl - cnt) : 0;
             while (word) {
+                int entry = t0 + 32 * lane8 + (__ffs(word) - 1);
+                if constexpr (SLOTS) entry |= (int)slot[min(local++, slot_last)] << kQueryBits;
                 // a routing that breaks the contract (repeats, too many kept blocks) must not
                 // write outside the slice's lists
-                if (pos < R) qs[pos] = t0 + 32 * lane8 + (__ffs(word) - 1);
+                if (pos < R) qs[pos] = entry;
                 ++pos;
                 word &= word - 1u;
             }
@@ -192,14 +276,20 @@ hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, i
 {
     const int nranges = (s.n + kRange - 1) / kRange;
     dim3 grid(schedule_grid(s.bh, (s.nchunk + 1) / 2), nranges), block(256);
-    hipLaunchKernelGGL((lists_chunk_kernel<false>), grid, block, 0, st, idx, cnt2,
+    hipLaunchKernelGGL((lists_chunk_kernel<false, false>), grid, block, 0, st, idx, cnt2,
                        (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R, s.bh);
     hipLaunchKernelGGL(lists_scan_kernel, dim3((s.n + 31) / 32, s.bh), block, 0, st, cnt2, off, s.n,
                        s.nchunk);
     hipLaunchKernelGGL(lists_offsets_kernel, dim3(s.bh), block, 0, st, off, s.n);
-    if (s.R > 0)
-        hipLaunchKernelGGL((lists_chunk_kernel<true>), grid, block, 0, st, idx, cnt2,
-                           (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R, s.bh);
+    if (s.R > 0) {
+        static_assert(kKeyMajorMaxTopk <= 255 && kListQ * kKeyMajorMaxTopk <= 65535, "slot byte, 16-bit run starts");
+        if (key_major_path(s))
+            hipLaunchKernelGGL((lists_chunk_kernel<true, true>), grid, block, (size_t)kListQ * s.k, st, idx,
+                               cnt2, (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R, s.bh);
+        else
+            hipLaunchKernelGGL((lists_chunk_kernel<true, false>), grid, block, 0, st, idx, cnt2,
+                               (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R, s.bh);
+    }
     return hipGetLastError();
 }
 

@@ -222,7 +222,7 @@ bool topk_mfma_supported(const Dims& s);
 hipError_t launch_topk_mfma(const Dims& s, const void* Q, const float* cent, int32_t* idx, void* ws,
                             hipStream_t st);
 
-constexpr int kKeyMajorMaxTopk = 64;      // longest row of kept blocks the key-major walk searches
+constexpr int kKeyMajorMaxTopk = 64;      // longest row of kept blocks the key-major kernels take
 
 // keys a key-major workgroup holds in registers as MFMA operands: the whole block up to 128
 // (d = 64) or 64 (d = 128) keys, else parts of that size

@@ -39,6 +39,23 @@ def routing_check(oracle, got_idx, ref_idx, kth, Q64, C64, B, rows=None):
     return exact, bad.size / max(nrows, 1)
 
 
+def check_lists(off, ql, idx, ref_off, ref_ql, k):
+    """off [bh, n+1], ql [bh, R] as the library wrote them; idx [bh, N, k] the routing they were
+    built from; ref_off / ref_ql the oracle's lists of the same routing.  A list entry holds the
+    query in its low 24 bits; where the key-block-major kernels will run, the high byte holds the
+    position of the block in that query's row of idx (checked against idx itself), elsewhere 0."""
+    assert np.array_equal(off, ref_off)
+    assert np.array_equal(ql & 0xffffff, ref_ql)
+    slots = ql >> 24
+    if not slots.any():
+        return
+    assert k <= 64
+    for s in range(off.shape[0]):
+        blocks = np.repeat(np.arange(off.shape[1] - 1), np.diff(off[s]))      # block of every entry
+        R = blocks.size
+        assert np.array_equal(idx[s][ref_ql[s, :R], slots[s, :R]], blocks)
+
+
 def rel_l2(a, b):
     a = np.asarray(a, np.float64).ravel()
     b = np.asarray(b, np.float64).ravel()

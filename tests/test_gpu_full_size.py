@@ -80,7 +80,9 @@ def check_slice(oracle, w, t, out, s, n_rows, blocks, rng):
     assert np.array_equal(np.diff(g_off), counts)
     for j in rng.integers(0, w.n, 8):
         lst = g_ql[g_off[j]:g_off[j + 1]]
-        assert np.array_equal(lst, np.nonzero((g_idx == j).any(-1))[0])
+        assert np.array_equal(lst & 0xffffff, np.nonzero((g_idx == j).any(-1))[0])
+        if (lst >> 24).any():              # high byte: where j sits in the query's row of kept blocks
+            assert (g_idx[lst & 0xffffff, lst >> 24] == j).all()
 
     # forward / dQ on sampled rows, with the oracle's own routing
     sample = rows if not full else np.unique(rng.integers(0, w.N, n_rows)).astype(np.int64)
