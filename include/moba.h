@@ -156,7 +156,8 @@ int moba_build_lists(const moba_shape* shape, const int32_t* topk_idx,
  * (Section 2; Section 4.2 forward algorithm).  Routing is an input.
  *   Q             in   [b,h,N,d] dtype
  *   K_eff, V      in   [b,kv,N,d] dtype (K_eff = K when there is no convolution)
- *   topk_idx, blk_off, blk_q   in   as produced by moba_topk / moba_build_lists
+ *   topk_idx, blk_off, blk_q   in   as produced by moba_topk / moba_build_lists for this shape and
+ *                                   these flags (moba_backward takes the same three)
  *   O         out  [b,h,N,d] dtype
  *   lse       out  [b,h,N] fp32: natural log of sum_u exp(scale * q.k_u) over the kept keys
  *   ws             at least fwd_ws bytes
