@@ -30,10 +30,10 @@ PEAK_HBM_GBS = 8000.0
 # plain copy kernel of known size).  Keyed by (benchmark configuration, kernel); not measured
 # for the others.
 MEASURED_TRAFFIC = {      # profiles/config3_hbm_traffic.txt: 2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE (KiB)
-    (3, "topk"): (2.0 * 64883.9 + 131357.9) * 1024,
-    (3, "forward"): (2.0 * 391904.1 + 67584.0) * 1024,
-    (3, "bwd_dq"): (2.0 * 492963.4 + 65536.0) * 1024,
-    (3, "bwd_dkdv"): (2.0 * 1008296.4 + 131072.0) * 1024,
+    (3, "topk"): (2.0 * 64806.5 + 131348.2) * 1024,
+    (3, "forward"): (2.0 * 394538.2 + 67584.0) * 1024,
+    (3, "bwd_dq"): (2.0 * 493945.0 + 65536.0) * 1024,
+    (3, "bwd_dkdv"): (2.0 * 985129.5 + 131072.0) * 1024,
 }
 
 
