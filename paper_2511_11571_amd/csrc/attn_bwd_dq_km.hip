@@ -43,7 +43,7 @@ template <int D, int NG>
 __global__ __launch_bounds__(DqKmCfg<D>::NT) void dq_km_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kt, const float2* __restrict__ ld,
-    const int32_t* __restrict__ idx, const int32_t* __restrict__ off,
+    const int32_t* __restrict__ off,
     const int32_t* __restrict__ ql, bf16_t* __restrict__ PdQ, int N, int B, int n, int k, int nsub,
     float scale, int64_t R, int bh, int G)
 {
@@ -308,7 +308,7 @@ static hipError_t dq_launch2(const Dims& s, const void* Q, const void* dO, const
         ProfileScope timing(MOBA_PROFILE_DQ, st);
         hipLaunchKernelGGL((dq_km_kernel<D, NG>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
                            dim3(C::NT), C::lds(NG), st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)K,
-                           (const bf16_t*)V, (const bf16_t*)Kt, ld, idx, off, ql, PdQ, s.N, s.B, s.n,
+                           (const bf16_t*)V, (const bf16_t*)Kt, ld, off, ql, PdQ, s.N, s.B, s.n,
                            s.k, nsub, s.scale, s.R, s.bh, s.G);
     }
     const int64_t rows = (int64_t)s.bh * s.N;

@@ -46,7 +46,7 @@ template <int D, int NG>
 __global__ __launch_bounds__(KmCfg<D>::NT) __attribute__((amdgpu_waves_per_eu(D == 128 ? 2 : 1)))
 void fwd_km_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt,
-    const int32_t* __restrict__ idx, const int32_t* __restrict__ off, const int32_t* __restrict__ ql,
+    const int32_t* __restrict__ off, const int32_t* __restrict__ ql,
     bf16_t* __restrict__ PO, float* __restrict__ Pml, int N, int B, int n, int k, int nsub,
     float scale, int64_t R, int bh, int G)
 {
@@ -376,7 +376,7 @@ static hipError_t km_launch2(const Dims& s, const void* Q, const void* K, const 
         ProfileScope timing(MOBA_PROFILE_FORWARD, st);
         hipLaunchKernelGGL((fwd_km_kernel<D, NG>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
                            dim3(C::NT), C::lds(NG), st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)Vt,
-                           idx, off, ql, PO, Pml, s.N, s.B, s.n, s.k, nsub, s.scale, s.R, s.bh, s.G);
+                           off, ql, PO, Pml, s.N, s.B, s.n, s.k, nsub, s.scale, s.R, s.bh, s.G);
     }
     const int64_t rows = (int64_t)s.bh * s.N;
     const int rpw = 256 / (D / 8);
