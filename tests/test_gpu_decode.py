@@ -65,6 +65,24 @@ def oracle_decode(oracle, Q, K, V, heads, hkv, N, B, k, q_len, scale):
     return idx, kth, O, lse, rows, Qf, Ce, C
 
 
+def random_case(i):
+    """Seeded random decode shapes: any sequence length (ragged own block), any top-k from 0 to
+    beyond the number of past blocks, shared heads, both I/O types."""
+    rng = np.random.default_rng(9900 + i)
+    d = int(rng.choice([64, 128]))
+    B = int(rng.choice([1, 8, 24, 32, 64, 128, 200]))
+    N = int(rng.integers(1, 40 * B + 1))
+    heads = int(rng.choice([1, 2, 4]))
+    kv = int(rng.choice([h for h in (1, 2, 4) if heads % h == 0]))
+    k = int(rng.integers(0, min((N - 1) // B + 3, 20)))
+    q_len = int(rng.integers(1, min(N, 24) + 1))
+    return ("random%d_N%d_B%d_k%d_q%d" % (i, N, B, k, q_len), int(rng.choice([1, 2])), heads,
+            0 if kv == heads else kv, N, d, B, k, q_len, "f32" if rng.random() < 0.3 else "bf16")
+
+
+CASES = CASES + [random_case(i) for i in range(16)]
+
+
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_decode_forward(oracle, case):
     name, batch, heads, kv, N, d, B, k, q_len, dtype = case
