@@ -246,18 +246,22 @@ void fwd_km_kernel(
                 const int r = 16 * qt + C::RPI * h + grow;          // parked row of this lane
                 const unsigned char* prk = stQ + r * C::SB;
                 const kmvec4_t v = *reinterpret_cast<const kmvec4_t*>(prk + gcol);
-                const int4 note = *reinterpret_cast<const int4*>(prk + 2 * D);     // (t, e), -, m, l
+                const int note = *reinterpret_cast<const int*>(prk + 2 * D);       // (t, e)
                 if (a0 + r < total) {
                     // clamped: lists that do not match the rows of kept blocks give a wrong result,
                     // never an address outside the partials
-                    const int e = min(list_slot(note.x), k);
-                    const int64_t prow = (sbase + min(list_query(note.x), N - 1)) * slots + (int64_t)e * nsub + c;
+                    const int e = min(list_slot(note), k);
+                    const int64_t prow = (sbase + min(list_query(note), N - 1)) * slots + (int64_t)e * nsub + c;
                     *reinterpret_cast<kmvec4_t*>(reinterpret_cast<char*>(PO + prow * D) + gcol) = v;
-                    if (lcol == 0)
-                        *reinterpret_cast<float2*>(Pml + prow * 2) =
-                            make_float2(__int_as_float(note.z), __int_as_float(note.w));
                 }
             }
+        }
+        // (m, l) of the step's 32 rows in one store instruction, a lane per row
+        if (lane < 32 && a0 + lane < total) {
+            const int4 note = *reinterpret_cast<const int4*>(stQ + lane * C::SB + 2 * D);    // (t, e), -, m, l
+            const int e = min(list_slot(note.x), k);
+            const int64_t prow = (sbase + min(list_query(note.x), N - 1)) * slots + (int64_t)e * nsub + c;
+            *reinterpret_cast<float2*>(Pml + prow * 2) = make_float2(__int_as_float(note.z), __int_as_float(note.w));
         }
         __builtin_amdgcn_wave_barrier();
     };
