@@ -142,6 +142,21 @@ int moba_topk(const moba_shape* shape, const void* Q, const float* centroids,
               void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * moba_topk for callers that cannot allocate device memory or hand over a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, with
+ * the workspace in a device array that is part of the library image, MOBA_TOPK_STATIC_MAX_BYTES
+ * long, one copy per GPU, held until the process ends.  The call allocates nothing.  Same
+ * arguments, outputs and checks as moba_topk without `ws`; a shape whose topk_ws (see
+ * moba_workspace_bytes) exceeds MOBA_TOPK_STATIC_MAX_BYTES returns MOBA_EWORKSPACE and launches
+ * nothing (batch 1, 16 heads, N = 32768, B = 32 needs 23 MiB).  All calls on one GPU share that
+ * GPU's array: calls that may overlap in time on one GPU (different streams, different threads)
+ * race and must be ordered by the caller.  Nothing in the array has to survive between calls.
+ */
+#define MOBA_TOPK_STATIC_MAX_BYTES (32u << 20)
+int moba_topk_static(const moba_shape* shape, const void* Q, const float* centroids,
+                     int32_t* topk_idx, int32_t* blk_off, int32_t* blk_q, void* stream);
+
+/*
  * The list-building half of moba_topk alone (Appendix C.1, varlen reformatting), for a
  * routing supplied by the caller.  topk_idx rows may list their blocks in any order;
  * entries must be -1 or a past block of the query, without repeats, and every query of

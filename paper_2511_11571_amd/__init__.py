@@ -5,4 +5,4 @@ kernels behind the C ABI declared in include/moba.h.
 """
 from .binding import (MobaError, Shape, backward, build_lists, centroids, decode_forward, forward,  # noqa: F401
                       key_conv_backward, lib,
-                      profile_begin, profile_end, routes_per_slice, topk, workspace_bytes)
+                      profile_begin, profile_end, routes_per_slice, topk, topk_static, workspace_bytes)

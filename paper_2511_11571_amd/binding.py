@@ -81,7 +81,7 @@ def lib():
         L.moba_strerror.argtypes = [ctypes.c_int]
         L.moba_last_hip_error.restype = ctypes.c_int
         for name in ("moba_routes_per_slice", "moba_workspace_bytes", "moba_centroids", "moba_topk",
-                     "moba_build_lists", "moba_forward", "moba_backward", "moba_backward_parts",
+                     "moba_topk_static", "moba_build_lists", "moba_forward", "moba_backward", "moba_backward_parts",
                      "moba_decode_forward",
                      "moba_profile_begin", "moba_profile_end", "moba_key_conv_backward",
                      "moba_key_conv_backward_workspace"):
@@ -170,6 +170,22 @@ def topk(shape: Shape, Q, cent, ws=None):
         ws = _ws(workspace_bytes(shape)[0], Q)
     _check(lib().moba_topk(ctypes.byref(shape.c()), _p(Q), _p(cent), _p(idx), _p(off), _p(ql),
                            _p(ws), ctypes.c_size_t(ws.numel()), _stream()), "moba_topk")
+    return idx, (off, ql)
+
+
+def topk_static(shape: Shape, Q, cent, out=None):
+    """moba_topk_static: as topk, with the library's own static scratch instead of a workspace.
+    ``out`` = (idx, (blk_off, blk_q)) lets the caller bring the output tensors, so that the call
+    itself allocates nothing."""
+    assert Q.is_contiguous() and cent.is_contiguous()
+    if out is None:
+        idx = torch.empty((shape.batch, shape.heads, shape.seqlen, shape.topk), dtype=torch.int32,
+                          device=Q.device)
+        off, ql = _list_buffers(shape, Q)
+    else:
+        idx, (off, ql) = out
+    _check(lib().moba_topk_static(ctypes.byref(shape.c()), _p(Q), _p(cent), _p(idx), _p(off), _p(ql),
+                                  _stream()), "moba_topk_static")
     return idx, (off, ql)
 
 

@@ -3,6 +3,8 @@
 // exercised on a machine without a GPU.
 #include <math.h>
 
+#include <mutex>
+
 #include "mfma.h"
 
 using namespace moba;
@@ -125,6 +127,37 @@ void profile_mark(int kernel, bool start, hipStream_t st)
 }
 
 }  // namespace moba
+
+// ---- scratch of the entry point that allocates nothing ------------------------------------------
+// moba_topk_static keeps the workspace of moba_topk here.  Every GPU the library runs on holds its
+// own copy of the array at its own address until the process ends; in host code the array's name
+// is only a handle for hipGetSymbolAddress, never a device address.
+constexpr size_t kStaticScratchBytes = (size_t)MOBA_TOPK_STATIC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU, once looked up
+
+// device address of this GPU's copy of `scratch` (looked up once per device, with that device
+// current); nullptr and *err set when HIP refuses
+void* static_scratch(hipError_t* err)
+{
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
 
 extern "C" {
 
@@ -258,6 +291,23 @@ int moba_topk(const moba_shape* shape, const void* Q, const float* centroids, in
                        : launch_topk_reference(d, Q, centroids, topk_idx, (hipStream_t)stream);
     if (e != hipSuccess) return hip_status(e);
     return hip_status(launch_build_lists(d, topk_idx, blk_off, blk_q, chunk_counts(d, ws), (hipStream_t)stream));
+}
+
+int moba_topk_static(const moba_shape* shape, const void* Q, const float* centroids,
+                     int32_t* topk_idx, int32_t* blk_off, int32_t* blk_q, void* stream)
+{
+    Dims d;
+    const int st = make_dims(shape, d);
+    if (st != MOBA_OK) return st;
+    if (!Q || !centroids || !blk_off) return MOBA_EINVAL;
+    if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
+    if (d.R > 0 && !blk_q) return MOBA_EINVAL;
+    if (d.n > kMaxBlocks) return MOBA_EUNSUPPORTED;
+    if (topk_ws_bytes(d) > kStaticScratchBytes) return MOBA_EWORKSPACE;
+    hipError_t e = hipSuccess;
+    void* ws = static_scratch(&e);
+    if (!ws) return hip_status(e);
+    return moba_topk(shape, Q, centroids, topk_idx, blk_off, blk_q, ws, kStaticScratchBytes, stream);
 }
 
 int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, const void* V,
