@@ -57,7 +57,10 @@ typedef enum moba_dtype { MOBA_F32 = 0, MOBA_BF16 = 1 } moba_dtype;
                                         * up to 128 (d = 64) / 64 (d = 128), or a multiple of that;
                                         * topk <= 64); elsewhere the flag is ignored              */
 #define MOBA_FLAG_QUERY_TILES 4u       /* attention by query tile (suits dense routing): force it   */
-/* With neither of the two the library picks by a cost estimate of both from the shape: key blocks
+#define MOBA_FLAG_GATE_EXACT_SEARCH 8u  /* moba_topk: skip the approximate first look of the selection and
+                                        * search on exact scores from the start (slower, same result; the
+                                        * path that queries with many equal scores take anyway)          */
+/* With neither of KEY_MAJOR and QUERY_TILES the library picks by a cost estimate of both from the shape: key blocks
  * where a tile of consecutive queries would meet a key block with few of its rows (small topk,
  * long sequences, large blocks: e.g. topk 8 of B = 128 at any length), query tiles where a query
  * keeps many blocks (e.g. topk 64 of B = 32 up to a few hundred thousand keys).  KEY_MAJOR and

@@ -18,6 +18,7 @@ F32, BF16 = 0, 1
 FLAG_REFERENCE_KERNELS = 1
 FLAG_KEY_MAJOR = 2
 FLAG_QUERY_TILES = 4
+FLAG_GATE_EXACT_SEARCH = 8
 
 
 class MobaError(RuntimeError):

@@ -21,9 +21,12 @@ namespace moba {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
 union Frag {               // one A or B operand
     bf16x8_t v;
     uint4 q;
+    u32x4_t n;             // the same four registers as one native vector (asm operands)
     uint32_t u[4];
 };
 

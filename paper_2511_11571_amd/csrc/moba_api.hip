@@ -32,7 +32,8 @@ int make_dims(const moba_shape* sh, Dims& d, bool ragged_ok = false)
     if (sh->block <= 0 || sh->topk < 0 || sh->conv_width < 0) return MOBA_EINVAL;
     if (!ragged_ok && sh->seqlen % sh->block != 0) return MOBA_EINVAL;
     if (sh->dtype != MOBA_F32 && sh->dtype != MOBA_BF16) return MOBA_EINVAL;
-    if (sh->flags & ~(uint32_t)(MOBA_FLAG_REFERENCE_KERNELS | MOBA_FLAG_KEY_MAJOR | MOBA_FLAG_QUERY_TILES))
+    if (sh->flags & ~(uint32_t)(MOBA_FLAG_REFERENCE_KERNELS | MOBA_FLAG_KEY_MAJOR | MOBA_FLAG_QUERY_TILES |
+                                 MOBA_FLAG_GATE_EXACT_SEARCH))
         return MOBA_EINVAL;
     if ((sh->flags & MOBA_FLAG_KEY_MAJOR) && (sh->flags & MOBA_FLAG_QUERY_TILES)) return MOBA_EINVAL;
     if (!(sh->softmax_scale == sh->softmax_scale) || isinf(sh->softmax_scale)) return MOBA_EINVAL;

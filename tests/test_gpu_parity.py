@@ -146,7 +146,12 @@ def test_key_conv_backward(oracle, dtype, d, width, N):
 MANY_BLOCKS = [W("n4096_B2", 1, 1, 8192, 64, 2, 8, seed=23), W("n4000_B2_k40", 1, 1, 8000, 64, 2, 40, seed=24)]
 
 
-@pytest.mark.parametrize("flags", FLAGS)
+# the selection with and without its approximate first look (the exact search alone is also what
+# queries with many equal scores fall back to)
+TOPK_FLAGS = FLAGS + [pytest.param(binding.FLAG_GATE_EXACT_SEARCH, id="exact_search")]
+
+
+@pytest.mark.parametrize("flags", TOPK_FLAGS)
 @pytest.mark.parametrize("w", SMALL + MANY_BLOCKS, ids=IDS + [w.name for w in MANY_BLOCKS])
 def test_topk_and_lists(oracle, w, flags):
     t = workloads.generate(w)
@@ -168,12 +173,15 @@ def test_topk_and_lists(oracle, w, flags):
     parity.check_lists(npi(off), npi(ql), npi(idx), g_off, g_ql, w.k)
 
 
-def test_topk_ties_go_to_the_lower_block():
+@pytest.mark.parametrize("topk", [5, 20])
+@pytest.mark.parametrize("flags", [0, binding.FLAG_GATE_EXACT_SEARCH], ids=["default", "exact_search"])
+def test_topk_ties_go_to_the_lower_block(flags, topk):
     """K = 0 makes every gate score equal: the kept blocks must be 0..min(k,c)-1.  With
-    three bit-identical blocks the kept copies must be a prefix of them."""
-    w = W("ties", 1, 2, 1024, 64, 32, 5, seed=40)
+    three bit-identical blocks the kept copies must be a prefix of them.  (top-k 5: kept blocks
+    as short lists; 20: as bit rows.)"""
+    w = W("ties", 1, 2, 1024, 64, 32, topk, seed=40)
     t = workloads.generate(w)
-    sh = shape_of(w)
+    sh = shape_of(w, flags)
     cent0 = torch.zeros((1, 2, w.n, w.d), dtype=torch.float32).cuda()
     idx, _ = moba.topk(sh, t["Q"].cuda(), cent0)
     got = npi(idx)
