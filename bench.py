@@ -25,16 +25,28 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3      # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch (fetch + write) of a kernel, from the rocprofv3 --pmc runs summarised
-# under profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a
-# plain copy kernel of known size).  Keyed by (benchmark configuration, kernel); not measured
-# for the others.
-MEASURED_TRAFFIC = {      # profiles/config3_hbm_traffic.txt: 2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE (KiB)
-    (3, "topk"): (2.0 * 64806.5 + 131348.2) * 1024,
-    (3, "forward"): (2.0 * 394538.2 + 67584.0) * 1024,
-    (3, "bwd_dq"): (2.0 * 493945.0 + 65536.0) * 1024,
-    (3, "bwd_dkdv"): (2.0 * 985129.5 + 131072.0) * 1024,
-}
+# HBM bytes per launch (fetch + write) of a kernel come from the rocprofv3 --pmc summaries kept
+# under profiles/ (FETCH_SIZE and WRITE_SIZE per dispatch, already scaled there by what the same
+# counters read for a plain copy of known size): profiles/config<N>_hbm_traffic.txt, one row per
+# kernel, last column = bytes per launch.  Not measured -> None.
+PROFILED_KERNEL = {"topk": "topk_mfma_kernel", "forward": ("forward_mfma_kernel", "fwd_km_kernel"),
+                   "bwd_dq": ("dq_mfma_kernel", "dq_km_kernel"), "bwd_dkdv": "dkdv_mfma_kernel"}
+
+
+def measured_traffic(config, kernel):
+    path = os.path.join(ROOT, "profiles", "config%d_hbm_traffic.txt" % config)
+    names = PROFILED_KERNEL.get(kernel)
+    if names is None or not os.path.exists(path):
+        return None
+    names = (names,) if isinstance(names, str) else names
+    for line in open(path):
+        f = line.split()
+        if len(f) == 4 and f[0] in names:
+            try:
+                return float(f[3])
+            except ValueError:
+                pass
+    return None
 
 
 def parse():
@@ -74,6 +86,10 @@ def parse():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB device to device once (a kernel of "
                          "known HBM traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--microbench", action="store_true",
+                    help="also run the library's two ceiling measurements once (a plain 1 GiB copy kernel, "
+                         "a register-only bf16 MFMA loop) and report the fractions of those measured "
+                         "ceilings next to the fractions of the published peaks")
     ap.add_argument("--cpu-max-slices", type=int, default=0,
                     help="cap on the (batch, head) slices of the CPU-baseline sample")
     return ap.parse_args()
@@ -124,7 +140,7 @@ def cpu_baseline(w, t, target_seconds=15.0, max_slices=0):
     flops = (4 + (10 if w.backward else 0)) * w.d * pairs
     return {
         "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
-        "seconds": dt,
+        "seconds": dt, "build": orc.BUILD_COMMAND,
         "sample": "%d of %d (batch, head) slices, whole chain (%scentroids, gate top-k, lists, "
                   "forward%s); %d attended pairs" % (
                       ns, w.bh, "key conv, " if w.conv_width else "",
@@ -331,7 +347,22 @@ def main():
             if work[kname][0] == "flop" and kms > 0:
                 tf = work[kname][1] / (kms * 1e-3) / 1e12
                 kernel_frac[kname] = {"tflops": tf, "frac_of_mfma_peak": tf / PEAK_BF16_TFLOPS}
-    roofline["traffic"] = MEASURED_TRAFFIC.get((a.config, dom)) if not a.reference_kernels else None
+    # the backward as the metric counts it: 10d flop per attended pair over both of its kernels (the
+    # per-kernel figures above count what each kernel executes: S and dP are computed in both)
+    if mfma and "bwd_dq" in timed and "bwd_dkdv" in timed:
+        for kname in ("bwd_dq", "bwd_dkdv"):
+            kernel_frac[kname]["counts"] = "executed flop of this kernel (%dd per attended pair)" % (
+                6 if kname == "bwd_dq" else 8)
+        bms = timed["bwd_dq"] + timed["bwd_dkdv"]
+        tf = bwd_flop / (bms * 1e-3) / 1e12
+        kernel_frac["backward"] = {"tflops": tf, "frac_of_mfma_peak": tf / PEAK_BF16_TFLOPS, "ms": bms,
+                                   "counts": "algorithmic flop of the backward (10d per attended pair) over "
+                                             "the dQ and the dK/dV kernel"}
+        ams = bms + timed.get("forward", 0.0)
+        tf = (fwd_flop + bwd_flop) / (ams * 1e-3) / 1e12
+        kernel_frac["attention_stage"] = {"tflops": tf, "frac_of_mfma_peak": tf / PEAK_BF16_TFLOPS, "ms": ams,
+                                          "counts": "algorithmic flop, forward + backward kernels"}
+    roofline["traffic"] = measured_traffic(a.config, dom) if not a.reference_kernels else None
     # HBM-bound stages, for the record: algorithmic bytes / measured time
     cent_bytes = w.bh * (w.N * w.d * es * (2 if w.conv_width else 1) + w.n * w.d * 4)
     topk_bytes = w.bh * (w.N * w.d * es + w.n * w.d * 4 + w.N * w.k * 4 + R * 4 + (w.n + 1) * 4)
@@ -379,6 +410,19 @@ def main():
         cb_bytes = 3 * w.bh * w.N * w.d * es
         out["key_conv_backward"] = {"ms": cb_ms, "GBs": cb_bytes / (cb_ms * 1e-3) / 1e9,
                                     "frac_of_hbm_peak": cb_bytes / (cb_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    if a.microbench:
+        mb = moba.microbench()
+        best = max(mb["mfma_tflops"].values())
+        out["microbench"] = {
+            "copy_GBs": mb["copy_GBs"], "copy_frac_of_hbm_peak": mb["copy_GBs"] / PEAK_HBM_GBS,
+            "mfma_loop_tflops_by_waves_per_simd": mb["mfma_tflops"],
+            "mfma_loop_frac_of_peak": best / PEAK_BF16_TFLOPS,
+            "roofline_frac_of_measured": (roofline["achieved"] / best if roofline["bound"] == "mfma"
+                                          else roofline["achieved"] / mb["copy_GBs"] if roofline["bound"] == "hbm"
+                                          else None),
+            "attention_kernels_frac_of_measured_mfma": {k: v["tflops"] / best for k, v in kernel_frac.items()},
+            "hbm_stages_frac_of_measured_copy": {k: v / mb["copy_GBs"] for k, v in hbm.items() if k != "peak_GBs"},
+        }
     if a.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read, 1 GiB written
         dst = torch.empty_like(src)

@@ -263,6 +263,20 @@ enum {
 int moba_profile_begin(void);
 int moba_profile_end(float* ms, int32_t* calls);
 
+/*
+ * Measured ceilings for benchmarks (no part of the method).  Both calls time their own kernels with
+ * a pair of HIP events on `stream` and wait for them.
+ * moba_microbench_copy: a plain grid-stride copy of `bytes` (a multiple of 16) from src to dst
+ *   (device buffers, not overlapping), `reps` launches after one warm-up; *ms = time per launch, so
+ *   the HBM rate is 2 * bytes / *ms.
+ * moba_microbench_mfma: a register-only loop of v_mfma_f32_16x16x32_bf16 (eight independent chains
+ *   per wave, `iters` rounds) on waves_per_simd (1..8) waves per SIMD of every compute unit; `sink`
+ *   is a device buffer of at least 1 KiB that is never written in practice; *ms = launch time,
+ *   *flop = floating-point operations of the launch.
+ */
+int moba_microbench_copy(void* dst, const void* src, size_t bytes, int reps, float* ms, void* stream);
+int moba_microbench_mfma(int waves_per_simd, int iters, void* sink, float* ms, double* flop, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

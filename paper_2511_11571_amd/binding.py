@@ -85,7 +85,7 @@ def lib():
                      "moba_topk_static", "moba_build_lists", "moba_forward", "moba_backward", "moba_backward_parts",
                      "moba_decode_forward",
                      "moba_profile_begin", "moba_profile_end", "moba_key_conv_backward",
-                     "moba_key_conv_backward_workspace"):
+                     "moba_key_conv_backward_workspace", "moba_microbench_copy", "moba_microbench_mfma"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -278,3 +278,20 @@ def profile_end():
     calls = (ctypes.c_int32 * len(PROFILE_KERNELS))()
     _check(lib().moba_profile_end(ms, calls), "moba_profile_end")
     return {name: (float(ms[i]), int(calls[i])) for i, name in enumerate(PROFILE_KERNELS)}
+
+
+def microbench(copy_bytes=1 << 30, mfma_iters=20000):
+    """The library's two ceiling measurements: -> {"copy_GBs": ..., "mfma_tflops": {waves per SIMD: ...}}."""
+    src = torch.ones(copy_bytes // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    ms = ctypes.c_float(0)
+    _check(lib().moba_microbench_copy(_p(dst), _p(src), ctypes.c_size_t(copy_bytes), ctypes.c_int(5),
+                                      ctypes.byref(ms), _stream()), "moba_microbench_copy")
+    out = {"copy_bytes": copy_bytes, "copy_ms": ms.value, "copy_GBs": 2.0 * copy_bytes / (ms.value * 1e-3) / 1e9,
+           "mfma_tflops": {}}
+    flop = ctypes.c_double(0)
+    for wps in (1, 2, 4, 8):
+        _check(lib().moba_microbench_mfma(ctypes.c_int(wps), ctypes.c_int(mfma_iters), _p(dst), ctypes.byref(ms),
+                                          ctypes.byref(flop), _stream()), "moba_microbench_mfma")
+        out["mfma_tflops"][wps] = flop.value / (ms.value * 1e-3) / 1e12
+    return out

@@ -14,8 +14,8 @@
 //   pass 2  the same walk again: p = exp(s - m) <= 1, so sum_u p_u <= (number of keys of the
 //           row) and, with V pre-scaled per channel to |v| <= 1, |sum_u p_u v_u| has the same
 //           bound; both sums are accumulated as integers scaled by 2^F, F chosen from that
-//           bound (each 32-key partial of P V is cut toward zero, a relative shrink of ~1e-5,
-//           two orders below the bf16 output's resolution; the row sums l round to nearest).
+//           bound (each 32-key partial of P V and of the row sum rounds to nearest: unbiased,
+//           2^-(F+1) per add at most; F >= 17, see kTileForwardMaxKeys).
 //           Integer adds commute exactly: the result does not depend on the order in which
 //           waves arrive, so the output is bit-reproducible.
 // Which rows go with which key block is a set of compact row lists in LDS (one byte per
@@ -238,7 +238,8 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
     const uint32_t qlane = 16u * g;
 
     // Fixed-point scale: a row attends at most nkeys keys, so sum p <= nkeys < 2^(31-F).
-    const int nkeys = min(t0 + rows_here, (k + 1) * B);
+    // (the library admits at most kTileForwardMaxKeys keys per query here: F >= 17)
+    const int nkeys = (int)min((int64_t)(t0 + rows_here), (int64_t)(k + 1) * B);
     const float Fbits = (float)(30 - (32 - __clz(nkeys)));
 
     // 0. Q tile -> LDS; clear the accumulators
@@ -291,7 +292,7 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
         for (int mt = 0; mt < C::MT; ++mt) {
             const f32x4_t o = mfma16(va[mt], pb, f32x4_t{0.f, 0.f, 0.f, 0.f});
 #pragma unroll
-            for (int i = 0; i < 4; ++i) oi[mt][i] = (int)o[i];      // toward zero: see header
+            for (int i = 0; i < 4; ++i) oi[mt][i] = __float2int_rn(o[i]);
         }
         if (valid) {
             atomicAdd(&lsum[row], __float2int_rn(lp));

@@ -251,6 +251,21 @@ inline bool mfma_path(const Dims& s)
     return s.dtype == MOBA_BF16 && s.B % 32 == 0 && !(s.flags & MOBA_FLAG_REFERENCE_KERNELS);
 }
 
+// The query-tile forward accumulates the row sums and P V as 32-bit fixed point with
+// F = 30 - bitlen(keys a query can attend) fraction bits, eight keys of a row per add: a partial sum
+// below 2^-(F+1) is lost, so a row with one dominant logit beside very many tiny ones can lose up to
+// keys * 2^-(F+4) of its denominator (the sum is biased: every term is positive).  With at most
+// 4096 keys per query F is at least 17 and that loss at most 0.2 % in the worst case (16384 keys
+// would allow 1.6 %, which shows in the output); longer rows go to the key-major or the plain
+// kernels, which keep their sums in floating point.
+constexpr int64_t kTileForwardMaxKeys = 4096;
+inline int64_t keys_per_query(const Dims& s)
+{
+    const int64_t kept = (int64_t)(s.k + 1) * s.B;
+    return kept < s.N ? kept : s.N;
+}
+inline bool tile_forward_ok(const Dims& s) { return keys_per_query(s) <= kTileForwardMaxKeys; }
+
 // shapes the key-major kernels cover: key blocks of one part or of whole parts
 inline bool key_major_shape(const Dims& s)
 {
@@ -272,6 +287,7 @@ inline bool key_major_path(const Dims& s)
 {
     if (!key_major_shape(s) || (s.flags & MOBA_FLAG_QUERY_TILES)) return false;
     if (s.flags & MOBA_FLAG_KEY_MAJOR) return true;
+    if (!tile_forward_ok(s)) return true;
     if (s.k <= 0) return false;
     const bool d64 = s.D == 64;
     const double T = d64 ? 256.0 : 128.0;

@@ -84,7 +84,8 @@ void* topk_terms(const Dims& d, void* ws) { return static_cast<char*>(ws) + chun
 size_t fwd_ws_bytes(const Dims& d)
 {
     if (!mfma_path(d)) return 256;
-    return align256(key_major_path(d) ? forward_km_ws_bytes(d) : forward_mfma_ws_bytes(d));
+    if (key_major_path(d)) return align256(forward_km_ws_bytes(d));
+    return tile_forward_ok(d) ? align256(forward_mfma_ws_bytes(d)) : 256;    // else: the plain kernel
 }
 // backward: D first in every layout; on the MFMA path the per-query pairs (lse log2 e, -D) of
 // the gathering kernels follow the layout, and with shared key/value heads the per-query-head sums
@@ -325,7 +326,7 @@ int moba_forward(const moba_shape* shape, const void* Q, const void* K_eff, cons
     if (mfma_path(d) && key_major_path(d))
         return hip_status(launch_forward_km(d, Q, K_eff, V, ws, topk_idx, blk_off, blk_q, O, lse,
                                             (hipStream_t)stream));
-    if (mfma_path(d))
+    if (mfma_path(d) && tile_forward_ok(d))
         return hip_status(launch_forward_mfma(d, Q, K_eff, V, ws, topk_idx, blk_off, blk_q, O, lse,
                                               (hipStream_t)stream));
     return hip_status(

@@ -44,3 +44,23 @@ def dense_backward(Q, K, V, mask, scale, dO):
     dQ = scale * dS @ K
     dK = scale * dS.T @ Q
     return dQ, dK, dV
+
+
+def ragged_block_mask(Q, K, B, k):
+    """The same for a sequence whose length need not be a multiple of B (paper Appendix C.1 cuts
+    N keys into ceil(N / B) blocks, the last one shorter): candidates of query t are the complete
+    blocks before its own, whose centroids are plain means; its own block, complete or not, is
+    attended up to t."""
+    N, d = Q.shape
+    nfull = N // B
+    cent = K[:nfull * B].reshape(nfull, B, d).mean(axis=1).astype(np.float32).astype(np.float64)
+    mask = np.zeros((N, N), dtype=bool)
+    chosen = []
+    for t in range(N):
+        own = t // B
+        keep = sorted(range(own), key=lambda j: (-float(Q[t] @ cent[j]), j))[:k] if k > 0 else []
+        chosen.append(set(keep))
+        for j in keep:
+            mask[t, j * B:(j + 1) * B] = True
+        mask[t, own * B:t + 1] = True
+    return mask, chosen

@@ -73,8 +73,11 @@ def test_routes_and_workspace(lib):
     (dict(heads=16, seqlen=8192, block=128, topk=8), True),                  # few kept blocks of many keys
     (dict(batch=2, heads=16, seqlen=524288, block=128, topk=8), True),       # the long end of the latency sweep
     (dict(heads=16, seqlen=131072, head_dim=128, block=64, topk=32, conv_width=4), True),
-    (dict(heads=16, seqlen=16384, block=128, topk=64), False),               # dense routing: tiles
+    (dict(heads=16, seqlen=16384, block=64, topk=60), False),                # dense routing: tiles
     (dict(heads=16, seqlen=8192, block=128, topk=0), False),                 # own block only
+    # more than 4096 keys per query: too many for the fixed-point accumulators of the query tiles
+    (dict(heads=2, seqlen=32768, block=32, topk=64), False),                 # 2080 keys: tiles
+    (dict(heads=2, seqlen=32768, block=128, topk=64), True),                 # 8320 keys: key blocks
 ])
 def test_default_cut_of_the_attention(kw, key_major):
     """With neither flag the library sizes (and runs) the forward and backward for the cut it

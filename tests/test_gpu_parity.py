@@ -466,6 +466,38 @@ def test_logit_far_above_the_own_block(oracle, flags):
         assert parity.rel_l2(np64(a), b) < parity.GRAD_TOL[w.dtype]
 
 
+@pytest.mark.parametrize("N,flags", [(4096, 0), (4096, binding.FLAG_QUERY_TILES), (16384, 0),
+                                     (16384, binding.FLAG_QUERY_TILES), (32768, 0)],
+                         ids=["4K_default", "4K_tiles", "16K_default", "16K_tiles", "32K_default"])
+def test_dense_rows_with_a_dominant_logit(oracle, N, flags):
+    """Full causal attention (every past block kept) over long rows in which one key's logit
+    stands ~14 above thousands of others: the denominators of such rows are made of one 1 and very
+    many tiny terms, which fixed-point sums with too few fraction bits would drop.  The query-tile
+    forward takes at most 4096 keys per query; these rows must go to a kernel that sums in floating
+    point whatever the flags say.  Sampled rows against the oracle."""
+    B = 128
+    w = W("dense_dominant", 1, 1, N, 64, B, N // B, seed=77)
+    t = workloads.generate(w)
+    rows = np.array([N - 1, N - 2, N - 200, N // 2 + 3, 3 * N // 4, 129, 5], dtype=np.int64)
+    for r in rows[:3]:                       # dominant key far in the past of these queries
+        q = t["Q"][0, 0, r].float()
+        t["K"][0, 0, 777 + int(r) % 50] = (q * (14.0 / (w.scale * float(q @ q)))).to(torch.bfloat16)
+    Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
+    n = N // B
+    idx = np.full((1, N, n), -1, np.int32)   # dense routing: all past blocks, ascending
+    for c in range(n):
+        idx[0, c * B:(c + 1) * B, :c] = np.arange(c, dtype=np.int32)
+    sh = shape_of(w, flags)
+    d = dev(t)
+    gidx = torch.from_numpy(idx).reshape(1, 1, N, n).cuda()
+    lists = moba.build_lists(sh, gidx)
+    O, lse = moba.forward(sh, d["Q"], d["K"], d["V"], gidx, lists)
+    rO, rlse = oracle.attn_fwd(Q, K, V, idx, B, w.scale, rows=rows)
+    got_O, got_lse = np64(O)[0][rows], lse.double().cpu().numpy().reshape(-1)[rows]
+    assert parity.max_abs(got_O, rO) < parity.O_TOL[w.dtype]
+    assert parity.max_abs(got_lse, rlse) < parity.LSE_TOL[w.dtype]
+
+
 def test_kernel_timing_session():
     """moba_profile_begin/_end: one event pair per launch of a main kernel, results unchanged."""
     w = W("timing", 1, 2, 2048, 64, 32, 8, backward=True, seed=72)

@@ -23,6 +23,36 @@ def _sets(idx_row):
     return set(int(x) for x in idx_row if x >= 0)
 
 
+# ---------------------------------------------------------------- ragged sequences by zero padding
+
+@pytest.mark.parametrize("N,B,k", [(37, 8, 2), (50, 4, 3), (23, 8, 5), (9, 16, 2), (64, 8, 0)])
+def test_zero_padded_sequence_equals_the_ragged_definition(oracle, N, B, k):
+    """The reading used for a ragged last block (training-shaped calls with caller-side padding,
+    the decode call, packed variable-length batches): run the operator on the sequence padded with
+    zero rows to the next multiple of B and keep the real rows.  A query never sees a later key,
+    the padded block is never a routing candidate of a real query, and zero dO rows add nothing to
+    dK and dV -- so the result must equal a dense evaluation of the ragged sequence itself."""
+    d = 8
+    Np = -(-N // B) * B
+    r = RNG(4000 + N)
+    Q, K, V, dO = (r.standard_normal((1, N, d)) for _ in range(4))
+    pad = lambda x: np.concatenate([x, np.zeros((1, Np - N, d))], axis=1)
+    scale = 1.0 / np.sqrt(d)
+    res = oracle.moba_forward(pad(Q), pad(K), pad(V), B, k, scale)
+    mask, chosen = brute.ragged_block_mask(Q[0], K[0], B, k)
+    for t in range(N):
+        assert _sets(res["idx"][0, t]) == chosen[t], t
+    O, lse, _ = brute.dense_attention(Q[0], K[0], V[0], mask, scale)
+    np.testing.assert_allclose(res["O"][0, :N], O, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(res["lse"][0, :N], lse, rtol=0, atol=1e-12)
+    gQ, gK, gV = oracle.attn_bwd(pad(Q), pad(K), pad(V), res["idx"], pad(dO), B, scale)
+    rQ, rK, rV = brute.dense_backward(Q[0], K[0], V[0], mask, scale, dO[0])
+    np.testing.assert_allclose(gQ[0, :N], rQ, rtol=0, atol=1e-11)
+    np.testing.assert_allclose(gK[0, :N], rK, rtol=0, atol=1e-11)
+    np.testing.assert_allclose(gV[0, :N], rV, rtol=0, atol=1e-11)
+    assert not gK[0, N:].any() and not gV[0, N:].any()      # the padded rows receive nothing
+
+
 # ---------------------------------------------------------------- brute force
 
 @pytest.mark.parametrize("B,d", [(1, 4), (2, 4), (4, 8), (8, 8)])
