@@ -160,6 +160,45 @@ int moba_topk_static(const moba_shape* shape, const void* Q, const float* centro
                      int32_t* topk_idx, int32_t* blk_off, int32_t* blk_q, void* stream);
 
 /*
+ * Packed variable-length batches (Appendix C.1: a sequence of N keys has ceil(N / B) blocks, the last
+ * one shorter).  The sequences of a batch lie one after the other along the token axis,
+ * [1, heads, T, d] with sequence i in rows seq_offsets[i] .. seq_offsets[i+1]; each is the operator
+ * on its own (blocks count from its first token, a query's candidates are the complete blocks before
+ * its own block in its own sequence).  The kernels work on a PADDED layout in which every sequence
+ * is followed by zero rows up to the next multiple of B and the whole is one sequence of T' tokens
+ * (pad_offsets[i] = start of sequence i there):
+ *   moba_varlen_layout       HOST ONLY: pad_offsets [num_seqs+1] and T' from seq_offsets
+ *                            [num_seqs+1] (both host arrays; seq_offsets[0] = 0, ascending)
+ *   moba_varlen_pad / _unpad [slices, T, row] <-> [slices, T', row] for rows of row_bytes bytes (a
+ *                            multiple of 4: Q, K, V, O, dO, gradients, lse); padding rows are
+ *                            written as zeros and dropped on the way back.  seq_offsets and
+ *                            pad_offsets are DEVICE arrays here.  Source and destination differ.
+ *   moba_varlen_block_first  block_first [T' / B] (device): first block of the sequence each block
+ *                            of the padded layout belongs to
+ *   moba_topk_varlen         moba_topk on the padded layout (shape.batch = 1, shape.seqlen = T'),
+ *                            the candidates of a query in block c being blocks
+ *                            block_first[c] .. c - 1.  topk_idx holds block numbers of the padded
+ *                            layout.  blk_q is sized for R of that shape (moba_routes_per_slice),
+ *                            an upper bound; the lists are blk_off[0] .. blk_off[T' / B].
+ * moba_centroids, moba_forward and moba_backward run unchanged on the padded tensors with the
+ * routing of moba_topk_varlen: no real query keeps a block of another sequence or sees a padding row,
+ * and padding rows of dO are zero.
+ */
+int moba_varlen_layout(int32_t num_seqs, const int32_t* seq_offsets, int32_t block, int32_t* pad_offsets,
+                       int32_t* padded_tokens);
+int moba_varlen_pad(int32_t num_seqs, const int32_t* seq_offsets, const int32_t* pad_offsets, int32_t slices,
+                    int32_t tokens, int32_t padded_tokens, int32_t row_bytes, const void* X, void* X_padded,
+                    void* stream);
+int moba_varlen_unpad(int32_t num_seqs, const int32_t* seq_offsets, const int32_t* pad_offsets, int32_t slices,
+                      int32_t tokens, int32_t padded_tokens, int32_t row_bytes, const void* X_padded, void* X,
+                      void* stream);
+int moba_varlen_block_first(int32_t num_seqs, const int32_t* pad_offsets, int32_t block, int32_t padded_tokens,
+                            int32_t* block_first, void* stream);
+int moba_topk_varlen(const moba_shape* shape, const void* Q, const float* centroids,
+                     const int32_t* block_first, int32_t* topk_idx, int32_t* blk_off, int32_t* blk_q,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
  * The list-building half of moba_topk alone (Appendix C.1, varlen reformatting), for a
  * routing supplied by the caller.  topk_idx rows may list their blocks in any order;
  * entries must be -1 or a past block of the query, without repeats, and every query of

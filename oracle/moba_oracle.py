@@ -282,3 +282,59 @@ def moba_forward(Q, K, V, B, k, scale, conv_w=None, heads=1, round_mode=ROUND_NO
     idx, kth = topk(Q, C, B, k)
     O, lse = attn_fwd(Q, Kp, V, idx, B, scale)
     return dict(K_eff=Kp, centroids=C, idx=idx, kth=kth, O=O, lse=lse)
+
+
+def _pad_seq(X, lo, hi, B):
+    """Rows lo..hi of X [bh, T, d] followed by zero rows up to the next multiple of B."""
+    L = hi - lo
+    Lp = -(-L // B) * B
+    out = np.zeros((X.shape[0], Lp) + X.shape[2:], dtype=np.float64)
+    out[:, :L] = X[:, lo:hi]
+    return out
+
+
+def moba_forward_varlen(Q, K, V, seq_offsets, B, k, scale):
+    """Packed variable-length batch (Appendix C.1: a sequence of N keys has ceil(N / B) blocks, the
+    last one shorter).  Q, K, V are [bh, T, d] with the sequences one after the other along T;
+    sequence i is rows seq_offsets[i] .. seq_offsets[i+1].  Every sequence is the operator of
+    Section 2 on its own: blocks count from the sequence's first token, candidates of a query are
+    the complete blocks before its own block in ITS sequence, the own block (complete or not) is
+    attended causally.  Written as a loop over the sequences, each padded with zero rows to a
+    multiple of B (tests pin that reading against a dense evaluation of the ragged sequence).
+    Returns O [bh, T, d], lse [bh, T] and idx [bh, T, k]: block numbers inside the query's
+    sequence, -1 padded."""
+    Q, K, V = (np.asarray(x, dtype=np.float64) for x in (Q, K, V))
+    bh, T, d = Q.shape
+    O = np.zeros((bh, T, d))
+    lse = np.zeros((bh, T))
+    idx = np.full((bh, T, k), -1, np.int32)
+    for lo, hi in zip(seq_offsets[:-1], seq_offsets[1:]):
+        if hi == lo:
+            continue
+        r = moba_forward(_pad_seq(Q, lo, hi, B), _pad_seq(K, lo, hi, B), _pad_seq(V, lo, hi, B), B, k, scale)
+        O[:, lo:hi], lse[:, lo:hi], idx[:, lo:hi] = r["O"][:, :hi - lo], r["lse"][:, :hi - lo], r["idx"][:, :hi - lo]
+    return dict(O=O, lse=lse, idx=idx)
+
+
+def attn_varlen(Q, K, V, idx, dO, seq_offsets, B, scale):
+    """Forward and backward of a packed variable-length batch at a GIVEN routing (idx as returned by
+    moba_forward_varlen: block numbers inside each query's sequence).  -> O, lse, dQ, dK, dV."""
+    Q, K, V, dO = (np.asarray(x, dtype=np.float64) for x in (Q, K, V, dO))
+    idx = np.asarray(idx, dtype=np.int32)
+    bh, T, d = Q.shape
+    O, dQ, dK, dV = (np.zeros((bh, T, d)) for _ in range(4))
+    lse = np.zeros((bh, T))
+    for lo, hi in zip(seq_offsets[:-1], seq_offsets[1:]):
+        L = hi - lo
+        if L == 0:
+            continue
+        q, kk, v, g = (_pad_seq(X, lo, hi, B) for X in (Q, K, V, dO))
+        ix = np.full((bh, q.shape[1], idx.shape[2]), -1, np.int32)
+        ix[:, :L] = idx[:, lo:hi]
+        for t in range(L, q.shape[1]):             # padded queries: any valid routing (they are dropped)
+            ix[:, t, :min(idx.shape[2], t // B)] = np.arange(min(idx.shape[2], t // B))
+        o, l = attn_fwd(q, kk, v, ix, B, scale)
+        gq, gk, gv = attn_bwd(q, kk, v, ix, g, B, scale)
+        O[:, lo:hi], lse[:, lo:hi] = o[:, :L], l[:, :L]
+        dQ[:, lo:hi], dK[:, lo:hi], dV[:, lo:hi] = gq[:, :L], gk[:, :L], gv[:, :L]
+    return O, lse, dQ, dK, dV

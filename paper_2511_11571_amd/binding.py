@@ -82,7 +82,8 @@ def lib():
         L.moba_strerror.argtypes = [ctypes.c_int]
         L.moba_last_hip_error.restype = ctypes.c_int
         for name in ("moba_routes_per_slice", "moba_workspace_bytes", "moba_centroids", "moba_topk",
-                     "moba_topk_static", "moba_build_lists", "moba_forward", "moba_backward", "moba_backward_parts",
+                     "moba_topk_static", "moba_topk_varlen", "moba_varlen_layout", "moba_varlen_pad",
+                     "moba_varlen_unpad", "moba_varlen_block_first", "moba_build_lists", "moba_forward", "moba_backward", "moba_backward_parts",
                      "moba_decode_forward",
                      "moba_profile_begin", "moba_profile_end", "moba_key_conv_backward",
                      "moba_key_conv_backward_workspace", "moba_microbench_copy", "moba_microbench_mfma"):
@@ -187,6 +188,64 @@ def topk_static(shape: Shape, Q, cent, out=None):
         idx, (off, ql) = out
     _check(lib().moba_topk_static(ctypes.byref(shape.c()), _p(Q), _p(cent), _p(idx), _p(off), _p(ql),
                                   _stream()), "moba_topk_static")
+    return idx, (off, ql)
+
+
+class VarlenLayout:
+    """Padded layout of a packed variable-length batch (moba_varlen_layout): every sequence starts at
+    a multiple of the block.  seq_offsets: host sequence of num_seqs + 1 ascending token offsets."""
+
+    def __init__(self, seq_offsets, block, device="cuda"):
+        self.num_seqs = len(seq_offsets) - 1
+        self.block = block
+        self.tokens = int(seq_offsets[-1])
+        so = (ctypes.c_int32 * (self.num_seqs + 1))(*[int(x) for x in seq_offsets])
+        po = (ctypes.c_int32 * (self.num_seqs + 1))()
+        tp = ctypes.c_int32(0)
+        _check(lib().moba_varlen_layout(ctypes.c_int32(self.num_seqs), so, ctypes.c_int32(block), po,
+                                        ctypes.byref(tp)), "moba_varlen_layout")
+        self.padded_tokens = tp.value
+        self.seq_offsets_host = list(so)
+        self.pad_offsets_host = list(po)
+        self.seq_offsets = torch.tensor(self.seq_offsets_host, dtype=torch.int32, device=device)
+        self.pad_offsets = torch.tensor(self.pad_offsets_host, dtype=torch.int32, device=device)
+        self.block_first = torch.empty(max(self.padded_tokens // block, 1), dtype=torch.int32, device=device)
+        _check(lib().moba_varlen_block_first(ctypes.c_int32(self.num_seqs), _p(self.pad_offsets),
+                                             ctypes.c_int32(block), ctypes.c_int32(self.padded_tokens),
+                                             _p(self.block_first), _stream()), "moba_varlen_block_first")
+
+    def _copy(self, fn, name, X, out_rows):
+        assert X.is_contiguous() and X.dim() >= 3
+        lead, rows = X.shape[:2], X.shape[2]
+        row_bytes = X[0, 0, 0].numel() * X.element_size() if X.dim() > 3 else X.element_size()
+        out = torch.empty(lead + (out_rows,) + X.shape[3:], dtype=X.dtype, device=X.device)
+        _check(fn(ctypes.c_int32(self.num_seqs), _p(self.seq_offsets), _p(self.pad_offsets),
+                  ctypes.c_int32(lead[0] * lead[1]), ctypes.c_int32(self.tokens),
+                  ctypes.c_int32(self.padded_tokens), ctypes.c_int32(row_bytes), _p(X), _p(out), _stream()), name)
+        return out
+
+    def pad(self, X):
+        """[1, heads, T, ...] -> [1, heads, T', ...], zero rows after every sequence."""
+        assert X.shape[2] == self.tokens
+        return self._copy(lib().moba_varlen_pad, "moba_varlen_pad", X, self.padded_tokens)
+
+    def unpad(self, Xp):
+        """[1, heads, T', ...] -> [1, heads, T, ...]."""
+        assert Xp.shape[2] == self.padded_tokens
+        return self._copy(lib().moba_varlen_unpad, "moba_varlen_unpad", Xp, self.tokens)
+
+
+def topk_varlen(shape: Shape, layout: VarlenLayout, Q, cent, ws=None):
+    """moba_topk_varlen on the padded layout (shape.seqlen = layout.padded_tokens, batch 1)."""
+    assert Q.is_contiguous() and cent.is_contiguous() and shape.seqlen == layout.padded_tokens
+    idx = torch.empty((shape.batch, shape.heads, shape.seqlen, shape.topk), dtype=torch.int32,
+                      device=Q.device)
+    off, ql = _list_buffers(shape, Q)
+    if ws is None:
+        ws = _ws(workspace_bytes(shape)[0], Q)
+    _check(lib().moba_topk_varlen(ctypes.byref(shape.c()), _p(Q), _p(cent), _p(layout.block_first), _p(idx),
+                                  _p(off), _p(ql), _p(ws), ctypes.c_size_t(ws.numel()), _stream()),
+           "moba_topk_varlen")
     return idx, (off, ql)
 
 

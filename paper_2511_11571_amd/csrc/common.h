@@ -170,6 +170,10 @@ struct Dims {
     float scale;
     int64_t R;          // routes per slice
     int nchunk;         // ceil(N / kChunkQ)
+    // Packed variable-length batches: first block of the sequence each key block belongs to
+    // (device, [n]); the candidates of a query in block c are blocks blk_first[c] .. c - 1.
+    // nullptr: one sequence, candidates 0 .. c - 1.
+    const int32_t* blk_first = nullptr;
 };
 
 // the same shape as seen by kernels that walk key/value-shaped tensors only
@@ -199,6 +203,11 @@ hipError_t launch_decode(const Dims& s, int q_len, const void* Q, const void* K,
 hipError_t launch_conv_backward(const Dims& s, const void* K, const float* w, const void* G, void* dK,
                                 float* dw, void* ws, hipStream_t st);
 size_t conv_bwd_ws_bytes(const Dims& s);
+hipError_t launch_varlen_copy(bool pad, const int32_t* seq_off, const int32_t* pad_off, int num_seqs,
+                              int64_t slices, int tokens, int padded_tokens, int row_bytes, const void* src,
+                              void* dst, hipStream_t st);
+hipError_t launch_varlen_block_first(const int32_t* pad_off, int num_seqs, int B, int nblocks, int32_t* first,
+                                     hipStream_t st);
 hipError_t launch_topk_reference(const Dims& s, const void* Q, const float* cent, int32_t* idx,
                                  hipStream_t st);
 hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, int32_t* ql,

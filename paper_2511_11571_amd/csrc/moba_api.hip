@@ -277,12 +277,14 @@ int moba_build_lists(const moba_shape* shape, const int32_t* topk_idx, int32_t* 
     return hip_status(launch_build_lists(d, topk_idx, blk_off, blk_q, chunk_counts(d, ws), (hipStream_t)stream));
 }
 
-int moba_topk(const moba_shape* shape, const void* Q, const float* centroids, int32_t* topk_idx,
-              int32_t* blk_off, int32_t* blk_q, void* ws, size_t ws_bytes, void* stream)
+namespace {
+int topk_call(const moba_shape* shape, const void* Q, const float* centroids, const int32_t* block_first,
+              int32_t* topk_idx, int32_t* blk_off, int32_t* blk_q, void* ws, size_t ws_bytes, void* stream)
 {
     Dims d;
     const int st = make_dims(shape, d);
     if (st != MOBA_OK) return st;
+    d.blk_first = block_first;
     if (!Q || !centroids || !blk_off) return MOBA_EINVAL;
     if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
     if (d.R > 0 && !blk_q) return MOBA_EINVAL;
@@ -293,6 +295,79 @@ int moba_topk(const moba_shape* shape, const void* Q, const float* centroids, in
                        : launch_topk_reference(d, Q, centroids, topk_idx, (hipStream_t)stream);
     if (e != hipSuccess) return hip_status(e);
     return hip_status(launch_build_lists(d, topk_idx, blk_off, blk_q, chunk_counts(d, ws), (hipStream_t)stream));
+}
+}  // namespace
+
+int moba_topk(const moba_shape* shape, const void* Q, const float* centroids, int32_t* topk_idx,
+              int32_t* blk_off, int32_t* blk_q, void* ws, size_t ws_bytes, void* stream)
+{
+    return topk_call(shape, Q, centroids, nullptr, topk_idx, blk_off, blk_q, ws, ws_bytes, stream);
+}
+
+int moba_topk_varlen(const moba_shape* shape, const void* Q, const float* centroids,
+                     const int32_t* block_first, int32_t* topk_idx, int32_t* blk_off, int32_t* blk_q,
+                     void* ws, size_t ws_bytes, void* stream)
+{
+    if (!block_first) return MOBA_EINVAL;
+    if (shape && shape->batch != 1) return MOBA_EINVAL;          // the batch is folded into the sequences
+    return topk_call(shape, Q, centroids, block_first, topk_idx, blk_off, blk_q, ws, ws_bytes, stream);
+}
+
+int moba_varlen_layout(int32_t num_seqs, const int32_t* seq_offsets, int32_t block, int32_t* pad_offsets,
+                       int32_t* padded_tokens)
+{
+    if (num_seqs <= 0 || !seq_offsets || block <= 0 || !pad_offsets || !padded_tokens) return MOBA_EINVAL;
+    if (seq_offsets[0] != 0) return MOBA_EINVAL;
+    int64_t run = 0;
+    for (int i = 0; i < num_seqs; ++i) {
+        const int64_t len = (int64_t)seq_offsets[i + 1] - seq_offsets[i];
+        if (len < 0) return MOBA_EINVAL;
+        pad_offsets[i] = (int32_t)run;
+        run += (len + block - 1) / block * block;
+        if (run > kMaxSeqlen) return MOBA_EUNSUPPORTED;
+    }
+    pad_offsets[num_seqs] = (int32_t)run;
+    *padded_tokens = (int32_t)run;
+    return MOBA_OK;
+}
+
+namespace {
+int varlen_copy(bool pad, int32_t num_seqs, const int32_t* seq_offsets, const int32_t* pad_offsets,
+                int32_t slices, int32_t tokens, int32_t padded_tokens, int32_t row_bytes, const void* src,
+                void* dst, void* stream)
+{
+    if (num_seqs <= 0 || !seq_offsets || !pad_offsets || slices <= 0 || tokens < 0 || padded_tokens < tokens)
+        return MOBA_EINVAL;
+    if (row_bytes <= 0 || (row_bytes & 3) || !src || !dst || src == dst) return MOBA_EINVAL;
+    return hip_status(launch_varlen_copy(pad, seq_offsets, pad_offsets, num_seqs, slices, tokens, padded_tokens,
+                                         row_bytes, src, dst, (hipStream_t)stream));
+}
+}  // namespace
+
+int moba_varlen_pad(int32_t num_seqs, const int32_t* seq_offsets, const int32_t* pad_offsets, int32_t slices,
+                    int32_t tokens, int32_t padded_tokens, int32_t row_bytes, const void* X, void* X_padded,
+                    void* stream)
+{
+    return varlen_copy(true, num_seqs, seq_offsets, pad_offsets, slices, tokens, padded_tokens, row_bytes, X,
+                       X_padded, stream);
+}
+
+int moba_varlen_unpad(int32_t num_seqs, const int32_t* seq_offsets, const int32_t* pad_offsets, int32_t slices,
+                      int32_t tokens, int32_t padded_tokens, int32_t row_bytes, const void* X_padded, void* X,
+                      void* stream)
+{
+    return varlen_copy(false, num_seqs, seq_offsets, pad_offsets, slices, tokens, padded_tokens, row_bytes,
+                       X_padded, X, stream);
+}
+
+int moba_varlen_block_first(int32_t num_seqs, const int32_t* pad_offsets, int32_t block, int32_t padded_tokens,
+                            int32_t* block_first, void* stream)
+{
+    if (num_seqs <= 0 || !pad_offsets || block <= 0 || padded_tokens < 0 || padded_tokens % block != 0 ||
+        !block_first)
+        return MOBA_EINVAL;
+    return hip_status(launch_varlen_block_first(pad_offsets, num_seqs, block, padded_tokens / block, block_first,
+                                                (hipStream_t)stream));
 }
 
 int moba_topk_static(const moba_shape* shape, const void* Q, const float* centroids,

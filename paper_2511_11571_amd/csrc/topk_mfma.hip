@@ -169,7 +169,7 @@ __global__ __launch_bounds__(kTopkWaves * kWave) __attribute__((amdgpu_waves_per
 void topk_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ c3, int ntile_all,
     int32_t* __restrict__ idx, int N, int B, int n, int k, int strips_per_slice, int Wn, int G,
-    int exact_only)
+    int exact_only, const int32_t* __restrict__ blk_first)
 {
     extern __shared__ uint32_t smem[];
     constexpr int KS = D / 32;
@@ -182,8 +182,9 @@ void topk_mfma_kernel(
     uint32_t* st_sh = st_lo + 64;
     uint32_t* st_need = st_sh + 64;                // blocks still to find inside the current interval
     uint32_t* st_state = st_need + 64;
-    uint32_t* st_past = st_state + 64;
-    uint32_t* st_hi = st_past + 64;                // the current interval is [lo, hi): at most 64 bins of 2^sh keys
+    uint32_t* st_past = st_state + 64;             // candidates of the query: blocks first .. past - 1
+    uint32_t* st_first = st_past + 64;
+    uint32_t* st_hi = st_first + 64;                // the current interval is [lo, hi): at most 64 bins of 2^sh keys
     float* st_tlo = reinterpret_cast<float*>(st_hi + 64);   // marking thresholds, see kBand
     float* st_thi = st_tlo + 64;
     uint32_t* st_cnt = reinterpret_cast<uint32_t*>(st_thi + 64);   // marking: blocks met inside the band
@@ -229,8 +230,12 @@ void topk_mfma_kernel(
     int32_t* out = idx + ((int64_t)s * N + t0) * k;
 
     if (wave == 0) {   // lane = query: initial state
-        const int past = lane < rows_here ? (t0 + lane) / B : 0;
-        st_past[lane] = past;
+        // (packed variable-length batches: the blocks of a query's own sequence start at blk_first)
+        const int own = lane < rows_here ? (t0 + lane) / B : 0;
+        const int first = blk_first && lane < rows_here ? blk_first[own] : 0;
+        const int past = own - first;                          // number of candidates
+        st_past[lane] = own;
+        st_first[lane] = first;
         st_lo[lane] = 0u;
         st_sh[lane] = 26u;
         st_hi[lane] = 0xffffffffu;
@@ -248,6 +253,11 @@ void topk_mfma_kernel(
     for (int i = tid; i < sel_words; i += kTopkWaves * kWave) selm[i] = 0u;
     const int pmax = (t0 + rows_here - 1) / B;
     const int ntile = (pmax + 15) / 16;
+    // first candidate block of the strip's first and last query (the queries of a strip are
+    // consecutive, so these are the smallest and the largest)
+    const int fmin = blk_first ? blk_first[t0 / B] : 0;
+    const int fmax = blk_first ? blk_first[pmax] : 0;
+    const int tbeg = fmin / 16;
 
     Frag qb[4][KS];
 #pragma unroll
@@ -259,30 +269,28 @@ void topk_mfma_kernel(
         }
     __syncthreads();
 
-    // Interior tiles hold only blocks that are past blocks of every query of the strip; the
-    // tail tiles need the per-query causal test.  The waves of the strip take alternate tiles.
-    const int ntile_int = min(ntile, (t0 / B) / 16);
-    auto sweep = [&](int tlo, int thi, auto f) {
-        const int mid = min(max(ntile_int, tlo), thi);
-        sweep_tiles<D, 2>(c3s, tlo + wave, mid, kTopkWaves, qb, lane, g,
-                          [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::false_type()); });
-        // first tail tile of this wave: same parity as its interior tiles
-        const int tail0 = mid + ((wave - (mid - tlo)) & (kTopkWaves - 1));
-        sweep_tiles<D, 2>(c3s, tail0, thi, kTopkWaves, qb, lane, g,
-                          [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::true_type()); });
+    // Interior tiles hold only blocks that are candidates of every query of the strip; the tiles
+    // before and after them need the per-query test.  The waves of the strip take alternate tiles
+    // (every sm-th tile in a sampled sweep): tile t belongs to wave ((t - tbeg) / sm) mod waves.
+    const int ihi = min(ntile, (t0 / B) / 16);
+    const int ilo = min(ihi, max(tbeg, (fmax + 15) / 16));
+    auto sweep_any = [&](auto top, int tlo, int thi, int sm, auto f) {
+        constexpr int TOP = decltype(top)::value;
+        const int step = kTopkWaves * sm, base = tbeg + sm * wave;
+        auto segment = [&](int a, int b, auto checked) {
+            a = max(a, max(tlo, tbeg));
+            b = min(b, thi);
+            const int first = a <= base ? base : base + (a - base + step - 1) / step * step;
+            sweep_tiles<D, TOP>(c3s, first, b, step, qb, lane, g,
+                                [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, checked); });
+        };
+        segment(tbeg, ilo, std::true_type());
+        segment(ilo, ihi, std::false_type());
+        segment(ihi, ntile, std::true_type());
     };
-    // every sm-th tile only (tiles 0, sm, 2 sm, ..., alternating between the waves), scores from
-    // the hi term alone
-    auto sweep_sample = [&](int sm, auto f) {
-        const int step = kTopkWaves * sm;
-        const int mid = min(ntile_int, ntile);
-        sweep_tiles<D, 0>(c3s, sm * wave, mid, step, qb, lane, g,
-                          [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::false_type()); });
-        int tail0 = sm * wave;
-        if (tail0 < mid) tail0 += (mid - tail0 + step - 1) / step * step;
-        sweep_tiles<D, 0>(c3s, tail0, ntile, step, qb, lane, g,
-                          [&](int qt, const f32x4_t& sc, int j0) { f(qt, sc, j0, std::true_type()); });
-    };
+    auto sweep = [&](int tlo, int thi, auto f) { sweep_any(std::integral_constant<int, 2>(), tlo, thi, 1, f); };
+    // every sm-th tile only, scores from the hi term alone
+    auto sweep_sample = [&](int sm, auto f) { sweep_any(std::integral_constant<int, 0>(), 0, ntile, sm, f); };
 
     // ---- first look, on hi-term scores (a third of the operand loads and MFMAs; the selection
     // below does not depend on these being right).
@@ -290,19 +298,24 @@ void topk_mfma_kernel(
     // blocks when there are few tiles, over every sm-th tile otherwise.  The first window is
     // [max / 4, max] (from the smallest score when no score is positive), 64 bins, open at the
     // top (its last bin also takes whatever lies above).
-    const int sm = min(max(ntile / 8, 1), LISTS ? 8 : 4);
+    const int sm = min(max((ntile - tbeg) / 8, 1), LISTS ? 8 : 4);
     if (!exact_only && __syncthreads_or(st_state[lane] == kUndecided)) {
         for (int i = tid; i < 64; i += kTopkWaves * kWave) { hist[i * kHistStride] = 0u; hist[i * kHistStride + 1] = 0xffffffffu; }
-        uint32_t past4[4];
+        uint32_t first4[4], span4[4];
         float mx4[4], mn4[4];
 #pragma unroll
-        for (int qt = 0; qt < 4; ++qt) { past4[qt] = st_past[16 * qt + m16]; mx4[qt] = -INFINITY; mn4[qt] = INFINITY; }
+        for (int qt = 0; qt < 4; ++qt) {
+            first4[qt] = st_first[16 * qt + m16];
+            span4[qt] = st_past[16 * qt + m16] - first4[qt];
+            mx4[qt] = -INFINITY;
+            mn4[qt] = INFINITY;
+        }
         __syncthreads();
         sweep_sample(sm, [&](int qt, const f32x4_t& sc, int j0, auto tail) {
             if (decltype(tail)::value) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    if ((uint32_t)(j0 + i) < past4[qt]) { mx4[qt] = fmaxf(mx4[qt], sc[i]); mn4[qt] = fminf(mn4[qt], sc[i]); }
+                    if ((uint32_t)(j0 + i) - first4[qt] < span4[qt]) { mx4[qt] = fmaxf(mx4[qt], sc[i]); mn4[qt] = fminf(mn4[qt], sc[i]); }
             } else {                               // (NaN scores are ignored here as in the counts)
                 mx4[qt] = fmaxf(fmaxf(mx4[qt], sc[0]), fmaxf(sc[1], fmaxf(sc[2], sc[3])));
                 mn4[qt] = fminf(fminf(mn4[qt], sc[0]), fminf(sc[1], fminf(sc[2], sc[3])));
@@ -343,14 +356,15 @@ void topk_mfma_kernel(
         // without a window get bin -2
         constexpr float kMagic = 12582912.f;                   // 1.5 * 2^23
         constexpr int kMagicBits = 0x4B400000;
-        uint32_t past4[4];
+        uint32_t first4[4], span4[4];
         float inv4[4], off4[4];
         int cap4[4];
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) {
             const int q = 16 * qt + m16;
             const float w = st_state[q] == kUndecided ? st_w[q] : 0.f;
-            past4[qt] = st_past[q];
+            first4[qt] = st_first[q];
+            span4[qt] = st_past[q] - first4[qt];
             inv4[qt] = w > 0.f ? 1.f / w : 0.f;
             off4[qt] = (w > 0.f ? -st_a[q] / w : -1.f) - 0.5f;
             cap4[qt] = kMagicBits + (st_open[q] ? 63 : 64);    // open at the top: the last bin takes the rest
@@ -362,7 +376,7 @@ void topk_mfma_kernel(
             for (int i = 0; i < 4; ++i) {
                 const int bi = min(__float_as_int(fmaf(sc[i], inv4[qt], off4[qt]) + kMagic), cap4[qt]) - kMagicBits;
                 bool in = (uint32_t)bi < 64u;
-                if (decltype(tail)::value) in = in && (uint32_t)(j0 + i) < past4[qt];
+                if (decltype(tail)::value) in = in && (uint32_t)(j0 + i) - first4[qt] < span4[qt];
                 if (in) atomicAdd(&row[bi], 1u);
             }
         });
@@ -428,13 +442,14 @@ void topk_mfma_kernel(
         // The sign of score - threshold is shifted into a mask, one bit per score (two instructions
         // per score and threshold, none of them waiting for a compare); a threshold of +0 is taken
         // as -0 so that a score of -0 does not come out below it.
-        int past4[4];
+        int past4[4], first4[4];
         uint32_t on4[4];
         float tlo4[4], thi4[4];
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) {
             const int q = 16 * qt + m16;
             past4[qt] = (int)st_past[q];
+            first4[qt] = (int)st_first[q];
             const uint32_t st = st_state[q];
             on4[qt] = st != kUndecided && st != kDone ? 0xfu : 0u;
             const float lo = st_tlo[q], hi = st_thi[q];
@@ -452,7 +467,8 @@ void topk_mfma_kernel(
                 below_lo = __builtin_amdgcn_alignbit(below_lo, __float_as_uint(sc[i] - tlo4[qt]), 31);
             }
             uint32_t ok = on4[qt];
-            if (decltype(tail)::value) ok &= (1u << min(max(past4[qt] - j0, 0), 4)) - 1u;
+            if (decltype(tail)::value)                            // blocks first .. past - 1 only
+                ok &= ((1u << min(max(past4[qt] - j0, 0), 4)) - 1u) & ~((1u << min(max(first4[qt] - j0, 0), 4)) - 1u);
             const uint32_t bits = ~below_hi & ok;                 // score >= thi
             const uint32_t cand = below_hi & ~below_lo & ok;      // tlo <= score < thi
             if (__ballot(cand != 0u)) {
@@ -542,7 +558,7 @@ void topk_mfma_kernel(
         if (band) {
             const int met = (int)st_cnt[q];
             c = min(met, kCand);
-            want = (int)min((uint32_t)k, st_past[q]) - kept;
+            want = (int)min((uint32_t)k, st_past[q] - st_first[q]) - kept;
             fits = room && met <= kCand && want >= 0 && want <= c;
         }
         if (band && (fits || !retry)) {
@@ -571,7 +587,7 @@ void topk_mfma_kernel(
                 st_lo[q] = 0u;
                 st_sh[q] = 26u;
                 st_hi[q] = 0xffffffffu;
-                st_need[q] = min((uint32_t)k, st_past[q]);
+                st_need[q] = min((uint32_t)k, st_past[q] - st_first[q]);
                 st_state[q] = kUndecided;
             } else {
                 st_state[q] = kDone;
@@ -590,13 +606,15 @@ void topk_mfma_kernel(
     const bool leftovers = __syncthreads_or(st_state[lane] != kDone);
     while (__syncthreads_or(st_state[lane] == kUndecided)) {
         for (int i = tid; i < 64 * kHistStride; i += kTopkWaves * kWave) hist[i] = 0u;
-        uint32_t lo4[4], sh4[4], past4[4];
+        uint32_t lo4[4], sh4[4], first4[4], span4[4];
         float flo4[4], fhi4[4];
         bool act4[4];
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) {
             const int q = 16 * qt + m16;
-            lo4[qt] = st_lo[q]; sh4[qt] = st_sh[q]; past4[qt] = st_past[q];
+            lo4[qt] = st_lo[q]; sh4[qt] = st_sh[q];
+            first4[qt] = st_first[q];
+            span4[qt] = st_past[q] - first4[qt];
             act4[qt] = st_state[q] == kUndecided;
             flo4[qt] = key_score(lo4[qt], -INFINITY);
             const uint32_t hi = st_hi[q];
@@ -609,7 +627,7 @@ void topk_mfma_kernel(
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 bool in = sc[i] >= flo4[qt] && !(sc[i] >= fhi4[qt]);
-                if (decltype(tail)::value) in = in && (uint32_t)(j0 + i) < past4[qt];
+                if (decltype(tail)::value) in = in && (uint32_t)(j0 + i) - first4[qt] < span4[qt];
                 if (in) {
                     // (an interval open at the top: its last bin takes everything above as well)
                     const uint32_t bin = min((order_key(sc[i]) - lo4[qt]) >> sh4[qt], 63u);
@@ -676,13 +694,14 @@ void topk_mfma_kernel(
 
     if (leftovers) {
         bool strict4[4];
-        uint32_t past4[4];
+        uint32_t first4[4], span4[4];
         float thr4[4];
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) {
             const int q = 16 * qt + m16;
             strict4[qt] = st_state[q] == kKeepTies;
-            past4[qt] = st_past[q];
+            first4[qt] = st_first[q];
+            span4[qt] = st_past[q] - first4[qt];
             thr4[qt] = key_score(st_lo[q], -INFINITY);
         }
         mark();
@@ -697,7 +716,7 @@ void topk_mfma_kernel(
                     uint32_t bits = 0;
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        if ((uint32_t)(j0 + i) < past4[qt] && sc[i] == thr4[qt]) bits |= 1u << i;
+                        if ((uint32_t)(j0 + i) - first4[qt] < span4[qt] && sc[i] == thr4[qt]) bits |= 1u << i;
                     if (bits) atomicOr(&hist[(16 * qt + m16) * kHistStride + ((j0 - r0) >> 5)], bits << (j0 & 31));
                 });
                 __syncthreads();
@@ -799,7 +818,7 @@ static hipError_t topk_launch2(const Dims& s, const void* Q, const bf16_t* c3, i
     const int sps = (s.N + 63) / 64;
     const int64_t strips = (int64_t)sps * s.bh;
     const int Wn = ((s.n + 31) / 32) | 1;      // words per bit row, odd for the same reason
-    const size_t lds = sizeof(uint32_t) * (size_t)(64 * kHistStride + 17 * 64 +
+    const size_t lds = sizeof(uint32_t) * (size_t)(64 * kHistStride + 18 * 64 +
                                                    (LISTS ? 64 * kKeptList / 2 + 64 : 64 * Wn));
     hipError_t e = hipFuncSetAttribute((const void*)topk_mfma_kernel<D, LISTS>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -807,7 +826,7 @@ static hipError_t topk_launch2(const Dims& s, const void* Q, const bf16_t* c3, i
     ProfileScope timing(MOBA_PROFILE_TOPK, st);
     hipLaunchKernelGGL((topk_mfma_kernel<D, LISTS>), dim3((unsigned)strips), dim3(kTopkWaves * kWave), lds, st,
                        (const bf16_t*)Q, c3, (s.n + 15) / 16, idx, s.N, s.B, s.n, s.k, sps, Wn, s.G,
-                       (s.flags & MOBA_FLAG_GATE_EXACT_SEARCH) ? 1 : 0);
+                       (s.flags & MOBA_FLAG_GATE_EXACT_SEARCH) ? 1 : 0, s.blk_first);
     return hipGetLastError();
 }
 

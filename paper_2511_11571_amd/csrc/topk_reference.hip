@@ -13,7 +13,8 @@ constexpr int kTopkMaxBlocks = 4096;   // LDS row length per wave
 template <typename T, int D>
 __global__ __launch_bounds__(256) void topk_reference_kernel(
     const T* __restrict__ Q, const float* __restrict__ cent, int32_t* __restrict__ idx,
-    int N, int B, int n, int k, int64_t total_rows, int lds_row, int G)
+    int N, int B, int n, int k, int64_t total_rows, int lds_row, int G,
+    const int32_t* __restrict__ blk_first)
 {
     extern __shared__ uint32_t smem[];
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
@@ -23,18 +24,20 @@ __global__ __launch_bounds__(256) void topk_reference_kernel(
     if (row >= total_rows) return;
     const int64_t s = row / N;
     const int t = (int)(row % N);
+    // candidates: blocks first .. past - 1 (first > 0 in packed variable-length batches only)
     const int past = t / B;
+    const int first = blk_first ? blk_first[past] : 0;
     int32_t* out = idx + row * k;
 
-    if (past <= k) {                      // keep every past block
-        for (int c = lane; c < k; c += kWave) out[c] = c < past ? c : -1;
+    if (past - first <= k) {              // keep every candidate
+        for (int c = lane; c < k; c += kWave) out[c] = first + c < past ? first + c : -1;
         return;
     }
     for (int c = lane; c < D; c += kWave) qs[c] = to_f32<T>(Q[row * D + c]);
     __builtin_amdgcn_wave_barrier();
 
     const float* cs = cent + (s / G) * n * D;        // G query heads share the centroids
-    for (int j = lane; j < past; j += kWave) {
+    for (int j = first + lane; j < past; j += kWave) {
         const float4* cj = reinterpret_cast<const float4*>(cs + (int64_t)j * D);
         float acc = 0.f;
 #pragma unroll 4
@@ -53,15 +56,15 @@ __global__ __launch_bounds__(256) void topk_reference_kernel(
     for (int bit = 31; bit >= 0; --bit) {
         const uint32_t cand = thr | (1u << bit);
         int c = 0;
-        for (int j = lane; j < past; j += kWave) c += keys[j] >= cand;
+        for (int j = first + lane; j < past; j += kWave) c += keys[j] >= cand;
         if (wave_sum_i(c) >= k) thr = cand;
     }
     int g = 0;
-    for (int j = lane; j < past; j += kWave) g += keys[j] > thr;
+    for (int j = first + lane; j < past; j += kWave) g += keys[j] > thr;
     const int need = k - wave_sum_i(g);     // how many of the blocks equal to thr to keep
 
     int pos = 0, eq_seen = 0;
-    for (int j0 = 0; j0 < past; j0 += kWave) {
+    for (int j0 = first; j0 < past; j0 += kWave) {
         const int j = j0 + lane;
         const uint32_t key = j < past ? keys[j] : 0u;
         const bool eq = j < past && key == thr;
@@ -89,7 +92,7 @@ static hipError_t launch_t(const Dims& s, const void* Q, const float* cent, int3
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((topk_reference_kernel<T, D>), grid, block, lds, st, (const T*)Q, cent, idx,
-                       s.N, s.B, s.n, s.k, rows, lds_row, s.G);
+                       s.N, s.B, s.n, s.k, rows, lds_row, s.G, s.blk_first);
     return hipGetLastError();
 }
 

@@ -1,0 +1,88 @@
+// Packed variable-length batches (paper Appendix C.1: a sequence of N keys is cut into
+// ceil(N / B) blocks, the last one shorter; its index reformatting is "varlen" from the start).
+//
+// Several sequences lie one after the other along the token axis of [slices, T, row].  The
+// attention kernels want every key block to start at a multiple of B, so the batch is brought
+// into a padded layout first: every sequence is followed by zero rows up to the next multiple of
+// B and the whole is treated as one sequence of T' tokens.  A query never sees a later key, so a
+// real query never meets the zero rows of its own last block; the gate takes the candidates of a
+// query from its own sequence only (blk_first); zero dO rows add nothing to dK and dV.  Rows of
+// the padding carry no meaning and are dropped on the way back.
+#include "common.h"
+
+namespace moba {
+
+// largest i with offs[i] <= x (offs ascending, offs[0] = 0, x < offs[num])
+__device__ __forceinline__ int seq_of(const int32_t* __restrict__ offs, int num, int x)
+{
+    int lo = 0, hi = num;                   // answer in [lo, hi)
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (offs[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// PAD: Xp[s][p] <- X[s][row of token p] or zeros;  !PAD: X[s][r] <- Xp[s][padded place of r].
+// One thread per 4-byte word of a row of the destination.
+template <bool PAD>
+__global__ __launch_bounds__(256) void varlen_copy_kernel(
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ pad_off, int num_seqs, int tokens,
+    int padded_tokens, int row_words, const uint32_t* __restrict__ src, uint32_t* __restrict__ dst,
+    int64_t total_words)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total_words) return;
+    const int drows = PAD ? padded_tokens : tokens, srows = PAD ? tokens : padded_tokens;
+    const int wd = (int)(i % row_words);
+    const int64_t row = i / row_words;
+    const int r = (int)(row % drows);
+    const int64_t s = row / drows;
+    uint32_t v = 0u;
+    if (PAD) {
+        const int q = seq_of(pad_off, num_seqs, r);
+        const int t = r - pad_off[q];
+        if (t < seq_off[q + 1] - seq_off[q]) v = src[(s * srows + seq_off[q] + t) * row_words + wd];
+    } else {
+        const int q = seq_of(seq_off, num_seqs, r);
+        v = src[(s * srows + pad_off[q] + (r - seq_off[q])) * row_words + wd];
+    }
+    dst[i] = v;
+}
+
+__global__ __launch_bounds__(256) void varlen_block_first_kernel(const int32_t* __restrict__ pad_off,
+                                                                 int num_seqs, int B, int nblocks,
+                                                                 int32_t* __restrict__ first)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= nblocks) return;
+    first[c] = pad_off[seq_of(pad_off, num_seqs, c * B)] / B;
+}
+
+hipError_t launch_varlen_copy(bool pad, const int32_t* seq_off, const int32_t* pad_off, int num_seqs,
+                              int64_t slices, int tokens, int padded_tokens, int row_bytes, const void* src,
+                              void* dst, hipStream_t st)
+{
+    const int row_words = row_bytes / 4;
+    const int64_t total = slices * (pad ? padded_tokens : tokens) * row_words;
+    if (total == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    if (pad)
+        hipLaunchKernelGGL(varlen_copy_kernel<true>, dim3(grid), dim3(256), 0, st, seq_off, pad_off, num_seqs,
+                           tokens, padded_tokens, row_words, (const uint32_t*)src, (uint32_t*)dst, total);
+    else
+        hipLaunchKernelGGL(varlen_copy_kernel<false>, dim3(grid), dim3(256), 0, st, seq_off, pad_off, num_seqs,
+                           tokens, padded_tokens, row_words, (const uint32_t*)src, (uint32_t*)dst, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_varlen_block_first(const int32_t* pad_off, int num_seqs, int B, int nblocks, int32_t* first,
+                                     hipStream_t st)
+{
+    if (nblocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(varlen_block_first_kernel, dim3((nblocks + 255) / 256), dim3(256), 0, st, pad_off,
+                       num_seqs, B, nblocks, first);
+    return hipGetLastError();
+}
+
+}  // namespace moba

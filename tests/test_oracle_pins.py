@@ -53,6 +53,35 @@ def test_zero_padded_sequence_equals_the_ragged_definition(oracle, N, B, k):
     assert not gK[0, N:].any() and not gV[0, N:].any()      # the padded rows receive nothing
 
 
+def test_packed_variable_length_batch_is_each_sequence_on_its_own(oracle):
+    """moba_forward_varlen / attn_varlen against a dense evaluation of every ragged sequence by
+    itself (lengths below, equal to and above multiples of B, one shorter than a block, one empty)."""
+    B, k, d, bh = 4, 2, 8, 2
+    lens = [13, 4, 0, 3, 22, 8]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    T = int(offs[-1])
+    r = RNG(515)
+    Q, K, V, dO = (r.standard_normal((bh, T, d)) for _ in range(4))
+    scale = 1.0 / np.sqrt(d)
+    res = oracle.moba_forward_varlen(Q, K, V, offs, B, k, scale)
+    O2, lse2, gQ, gK, gV = oracle.attn_varlen(Q, K, V, res["idx"], dO, offs, B, scale)
+    np.testing.assert_allclose(O2, res["O"], rtol=0, atol=1e-13)
+    for s in range(bh):
+        for lo, hi in zip(offs[:-1], offs[1:]):
+            if hi == lo:
+                continue
+            mask, chosen = brute.ragged_block_mask(Q[s, lo:hi], K[s, lo:hi], B, k)
+            for t in range(hi - lo):
+                assert _sets(res["idx"][s, lo + t]) == chosen[t], (s, lo, t)
+            O, lse, _ = brute.dense_attention(Q[s, lo:hi], K[s, lo:hi], V[s, lo:hi], mask, scale)
+            np.testing.assert_allclose(res["O"][s, lo:hi], O, rtol=0, atol=1e-12)
+            np.testing.assert_allclose(res["lse"][s, lo:hi], lse, rtol=0, atol=1e-12)
+            rQ, rK, rV = brute.dense_backward(Q[s, lo:hi], K[s, lo:hi], V[s, lo:hi], mask, scale, dO[s, lo:hi])
+            np.testing.assert_allclose(gQ[s, lo:hi], rQ, rtol=0, atol=1e-11)
+            np.testing.assert_allclose(gK[s, lo:hi], rK, rtol=0, atol=1e-11)
+            np.testing.assert_allclose(gV[s, lo:hi], rV, rtol=0, atol=1e-11)
+
+
 # ---------------------------------------------------------------- brute force
 
 @pytest.mark.parametrize("B,d", [(1, 4), (2, 4), (4, 8), (8, 8)])
