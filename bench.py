@@ -86,6 +86,9 @@ def parse():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB device to device once (a kernel of "
                          "known HBM traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--separate-workspaces", action="store_true",
+                    help="give forward and backward a workspace each (every call then makes its own copies "
+                         "of K and V) instead of one shared workspace prepared by the forward call")
     ap.add_argument("--microbench", action="store_true",
                     help="also run the library's two ceiling measurements once (a plain 1 GiB copy kernel, "
                          "a register-only bf16 MFMA loop) and report the fractions of those measured "
@@ -156,11 +159,17 @@ def measure(w, a, moba, binding, workloads, torch):
                   for _ in range(max(a.rotate_inputs, 1) - 1)]
     flags = binding.FLAG_REFERENCE_KERNELS if a.reference_kernels else 0
     flags |= {"auto": 0, "tiles": binding.FLAG_QUERY_TILES, "keymajor": binding.FLAG_KEY_MAJOR}[a.attention]
+    if w.backward and not a.separate_workspaces:
+        flags |= binding.FLAG_SHARED_WORKSPACE      # forward and backward share the prepared copies of K and V
     sh = moba.Shape(w.batch, w.heads, w.N, w.d, w.B, w.k, w.conv_width,
                     binding.BF16 if w.dtype == "bf16" else binding.F32, 0.0, flags, w.kv_heads)
     R = moba.routes_per_slice(sh)
-    ws_topk, ws_fwd, ws_bwd = (torch.empty(max(x, 256), dtype=torch.uint8, device="cuda")
-                               for x in moba.workspace_bytes(sh))
+    sizes = moba.workspace_bytes(sh)
+    ws_topk = torch.empty(max(sizes[0], 256), dtype=torch.uint8, device="cuda")
+    if flags & binding.FLAG_SHARED_WORKSPACE:
+        ws_fwd = ws_bwd = torch.empty(max(sizes[1], sizes[2], 256), dtype=torch.uint8, device="cuda")
+    else:
+        ws_fwd, ws_bwd = (torch.empty(max(x, 256), dtype=torch.uint8, device="cuda") for x in sizes[1:])
     dev = torch.device("cuda")
     Keff = torch.empty_like(d["K"]) if w.conv_width else None
     cent = torch.empty((w.batch, w.hkv, w.n, w.d), dtype=torch.float32, device=dev)

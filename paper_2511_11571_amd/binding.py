@@ -19,6 +19,7 @@ FLAG_REFERENCE_KERNELS = 1
 FLAG_KEY_MAJOR = 2
 FLAG_QUERY_TILES = 4
 FLAG_GATE_EXACT_SEARCH = 8
+FLAG_SHARED_WORKSPACE = 16
 
 
 class MobaError(RuntimeError):

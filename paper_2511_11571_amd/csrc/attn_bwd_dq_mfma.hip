@@ -287,45 +287,31 @@ static hipError_t dq_launch(const Dims& s, const void* Q, const void* Ka, const 
     return hipGetLastError();
 }
 
-// Workspace of the MFMA backward: [D vector: bh*N fp32][slot-ordered scaled K: bh*N*D bf16]
-// [operand-ordered K: bh*N*D bf16][operand-ordered V: bh*N*D bf16][kmax: bh*D words]
-// [vmax: bh*D words], each part 256-byte aligned.
+// Workspace of the MFMA backward: [D vector: bh*N fp32][prepared copies: maxima of K and V,
+// operand-ordered K, slot-ordered scaled K, operand-ordered V], each part 256-byte aligned.  When
+// the workspace is shared with the forward (MOBA_FLAG_SHARED_WORKSPACE) the forward's slot-ordered
+// V lies among the copies too, and the forward call has made all of them.
 
 size_t backward_mfma_ws_bytes(const Dims& s)
 {
-    return a256(sizeof(float) * (size_t)s.bh * s.N) + 3 * a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D) +
-           2 * a256(sizeof(uint32_t) * (size_t)s.bh * s.D);
+    return a256(sizeof(float) * (size_t)s.bh * s.N) +
+           prepared_layout(s, shared_workspace(s) ? kPrepAll : kPrepBackward, nullptr, nullptr);
 }
 
 hipError_t launch_dq_mfma(const Dims& s, const void* Q, const void* K, const void* V, const void* dO,
                           const float* lse, const int32_t* idx, const int32_t* off, const int32_t* ql,
                           void* dQ, void* ws, hipStream_t st)
 {
-    char* p = (char*)ws;
-    const float* Dv = (const float*)p;
-    p += a256(sizeof(float) * (size_t)s.bh * s.N);
-    void* Kt = p;
-    p += a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
-    void* Ka = p;
-    p += a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
-    void* Va = p;
-    p += a256(sizeof(bf16_t) * (size_t)s.bh * s.N * s.D);
-    uint32_t* kmax = (uint32_t*)p;
-    p += a256(sizeof(uint32_t) * (size_t)s.bh * s.D);
-    uint32_t* vmax = (uint32_t*)p;
-    const Dims kv = kv_view(s);      // K and V: one slice per key/value head (the parts stay sized for bh)
-    hipError_t e = launch_absmax(kv, K, kmax, st);
-    if (e != hipSuccess) return e;
-    e = launch_absmax(kv, V, vmax, st);
-    if (e != hipSuccess) return e;
-    e = launch_slot_major_copy(kv, K, Kt, kmax, st);
-    if (e != hipSuccess) return e;
-    e = launch_operand_copy(kv, K, Ka, st);
-    if (e != hipSuccess) return e;
-    e = launch_operand_copy(kv, V, Va, st);
-    if (e != hipSuccess) return e;
-    return s.D == 64 ? dq_launch<64>(s, Q, Ka, Va, Kt, kmax, vmax, dO, lse, Dv, idx, dQ, st)
-                     : dq_launch<128>(s, Q, Ka, Va, Kt, kmax, vmax, dO, lse, Dv, idx, dQ, st);
+    const float* Dv = (const float*)ws;
+    Prepared p;
+    prepared_layout(s, shared_workspace(s) ? kPrepAll : kPrepBackward,
+                    (char*)ws + a256(sizeof(float) * (size_t)s.bh * s.N), &p);
+    if (!shared_workspace(s)) {
+        hipError_t e = launch_prepare(kv_view(s), K, V, p, st);
+        if (e != hipSuccess) return e;
+    }
+    return s.D == 64 ? dq_launch<64>(s, Q, p.Ka, p.Va, p.Kt, p.kmax, p.vmax, dO, lse, Dv, idx, dQ, st)
+                     : dq_launch<128>(s, Q, p.Ka, p.Va, p.Kt, p.kmax, p.vmax, dO, lse, Dv, idx, dQ, st);
 }
 
 }  // namespace moba

@@ -49,41 +49,8 @@ struct FwdCfg {
                                   4 * 2 * (RANGE + 1) + 4 * NW + 8 + LCAP + 64;
 };
 
-// ---- per-channel scale of V and the slot-ordered transposed copy (see mfma.h) -----------
-
-__global__ void zero_words_kernel(uint32_t* p, int count)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) p[i] = 0u;
-}
-
-// vmax[s][c] = max_t |X[s][t][c]| as raw fp32 bits (non-negative floats order like integers)
-template <int D>
-__global__ __launch_bounds__(256) void absmax_kernel(const bf16_t* __restrict__ X,
-                                                     uint32_t* __restrict__ vmax, int N,
-                                                     int rows_per_wg)
-{
-    __shared__ float red[256 / (D / 8)][D];
-    constexpr int G = D / 8;
-    const int s = blockIdx.y, part = threadIdx.x % G, rr = threadIdx.x / G;
-    const int r0 = blockIdx.x * rows_per_wg, r1 = min(N, r0 + rows_per_wg);
-    float mx[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-    for (int r = r0 + rr; r < r1; r += 256 / G) {
-        float v[8];
-        Vec8<bf16_t>::load(X + ((int64_t)s * N + r) * D + part * 8, v);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) mx[e] = fmaxf(mx[e], fabsf(v[e]));
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) red[rr][part * 8 + e] = mx[e];
-    __syncthreads();
-    if (threadIdx.x < D) {
-        float m = 0.f;
-        for (int i = 0; i < 256 / G; ++i) m = fmaxf(m, red[i][threadIdx.x]);
-        atomicMax(&vmax[s * D + threadIdx.x], __float_as_uint(m));
-    }
-}
+// ---- the slot-ordered transposed copy alone (see mfma.h; the key-major kernels use it unscaled;
+// the copies of the query-tile kernels are made in prepare.hip) -----------
 
 template <int D>
 __global__ __launch_bounds__(256) void slot_major_copy_kernel(const bf16_t* __restrict__ X,
@@ -121,22 +88,6 @@ __global__ __launch_bounds__(256) void slot_major_copy_kernel(const bf16_t* __re
     }
 }
 
-// vmax[bh][D] <- largest magnitude of each channel of X, as fp32 bits
-hipError_t launch_absmax(const Dims& s, const void* X, uint32_t* vmax, hipStream_t st)
-{
-    if (s.N == 0) return hipSuccess;
-    const int cnt = s.bh * s.D, rows_per_wg = 256;         // enough workgroups to keep all of HBM busy
-    hipLaunchKernelGGL(zero_words_kernel, dim3((cnt + 255) / 256), dim3(256), 0, st, vmax, cnt);
-    dim3 grid((s.N + rows_per_wg - 1) / rows_per_wg, s.bh);
-    if (s.D == 64)
-        hipLaunchKernelGGL(absmax_kernel<64>, grid, dim3(256), 0, st, (const bf16_t*)X, vmax, s.N,
-                           rows_per_wg);
-    else
-        hipLaunchKernelGGL(absmax_kernel<128>, grid, dim3(256), 0, st, (const bf16_t*)X, vmax, s.N,
-                           rows_per_wg);
-    return hipGetLastError();
-}
-
 // Xt <- slot-ordered transposed copy of X, each channel scaled by 2^-e (e from its largest
 // magnitude vmax[bh][D], fp32 bits); vmax == nullptr: plain copy.
 hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, const uint32_t* vmax,
@@ -150,39 +101,6 @@ hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, const 
     else
         hipLaunchKernelGGL(slot_major_copy_kernel<128>, dim3((unsigned)groups), dim3(256), 0, st,
                            (const bf16_t*)X, vmax, (bf16_t*)Xt, gps);
-    return hipGetLastError();
-}
-
-// Xa <- copy of X in MFMA operand order: the 16 bytes lane (m, g) feeds to the MFMA as rows
-// 16 mt + m, channels 32 ks + 8 g .. + 8 of 32-key group kap sit at
-// ((kap * 2 + mt) * (D / 32) + ks) * 1024 + 16 * lane.  One load instruction of a wave then
-// covers 1 KB of consecutive bytes; reading the same operand from the row-major tensor (16
-// rows x 64 bytes per instruction) runs at a quarter of that rate on this chip.
-template <int D>
-__global__ __launch_bounds__(256) void operand_copy_kernel(const bf16_t* __restrict__ X,
-                                                           bf16_t* __restrict__ Xa, int64_t chunks)
-{
-    constexpr int KS = D / 32;
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= chunks) return;
-    const int lane = (int)(i % 64), ks = (int)((i / 64) % KS), mt = (int)((i / (64 * KS)) % 2);
-    const int64_t kap = i / (64 * KS * 2);
-    const int m = lane & 15, g = lane >> 4;
-    const uint4 v = *reinterpret_cast<const uint4*>(X + (kap * 32 + 16 * mt + m) * D + 32 * ks + 8 * g);
-    *reinterpret_cast<uint4*>(Xa + i * 8) = v;
-}
-
-hipError_t launch_operand_copy(const Dims& s, const void* X, void* Xa, hipStream_t st)
-{
-    const int64_t chunks = (int64_t)s.bh * s.N * s.D / 8;
-    if (chunks == 0) return hipSuccess;
-    const unsigned grid = (unsigned)((chunks + 255) / 256);
-    if (s.D == 64)
-        hipLaunchKernelGGL(operand_copy_kernel<64>, dim3(grid), dim3(256), 0, st, (const bf16_t*)X,
-                           (bf16_t*)Xa, chunks);
-    else
-        hipLaunchKernelGGL(operand_copy_kernel<128>, dim3(grid), dim3(256), 0, st, (const bf16_t*)X,
-                           (bf16_t*)Xa, chunks);
     return hipGetLastError();
 }
 
@@ -461,29 +379,30 @@ static hipError_t fwd_launch(const Dims& s, const void* Q, const void* K, const 
     return hipGetLastError();
 }
 
+// ws: the prepared copies the forward reads (maxima of V, operand-ordered K, slot-ordered scaled V);
+// with a workspace shared with the backward: behind the backward's D vector, and everything the
+// backward reads as well
 size_t forward_mfma_ws_bytes(const Dims& s)
 {
-    return 2 * (sizeof(bf16_t) * (size_t)s.bhk * s.N * s.D + 256) + sizeof(uint32_t) * (size_t)s.bhk * s.D;
+    if (shared_workspace(s)) return backward_mfma_ws_bytes(s);
+    return prepared_layout(s, kPrepForward, nullptr, nullptr);
 }
 
-// ws (per key/value slice): [N*D bf16 slot-ordered scaled V][pad to 256][N*D bf16 operand-ordered K]
-//     [pad to 256][D fp32 bits: channel maxima of V]
 hipError_t launch_forward_mfma(const Dims& s, const void* Q, const void* K, const void* V,
                                void* ws, const int32_t* idx, const int32_t* off, const int32_t* ql,
                                void* O, float* lse, hipStream_t st)
 {
-    const size_t vt_bytes = (sizeof(bf16_t) * (size_t)s.bhk * s.N * s.D + 255) & ~(size_t)255;
-    void* Ka = (char*)ws + vt_bytes;
-    uint32_t* vmax = reinterpret_cast<uint32_t*>((char*)ws + 2 * vt_bytes);
-    const Dims kv = kv_view(s);                              // K and V: one slice per key/value head
-    hipError_t e = launch_absmax(kv, V, vmax, st);
+    Prepared p;
+    if (shared_workspace(s)) {
+        prepared_layout(s, kPrepAll, (char*)ws + a256(sizeof(float) * (size_t)s.bh * s.N), &p);
+    } else {
+        prepared_layout(s, kPrepForward, ws, &p);
+        p.kmax = nullptr;                                    // (only the dQ kernel scales K)
+    }
+    hipError_t e = launch_prepare(kv_view(s), K, V, p, st);  // K and V: one slice per key/value head
     if (e != hipSuccess) return e;
-    e = launch_slot_major_copy(kv, V, ws, vmax, st);
-    if (e != hipSuccess) return e;
-    e = launch_operand_copy(kv, K, Ka, st);
-    if (e != hipSuccess) return e;
-    return s.D == 64 ? fwd_launch<64>(s, Q, Ka, ws, vmax, idx, O, lse, st)
-                     : fwd_launch<128>(s, Q, Ka, ws, vmax, idx, O, lse, st);
+    return s.D == 64 ? fwd_launch<64>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, st)
+                     : fwd_launch<128>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, st);
 }
 
 }  // namespace moba

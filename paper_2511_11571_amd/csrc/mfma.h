@@ -199,8 +199,29 @@ __device__ __forceinline__ void build_block_lists(const int32_t* __restrict__ id
     __syncthreads();
 }
 
-hipError_t launch_operand_copy(const Dims& s, const void* X, void* Xa, hipStream_t st);
-hipError_t launch_absmax(const Dims& s, const void* X, uint32_t* vmax, hipStream_t st);
+// ---- prepared copies of K and V (prepare.hip) ------------------------------------------------
+// "MFMA operand order": the 16 bytes lane (m, g) feeds to the MFMA as rows 16 mt + m, channels
+// 32 ks + 8 g .. + 8 of 32-key group kap sit at ((kap * 2 + mt) * (D / 32) + ks) * 1024 + 16 * lane.
+// One load instruction of a wave then covers 1 KB of consecutive bytes; reading the same operand
+// from the row-major tensor (16 rows x 64 bytes per instruction) runs at a quarter of that rate on
+// this chip.  "Slot-ordered transposed": slot_major_offset() above.
+struct Prepared {
+    uint32_t* kmax = nullptr;   // [bhk][D] largest magnitude per channel of K, fp32 bits
+    uint32_t* vmax = nullptr;   //                                          of V
+    void* Ka = nullptr;         // K in MFMA operand order
+    void* Vt = nullptr;         // V slot-ordered transposed, scaled per channel
+    void* Kt = nullptr;         // K slot-ordered transposed, scaled per channel
+    void* Va = nullptr;         // V in MFMA operand order
+};
+constexpr unsigned kPrepKa = 1, kPrepVt = 2, kPrepKt = 4, kPrepVa = 8;
+constexpr unsigned kPrepForward = kPrepKa | kPrepVt;             // what the query-tile forward reads
+constexpr unsigned kPrepBackward = kPrepKa | kPrepKt | kPrepVa;  // what the query-tile dQ kernel reads
+constexpr unsigned kPrepAll = kPrepForward | kPrepBackward;
+size_t prepared_layout(const Dims& s, unsigned mask, void* base, Prepared* out);
+// makes the parts of `p` that are not null (the maxima it needs first)
+hipError_t launch_prepare(const Dims& kv, const void* K, const void* V, const Prepared& p, hipStream_t st);
+bool shared_workspace(const Dims& s);
+
 hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, const uint32_t* vmax,
                                   hipStream_t st);
 size_t forward_mfma_ws_bytes(const Dims& s);
@@ -297,6 +318,13 @@ inline bool key_major_path(const Dims& s)
                          s.k * (s.B / 32.0) * (d64 ? 0.015 + 0.14 / rows : 0.033 + 0.272 / rows);
     const double keymajor = (d64 ? 0.145 : 0.23) * (s.k + 1) * (1.0 + 0.7 * (parts - 1.0));
     return keymajor < tiles;
+}
+
+// The caller gives forward and backward the same workspace and the forward call prepares for both:
+// only where both run on the query-tile kernels.
+inline bool shared_workspace(const Dims& s)
+{
+    return (s.flags & MOBA_FLAG_SHARED_WORKSPACE) && mfma_path(s) && tile_forward_ok(s) && !key_major_path(s);
 }
 
 size_t forward_km_ws_bytes(const Dims& s);

@@ -33,7 +33,7 @@ int make_dims(const moba_shape* sh, Dims& d, bool ragged_ok = false)
     if (!ragged_ok && sh->seqlen % sh->block != 0) return MOBA_EINVAL;
     if (sh->dtype != MOBA_F32 && sh->dtype != MOBA_BF16) return MOBA_EINVAL;
     if (sh->flags & ~(uint32_t)(MOBA_FLAG_REFERENCE_KERNELS | MOBA_FLAG_KEY_MAJOR | MOBA_FLAG_QUERY_TILES |
-                                 MOBA_FLAG_GATE_EXACT_SEARCH))
+                                 MOBA_FLAG_GATE_EXACT_SEARCH | MOBA_FLAG_SHARED_WORKSPACE))
         return MOBA_EINVAL;
     if ((sh->flags & MOBA_FLAG_KEY_MAJOR) && (sh->flags & MOBA_FLAG_QUERY_TILES)) return MOBA_EINVAL;
     if (!(sh->softmax_scale == sh->softmax_scale) || isinf(sh->softmax_scale)) return MOBA_EINVAL;
@@ -80,12 +80,15 @@ size_t topk_ws_bytes(const Dims& d)
 }
 int32_t* chunk_counts(const Dims&, void* ws) { return static_cast<int32_t*>(ws); }
 void* topk_terms(const Dims& d, void* ws) { return static_cast<char*>(ws) + chunk_counts_bytes(d); }
+size_t bwd_ws_bytes(const Dims& d);
 // forward: operand copies of K and V (+ the per-pair partials of the key-major kernel)
 size_t fwd_ws_bytes(const Dims& d)
 {
     if (!mfma_path(d)) return 256;
     if (key_major_path(d)) return align256(forward_km_ws_bytes(d));
-    return tile_forward_ok(d) ? align256(forward_mfma_ws_bytes(d)) : 256;    // else: the plain kernel
+    if (!tile_forward_ok(d)) return 256;                                     // the plain kernel
+    // one workspace for forward and backward: sized for the backward, which includes the forward's parts
+    return shared_workspace(d) ? bwd_ws_bytes(d) : align256(forward_mfma_ws_bytes(d));
 }
 // backward: D first in every layout; on the MFMA path the per-query pairs (lse log2 e, -D) of
 // the gathering kernels follow the layout, and with shared key/value heads the per-query-head sums

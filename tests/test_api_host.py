@@ -94,7 +94,7 @@ def test_default_cut_of_the_attention(kw, key_major):
 @pytest.mark.parametrize("kw,status", [
     (dict(batch=0), -1), (dict(heads=-1), -1), (dict(seqlen=0), -1), (dict(block=0), -1),
     (dict(seqlen=1000), -1),            # not a multiple of the block
-    (dict(topk=-1), -1), (dict(dtype=7), -1), (dict(conv_width=-2), -1), (dict(flags=16), -1),
+    (dict(topk=-1), -1), (dict(dtype=7), -1), (dict(conv_width=-2), -1), (dict(flags=32), -1),
     (dict(head_dim=96), -2), (dict(conv_width=9), -2), (dict(topk=5000), -2),
     (dict(seqlen=(1 << 24) + 32, topk=0), -2),      # longer than the 32-bit row offsets allow
     (dict(heads=6, kv_heads=4), -1),    # key/value heads must divide the query heads

@@ -498,6 +498,32 @@ def test_dense_rows_with_a_dominant_logit(oracle, N, flags):
     assert parity.max_abs(got_lse, rlse) < parity.LSE_TOL[w.dtype]
 
 
+def test_shared_workspace_gives_the_same_results():
+    """MOBA_FLAG_SHARED_WORKSPACE: forward and backward on one workspace, the copies of K and V made
+    once by the forward call -- bit-identical to separate workspaces (and no effect where the
+    key-major kernels run)."""
+    for w, extra in ((W("shared_ws", 1, 2, 2048, 64, 32, 8, backward=True, seed=81), 0),
+                     (W("shared_ws_d128", 2, 2, 1024, 128, 64, 3, backward=True, seed=82), binding.FLAG_QUERY_TILES),
+                     (W("shared_ws_gqa", 1, 4, 1024, 64, 32, 4, backward=True, kv_heads=2, seed=83), 0),
+                     (W("shared_ws_km", 1, 2, 1024, 64, 128, 2, backward=True, seed=84), binding.FLAG_KEY_MAJOR)):
+        d = dev(workloads.generate(w))
+        outs = []
+        for shared in (0, binding.FLAG_SHARED_WORKSPACE):
+            sh = shape_of(w, extra | shared)
+            Keff, cent = moba.centroids(sh, d["K"])
+            idx, lists = moba.topk(sh, d["Q"], cent)
+            sizes = moba.workspace_bytes(sh)
+            if shared:                  # (equal sizes where the flag takes effect; the larger one serves both)
+                ws_f = ws_b = torch.empty(max(sizes[1:]), dtype=torch.uint8, device="cuda")
+            else:
+                ws_f, ws_b = (torch.empty(x, dtype=torch.uint8, device="cuda") for x in sizes[1:])
+            O, lse = moba.forward(sh, d["Q"], Keff, d["V"], idx, lists, ws=ws_f)
+            grads = moba.backward(sh, d["Q"], Keff, d["V"], O, lse, d["dO"], idx, lists, ws=ws_b)
+            outs.append((O, lse) + tuple(grads))
+        for a, b in zip(*outs):
+            assert torch.equal(a, b)
+
+
 def test_kernel_timing_session():
     """moba_profile_begin/_end: one event pair per launch of a main kernel, results unchanged."""
     w = W("timing", 1, 2, 2048, 64, 32, 8, backward=True, seed=72)
