@@ -17,7 +17,8 @@
  *     `shape->dtype` (fp32, or bf16 as raw 16-bit words) for Q, K, V, K_eff, O, dO,
  *     dQ, dK, dV.  Centroids, lse and conv weights are always fp32; indices int32.
  *   - Arguments are checked on the host before anything is enqueued; a call that
- *     returns non-zero has launched nothing.  Work is enqueued on `stream`
+ *     returns MOBA_EINVAL, MOBA_EUNSUPPORTED or MOBA_EWORKSPACE has launched nothing (MOBA_EHIP:
+ *     a launch failed; kernels enqueued before it may still run).  Work is enqueued on `stream`
  *     (a hipStream_t passed as void*; NULL = the default stream) and the call
  *     returns without synchronising.
  *   - Return value: MOBA_OK (0) or a negative moba_status.  No exceptions, no abort.
@@ -104,7 +105,8 @@ int moba_workspace_bytes(const moba_shape* shape, size_t* topk_ws, size_t* fwd_w
  *   K         in   [b,kv,N,d] dtype
  *   conv_w    in   [kv,d,W] fp32, last axis = lag l; must be NULL iff conv_width == 0
  *   K_eff     out  [b,kv,N,d] dtype: the convolved keys rounded to dtype; required iff
- *                  conv_width > 0 (with conv_width == 0 it may be NULL; if given, K is copied)
+ *                  conv_width > 0 (with conv_width == 0 it may be NULL; if given, K is copied);
+ *                  with conv_width > 1 it must not be K itself (MOBA_EINVAL) nor overlap it
  *   centroids out  [b,kv,n,d] fp32: mean over each block of the (rounded) K_eff rows
  */
 int moba_centroids(const moba_shape* shape, const void* K, const float* conv_w,
@@ -143,8 +145,11 @@ int moba_key_conv_backward(const moba_shape* shape, const void* K, const float* 
  *                  query's position in the sequence.  Bits 24..31 are for the library's
  *                  own use: where the shape and flags select the key-block-major
  *                  attention kernels they hold the position of block j in that query's
- *                  row of topk_idx, otherwise zero.  Lists are therefore built (here or
- *                  by moba_build_lists) with the shape and flags they are used with.
+ *                  row of topk_idx, otherwise zero.  Lists MUST therefore be built (here or
+ *                  by moba_build_lists) with the shape and flags they are used with: the
+ *                  key-block-major kernels file their partial results by that position, and
+ *                  lists built without it (e.g. with MOBA_FLAG_QUERY_TILES, then used with
+ *                  MOBA_FLAG_KEY_MAJOR) give a wrong result that no status code reports.
  *   ws             at least topk_ws bytes from moba_workspace_bytes
  */
 int moba_topk(const moba_shape* shape, const void* Q, const float* centroids,

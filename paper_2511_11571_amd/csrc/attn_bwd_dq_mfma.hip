@@ -39,6 +39,7 @@ struct DqCfg {
 };
 
 constexpr float kDqBits = 30.f;
+constexpr int kNanRow = 1 << 20;          // in place of a row's scale exponent: the row's dQ is NaN
 
 template <int D>
 __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
@@ -97,18 +98,24 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
     __syncthreads();
     // per-row scale: 2^e_t >= sum_c |dO_tc| 2^ev_c + |D_t|
     for (int r = tid; r < C::TILE; r += C::NT) {
-        float bound = 0.f, Dt = 0.f, L = 0.f;
+        float bound = 0.f, Dt = 0.f, L = 0.f, qsum = 0.f;
+        bool finite = true;
         if (r < rows_here) {
             for (int c = 0; c < D; ++c) {
-                const bf16_t gv = *reinterpret_cast<const bf16_t*>(
-                    Gs + (uint32_t)r * C::ROWB + ((((c >> 3) ^ (r & 7)) << 4) | ((c & 7) << 1)));
+                const uint32_t o = (uint32_t)r * C::ROWB + ((((c >> 3) ^ (r & 7)) << 4) | ((c & 7) << 1));
+                const bf16_t gv = *reinterpret_cast<const bf16_t*>(Gs + o);
                 bound += fabsf(bf16_to_f32(gv)) * ldexpf(1.f, scale_exponent(vmax[skv * D + c]));
+                qsum += fabsf(bf16_to_f32(*reinterpret_cast<const bf16_t*>(Qs + o)));
+                finite = finite && !nonfinite_bits(kmax[skv * D + c]) && !nonfinite_bits(vmax[skv * D + c]);
             }
             Dt = Dv[sbase + t0 + r];
             L = lse[sbase + t0 + r];
             bound += fabsf(Dt);
+            // an infinity or a NaN in the row's dO, D, lse or Q, or anywhere in K or V: the integer
+            // sums cannot carry it, the row's dQ is written as NaN
+            finite = finite && fabsf(bound) < INFINITY && fabsf(L) < INFINITY && fabsf(qsum) < INFINITY;
         }
-        const int e = max(scale_exponent(__float_as_uint(bound)), -60);   // keeps 2^(30-e) finite
+        const int e = finite ? max(scale_exponent(__float_as_uint(bound)), -60) : kNanRow;   // keeps 2^(30-e) finite
         esc[r] = e;
         Dr[r] = -Dt;                   // start value of the dP product: dP - D comes out of the MFMA
         pexp[r] = L * kLog2e - kDqBits + (float)e;
@@ -263,7 +270,8 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
         float v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            v[e] = scale * ldexpf((float)acc[r * C::OSTRIDE + 8 * c + e], et + scale_exponent(kmax[skv * D + 8 * c + e]));
+            v[e] = esc[r] == kNanRow ? NAN
+                 : scale * ldexpf((float)acc[r * C::OSTRIDE + 8 * c + e], et + scale_exponent(kmax[skv * D + 8 * c + e]));
         Vec8<bf16_t>::store(dQg + (int64_t)r * D + 8 * c, v);
     }
 }

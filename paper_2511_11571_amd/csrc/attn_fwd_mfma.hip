@@ -109,7 +109,7 @@ hipError_t launch_slot_major_copy(const Dims& s, const void* X, void* Xt, const 
 // monotone map fp32 -> int32 (and back): larger float <=> larger int
 __device__ __forceinline__ int float_key(float x)
 {
-    const int b = __float_as_int(x);
+    const int b = x != x ? 0x7fc00000 : __float_as_int(x);      // a NaN of either sign: above everything
     return b ^ ((b >> 31) & 0x7fffffff);
 }
 __device__ __forceinline__ float key_float(int k)
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                 }
                 if (pass == 0) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) mx = fmaxf(mx, x[e]);
+                    for (int e = 0; e < 8; ++e) mx = max_nan(mx, x[e]);
                 } else {
                     accumulate(row, x, va, true);
                 }
@@ -306,8 +306,9 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                         for (int ks = 0; ks < C::KS; ++ks) sc[mt] = mfma16(ka[mt][ks], qb[ks], sc[mt]);
                     }
                     if (pass == 0) {
-                        float mx = fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3]));
-                        mx = fmaxf(mx, fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+                        // (a NaN score makes the row's reference, and with it the row, NaN)
+                        float mx = max_nan(max_nan(sc[0][0], sc[0][1]), max_nan(sc[0][2], sc[0][3]));
+                        mx = max_nan(mx, max_nan(max_nan(sc[1][0], sc[1][1]), max_nan(sc[1][2], sc[1][3])));
                         if (valid) atomicMax(&mkey[row], float_key(mx * c2));
                     } else {
                         float x[8];
@@ -355,8 +356,11 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
         const float inv = 1.f / lf;
         float v[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            v[e] = ldexpf((float)Os[r * C::OSTRIDE + 8 * c + e] * inv, scale_exponent(vmax[skv * D + 8 * c + e]));
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t vm = vmax[skv * D + 8 * c + e];
+            v[e] = nonfinite_bits(vm) ? NAN          // V holds an infinity or a NaN in this channel
+                                      : ldexpf((float)Os[r * C::OSTRIDE + 8 * c + e] * inv, scale_exponent(vm));
+        }
         Vec8<bf16_t>::store(Og + (int64_t)r * D + 8 * c, v);
         if (c == 0) lse[sbase + t0 + r] = (__int_as_float(mkey[r]) + fast_log2(lf)) * kLn2;
     }

@@ -287,6 +287,11 @@ static hipError_t fwd_t(const Dims& s, const void* Q, const void* K, const void*
     const int64_t rows = (int64_t)s.bh * s.N;
     if (rows == 0) return hipSuccess;
     const size_t lds = sizeof(float) * 4 * (D + 2 * kWave) + sizeof(int32_t) * 4 * (size_t)s.k;
+    if (lds > 64 * 1024) {     // top-k in the thousands: above the default dynamic LDS limit, opt in
+        hipError_t e = hipFuncSetAttribute((const void*)forward_reference_kernel<T, D>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL((forward_reference_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)), dim3(256),
                        lds, st, (const T*)Q, (const T*)K, (const T*)V, idx, (T*)O, lse, s.N, s.B, s.k,
                        s.scale, rows, s.G);
@@ -306,6 +311,11 @@ static hipError_t bwd_t(const Dims& s, const void* Q, const void* K, const void*
     hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0,
                        st, (const T*)dO, (const T*)O, Dvec, rows, lse, packed);
     const size_t lds = sizeof(float) * 4 * (2 * D + 2 * kWave) + sizeof(int32_t) * 4 * (size_t)s.k;
+    if ((parts & MOBA_BWD_DQ) && lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)dq_reference_kernel<T, D>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
     if (parts & MOBA_BWD_DQ)
     hipLaunchKernelGGL((dq_reference_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)), dim3(256), lds,
                        st, (const T*)Q, (const T*)K, (const T*)V, (const T*)dO, lse, Dvec, idx,

@@ -67,6 +67,11 @@ __device__ __forceinline__ int scale_exponent(uint32_t vmax_bits)
     return E == 0 ? 0 : E - 127 + 1;
 }
 
+// maximum that hands a NaN on (v_maximum3_f32 on gfx950; fmaxf would drop it)
+__device__ __forceinline__ float max_nan(float a, float b) { return __builtin_elementwise_maximum(a, b); }
+// channel maximum (fp32 bits of a magnitude) of a tensor that holds an infinity or a NaN
+__device__ __forceinline__ bool nonfinite_bits(uint32_t magnitude_bits) { return magnitude_bits >= 0x7f800000u; }
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 

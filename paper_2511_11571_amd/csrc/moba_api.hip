@@ -242,6 +242,9 @@ int moba_centroids(const moba_shape* shape, const void* K, const float* conv_w, 
     if (!K || !centroids) return MOBA_EINVAL;
     if ((d.W > 0) != (conv_w != nullptr)) return MOBA_EINVAL;
     if (d.W > 0 && !K_eff) return MOBA_EINVAL;
+    // the convolution reads the rows before a run of keys while other lanes already write theirs:
+    // not in place
+    if (d.W > 1 && K_eff == K) return MOBA_EINVAL;
     return hip_status(launch_centroids(kv_view(d), K, conv_w, K_eff, centroids, (hipStream_t)stream));
 }
 

@@ -23,28 +23,30 @@ __global__ __launch_bounds__(256) void absmax2_kernel(const bf16_t* __restrict__
                                                       uint32_t* __restrict__ kmax, uint32_t* __restrict__ vmax,
                                                       int N, int rows_per_wg, int first_z)
 {
-    __shared__ float red[256 / (D / 8)][D];
+    __shared__ uint32_t red[256 / (D / 8)][D];
     constexpr int G = D / 8;
     const int z = blockIdx.z + first_z;
     const bf16_t* X = z == 0 ? K : V;
     uint32_t* out = z == 0 ? kmax : vmax;
     const int s = blockIdx.y, part = threadIdx.x % G, rr = threadIdx.x / G;
     const int r0 = blockIdx.x * rows_per_wg, r1 = min(N, r0 + rows_per_wg);
-    float mx[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // magnitudes compared as integers: infinities and NaNs come out on top instead of being dropped,
+    // and the kernels that read the maxima turn them into NaN results
+    uint32_t mx[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
 #pragma unroll 4
     for (int r = r0 + rr; r < r1; r += 256 / G) {
         float v[8];
         Vec8<bf16_t>::load(X + ((int64_t)s * N + r) * D + part * 8, v);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) mx[e] = fmaxf(mx[e], fabsf(v[e]));
+        for (int e = 0; e < 8; ++e) mx[e] = max(mx[e], __float_as_uint(v[e]) & 0x7fffffffu);
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) red[rr][part * 8 + e] = mx[e];
     __syncthreads();
     if (threadIdx.x < D) {
-        float m = 0.f;
-        for (int i = 0; i < 256 / G; ++i) m = fmaxf(m, red[i][threadIdx.x]);
-        atomicMax(&out[s * D + threadIdx.x], __float_as_uint(m));
+        uint32_t m = 0u;
+        for (int i = 0; i < 256 / G; ++i) m = max(m, red[i][threadIdx.x]);
+        atomicMax(&out[s * D + threadIdx.x], m);
     }
 }
 

@@ -157,3 +157,11 @@ def test_profile_session_misuse_is_rejected(lib):
     assert lib.moba_profile_end(None, calls) == -1          # null array: the session stays open
     assert lib.moba_profile_end(ms, calls) == 0             # no launches: all zero, no HIP call
     assert list(calls) == [0, 0, 0, 0] and list(ms) == [0.0] * 4
+
+
+def test_convolution_in_place_is_rejected(lib):
+    one = ctypes.c_void_p(256)                 # never dereferenced on these paths
+    sh = _shape(conv_width=4).c()
+    assert lib.moba_centroids(ctypes.byref(sh), one, one, one, one, None) == -1      # K_eff == K
+    sh1 = _shape(conv_width=0).c()
+    assert lib.moba_centroids(ctypes.byref(sh1), None, None, None, one, None) == -1   # K missing

@@ -392,8 +392,12 @@ def test_ragged_sequence_by_zero_padding():
 @pytest.mark.parametrize("flags", FLAGS)
 @pytest.mark.parametrize("w", [W("chain_bf16", 1, 2, 1024, 64, 32, 4, backward=True, seed=50),
                                W("chain_conv", 1, 2, 1024, 128, 64, 3, conv_width=4, seed=51),
-                               W("chain_f32", 1, 2, 512, 64, 32, 3, dtype="f32", seed=52)],
-                         ids=["bf16", "conv_d128", "f32"])
+                               W("chain_f32", 1, 2, 512, 64, 32, 3, dtype="f32", seed=52),
+                               # the largest top-k the library takes (rows of 4096 entries, full causal
+                               # attention): the plain kernels then need more LDS than the default limit
+                               W("chain_k4096", 1, 1, 256, 64, 2, 4096, dtype="f32", seed=53),
+                               W("chain_k4096_bf16", 1, 1, 256, 64, 2, 4096, seed=54)],
+                         ids=["bf16", "conv_d128", "f32", "f32_k4096", "bf16_k4096"])
 def test_whole_chain(oracle, w, flags):
     t = workloads.generate(w)
     Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
@@ -522,6 +526,45 @@ def test_shared_workspace_gives_the_same_results():
             outs.append((O, lse) + tuple(grads))
         for a, b in zip(*outs):
             assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("flags", ATTN_FLAGS)
+def test_nonfinite_inputs_reach_the_outputs(flags):
+    """A NaN in Q, K, V or dO must not vanish inside the attention kernels (a training loop's
+    overflow detection looks for it in the outputs): every row that attends the poisoned key, or is
+    the poisoned query, comes out NaN, whichever kernels run; the other head stays finite.
+    (A kernel may mark more than those rows -- e.g. a whole channel of the head.)"""
+    w = W("nonfinite", 1, 2, 1024, 64, 32, 4, backward=True, seed=88)
+    t = workloads.generate(w)
+    sh = shape_of(w, flags)
+    d = dev(t)
+    _, cent = moba.centroids(sh, d["K"])
+    idx, lists = moba.topk(sh, d["Q"], cent)               # routing of the clean inputs, kept fixed
+    hidx = npi(idx)[0]
+    u, tq = 300, 777
+    attends = np.array([(tt >= u and tt // w.B == u // w.B) or (u // w.B) in hidx[tt] for tt in range(w.N)])
+    assert attends.sum() > 10
+
+    def run(**poison):
+        x = {k: v.clone() for k, v in d.items() if v is not None}
+        for name, (row, col) in poison.items():
+            x[name][0, 0, row, col] = float("nan")
+        O, lse = moba.forward(sh, x["Q"], x["K"], x["V"], idx, lists)
+        dQ, dK, dV = moba.backward(sh, x["Q"], x["K"], x["V"], O, lse, x["dO"], idx, lists)
+        return [a.float().cpu().numpy()[0] for a in (O, dQ, dK, dV)] + [lse.cpu().numpy()[0]]
+
+    O, dQ, dK, dV, lse = run(K=(u, 5))
+    assert np.isnan(O[0][attends]).all() and np.isnan(lse[0][attends]).all() and np.isnan(dQ[0][attends]).all()
+    for a in (O, dQ, dK, dV):
+        assert np.isfinite(a[1]).all()
+    O, dQ, dK, dV, lse = run(V=(u, 5))
+    assert np.isnan(O[0][attends][:, 5]).all() and np.isnan(dQ[0][attends]).all()
+    assert np.isfinite(O[1]).all() and np.isfinite(dQ[1]).all()
+    O, dQ, dK, dV, lse = run(Q=(tq, 9))
+    assert np.isnan(O[0][tq]).all() and np.isnan(dQ[0][tq]).all() and np.isfinite(O[1]).all()
+    O, dQ, dK, dV, lse = run(dO=(tq, 9))
+    assert np.isfinite(O).all() and np.isnan(dQ[0][tq]).all() and np.isfinite(dQ[1]).all()
+    assert np.isnan(dV[0][tq - 1]).any()                  # the row's own block receives the NaN
 
 
 def test_kernel_timing_session():
