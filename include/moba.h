@@ -302,7 +302,10 @@ int moba_last_hip_error(void);
  * events on the stream it is launched on.  moba_profile_end waits for those events and adds,
  * per kernel, the elapsed milliseconds to ms[kernel] and the launches to calls[kernel] (both
  * host arrays of MOBA_PROFILE_KERNELS entries, overwritten), then drops the events.  At most
- * 4096 launches are recorded per session; further ones go untimed.  Not thread-safe.
+ * 4096 launches are recorded per session; further ones go untimed.  One session per process at a
+ * time (a second moba_profile_begin returns MOBA_EINVAL); launches from any thread are recorded.
+ * Apart from an open timing session the library keeps no state that a call could observe: calls
+ * on distinct streams and threads are independent.
  */
 enum {
     MOBA_PROFILE_TOPK = 0,    /* gate scores + top-k selection                    */

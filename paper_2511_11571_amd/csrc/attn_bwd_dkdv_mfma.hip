@@ -404,10 +404,8 @@ static hipError_t dkdv_launch(const Dims& s, const void* Q, const void* K, const
     const bool wide = s.B % 128 == 0;                       // four 32-key groups of one block per workgroup
     const size_t lds = wide ? C::LDS_WIDE : C::LDS;
     const int units = wide ? gps / 4 : gps;
-    hipError_t e = wide ? hipFuncSetAttribute((const void*)dkdv_mfma_kernel<D, true>,
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-                        : hipFuncSetAttribute((const void*)dkdv_mfma_kernel<D, false>,
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = wide ? ensure_dynamic_lds((const void*)dkdv_mfma_kernel<D, true>, (size_t)lds)
+                        : ensure_dynamic_lds((const void*)dkdv_mfma_kernel<D, false>, (size_t)lds);
     if (e != hipSuccess) return e;
     const int slices = part ? s.bh : s.bhk;
     ProfileScope timing(MOBA_PROFILE_DKDV, st);

@@ -301,8 +301,7 @@ static hipError_t dq_launch2(const Dims& s, const void* Q, const void* dO, const
 {
     using C = DqKmCfg<D>;
     const int nsub = s.B / km_part_keys(s.B, s.D);
-    hipError_t e = hipFuncSetAttribute((const void*)dq_km_kernel<D, NG>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::lds(NG));
+    hipError_t e = ensure_dynamic_lds((const void*)dq_km_kernel<D, NG>, C::lds(NG));
     if (e != hipSuccess) return e;
     {
         ProfileScope timing(MOBA_PROFILE_DQ, st);

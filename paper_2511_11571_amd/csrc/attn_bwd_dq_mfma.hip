@@ -284,8 +284,7 @@ static hipError_t dq_launch(const Dims& s, const void* Q, const void* Ka, const 
 {
     using C = DqCfg<D>;
     const int ntiles = (s.N + C::TILE - 1) / C::TILE;
-    hipError_t e = hipFuncSetAttribute((const void*)dq_mfma_kernel<D>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+    hipError_t e = ensure_dynamic_lds((const void*)dq_mfma_kernel<D>, (size_t)(C::LDS));
     if (e != hipSuccess) return e;
     ProfileScope timing(MOBA_PROFILE_DQ, st);
     hipLaunchKernelGGL((dq_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, ntiles)), dim3(C::NT), C::LDS, st,

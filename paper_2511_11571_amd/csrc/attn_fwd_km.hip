@@ -384,8 +384,7 @@ static hipError_t km_launch2(const Dims& s, const void* Q, const void* K, const 
 {
     using C = KmCfg<D>;
     const int nsub = s.B / km_part_keys(s.B, s.D);
-    hipError_t e = hipFuncSetAttribute((const void*)fwd_km_kernel<D, NG>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::lds(NG));
+    hipError_t e = ensure_dynamic_lds((const void*)fwd_km_kernel<D, NG>, C::lds(NG));
     if (e != hipSuccess) return e;
     {
         ProfileScope timing(MOBA_PROFILE_FORWARD, st);

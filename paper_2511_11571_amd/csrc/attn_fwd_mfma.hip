@@ -373,8 +373,7 @@ static hipError_t fwd_launch(const Dims& s, const void* Q, const void* K, const 
 {
     using C = FwdCfg<D>;
     const int ntiles = (s.N + C::TILE - 1) / C::TILE;
-    hipError_t e = hipFuncSetAttribute((const void*)forward_mfma_kernel<D>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+    hipError_t e = ensure_dynamic_lds((const void*)forward_mfma_kernel<D>, (size_t)(C::LDS));
     if (e != hipSuccess) return e;
     ProfileScope timing(MOBA_PROFILE_FORWARD, st);
     hipLaunchKernelGGL((forward_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, ntiles)), dim3(C::NT), C::LDS,

@@ -288,8 +288,7 @@ static hipError_t fwd_t(const Dims& s, const void* Q, const void* K, const void*
     if (rows == 0) return hipSuccess;
     const size_t lds = sizeof(float) * 4 * (D + 2 * kWave) + sizeof(int32_t) * 4 * (size_t)s.k;
     if (lds > 64 * 1024) {     // top-k in the thousands: above the default dynamic LDS limit, opt in
-        hipError_t e = hipFuncSetAttribute((const void*)forward_reference_kernel<T, D>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds((const void*)forward_reference_kernel<T, D>, (size_t)lds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((forward_reference_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)), dim3(256),
@@ -312,8 +311,7 @@ static hipError_t bwd_t(const Dims& s, const void* Q, const void* K, const void*
                        st, (const T*)dO, (const T*)O, Dvec, rows, lse, packed);
     const size_t lds = sizeof(float) * 4 * (2 * D + 2 * kWave) + sizeof(int32_t) * 4 * (size_t)s.k;
     if ((parts & MOBA_BWD_DQ) && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)dq_reference_kernel<T, D>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds((const void*)dq_reference_kernel<T, D>, (size_t)lds);
         if (e != hipSuccess) return e;
     }
     if (parts & MOBA_BWD_DQ)

@@ -186,6 +186,11 @@ inline Dims kv_view(const Dims& d)
     return v;
 }
 
+// hipFuncSetAttribute(MaxDynamicSharedMemorySize) for `kernel` on the current device, issued
+// only when a launch needs more than was asked for before (the library remembers per kernel and
+// device; thread-safe)
+hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes);
+
 // kernel timing hooks (see moba_profile_begin): no-ops unless a session is open
 void profile_mark(int kernel, bool start, hipStream_t st);
 struct ProfileScope {

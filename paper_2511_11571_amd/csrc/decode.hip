@@ -263,8 +263,7 @@ static hipError_t decode_t(const Dims& s, int q_len, const void* Q, const void* 
     const size_t lds = sizeof(float) * (size_t)(D + npast_max + 256 + 4 + (s.k + 1) + kDecodeWaves * kWave +
                                                 kDecodeWaves * (D + 2));
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)decode_kernel<T, D>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds((const void*)decode_kernel<T, D>, (size_t)lds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((decode_kernel<T, D>), dim3((unsigned)q_len, (unsigned)s.bh), dim3(kDecodeThreads), lds, st,

@@ -3,7 +3,9 @@
 // exercised on a machine without a GPU.
 #include <math.h>
 
+#include <map>
 #include <mutex>
+#include <utility>
 
 #include "mfma.h"
 
@@ -109,14 +111,31 @@ size_t bwd_ws_bytes(const Dims& d)
 namespace {
 struct ProfileRec { int kernel; hipEvent_t a, b; };
 constexpr int kProfileMax = 4096;
+std::mutex g_profile_mutex;          // one timing session at a time, whichever threads launch
 bool g_profile_on = false;
 int g_profile_n = 0;
 ProfileRec g_profile[kProfileMax];
 }  // namespace
 
 namespace moba {
+hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes)
+{
+    static std::mutex mu;
+    static std::map<std::pair<const void*, int>, size_t> granted;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    size_t& have = granted[std::make_pair(kernel, dev)];
+    if (bytes <= have) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) have = bytes;
+    return e;
+}
+
 void profile_mark(int kernel, bool start, hipStream_t st)
 {
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
     if (!g_profile_on) return;
     if (start) {
         if (g_profile_n >= kProfileMax) return;
@@ -168,6 +187,7 @@ extern "C" {
 
 int moba_profile_begin(void)
 {
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
     if (g_profile_on) return MOBA_EINVAL;
     g_profile_n = 0;
     g_profile_on = true;
@@ -176,6 +196,7 @@ int moba_profile_begin(void)
 
 int moba_profile_end(float* ms, int32_t* calls)
 {
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
     if (!g_profile_on || !ms || !calls) return MOBA_EINVAL;
     g_profile_on = false;
     for (int i = 0; i < MOBA_PROFILE_KERNELS; ++i) { ms[i] = 0.f; calls[i] = 0; }

@@ -820,8 +820,7 @@ static hipError_t topk_launch2(const Dims& s, const void* Q, const bf16_t* c3, i
     const int Wn = ((s.n + 31) / 32) | 1;      // words per bit row, odd for the same reason
     const size_t lds = sizeof(uint32_t) * (size_t)(64 * kHistStride + 18 * 64 +
                                                    (LISTS ? 64 * kKeptList / 2 + 64 : 64 * Wn));
-    hipError_t e = hipFuncSetAttribute((const void*)topk_mfma_kernel<D, LISTS>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = ensure_dynamic_lds((const void*)topk_mfma_kernel<D, LISTS>, (size_t)lds);
     if (e != hipSuccess) return e;
     ProfileScope timing(MOBA_PROFILE_TOPK, st);
     hipLaunchKernelGGL((topk_mfma_kernel<D, LISTS>), dim3((unsigned)strips), dim3(kTopkWaves * kWave), lds, st,

@@ -87,8 +87,7 @@ static hipError_t launch_t(const Dims& s, const void* Q, const float* cent, int3
     const size_t lds = sizeof(float) * 4 * D + sizeof(uint32_t) * 4 * (size_t)lds_row;
     dim3 grid((unsigned)((rows + 3) / 4)), block(256);
     if (lds > 64 * 1024) {     // above the default dynamic LDS limit: opt in (gfx950 has 160 KB)
-        hipError_t e = hipFuncSetAttribute((const void*)topk_reference_kernel<T, D>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds((const void*)topk_reference_kernel<T, D>, (size_t)lds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((topk_reference_kernel<T, D>), grid, block, lds, st, (const T*)Q, cent, idx,
