@@ -30,6 +30,8 @@
 // rate of the row-major pattern on this chip), (b) the workgroups of one XCD work on the same
 // slice and walk its blocks in ascending order, so these reads hit that XCD's L2, and (c) 16
 // waves per workgroup keep loads, LDS traffic and MFMA work of different units overlapped.
+#include <type_traits>
+
 #include "mfma.h"
 
 namespace moba {
@@ -117,7 +119,9 @@ __device__ __forceinline__ float key_float(int k)
     return __int_as_float(k ^ ((k >> 31) & 0x7fffffff));
 }
 
-template <int D>
+// GMAX: 32-key groups of a block that one unit takes together (2 needs B >= 64 and the registers
+// of d = 64)
+template <int D, int GMAX>
 __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Ka, const bf16_t* __restrict__ Vt,
     const uint32_t* __restrict__ vmax, const int32_t* __restrict__ idx, bf16_t* __restrict__ O,
@@ -196,22 +200,26 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) qb[ks].q = *reinterpret_cast<const uint4*>(qr + 64 * ks);
     };
-    // x: eight scores of this lane's row (log2 units, reference subtracted) -> probabilities,
-    // row-sum and P V into the row's accumulators
-    auto accumulate = [&](int row, float (&x)[8], const Frag (&va)[C::MT], bool valid) {
-        float lp = 0.f;
+    // x: eight scores of this lane's row (log2 units, reference subtracted) -> probabilities;
+    // their sum goes to lp and P V to the MFMA accumulators o, which a row's unit keeps over all
+    // the 32-key groups it covers; flush() then adds them to the row's accumulators in LDS,
+    // rounded to nearest once
+    auto attend = [&](float (&x)[8], const Frag (&va)[C::MT], float& lp, f32x4_t (&o)[C::MT], bool fresh) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) { x[e] = fast_exp2(x[e]); lp += x[e]; }
         Frag pb;
 #pragma unroll
         for (int e = 0; e < 4; ++e) pb.u[e] = pack2(x[2 * e], x[2 * e + 1]);
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt)
+            o[mt] = mfma16(va[mt], pb, fresh ? f32x4_t{0.f, 0.f, 0.f, 0.f} : o[mt]);
+    };
+    auto flush = [&](int row, float lp, const f32x4_t (&o)[C::MT], bool valid) {
         int oi[C::MT][4];
 #pragma unroll
-        for (int mt = 0; mt < C::MT; ++mt) {
-            const f32x4_t o = mfma16(va[mt], pb, f32x4_t{0.f, 0.f, 0.f, 0.f});
+        for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) oi[mt][i] = __float2int_rn(o[i]);
-        }
+            for (int i = 0; i < 4; ++i) oi[mt][i] = __float2int_rn(o[mt][i]);
         if (valid) {
             atomicAdd(&lsum[row], __float2int_rn(lp));
             int* orow = Os + (uint32_t)row * C::OSTRIDE + g * (D / 4);
@@ -220,6 +228,10 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
 #pragma unroll
                 for (int i = 0; i < 4; ++i) atomicAdd(&orow[4 * mt + i], oi[mt][i]);
         }
+    };
+    auto clear = [&](f32x4_t (&o)[C::MT]) {
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt) o[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     };
 
     for (int pass = 0; pass < 2; ++pass) {
@@ -233,7 +245,9 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
             Frag qb[C::KS];
             gather_q(row, qb);
             const float mr = pass == 1 ? __int_as_float(mkey[row]) : 0.f;
-            float mx = -INFINITY;
+            float mx = -INFINITY, lp = 0.f;
+            f32x4_t o[C::MT];
+            if (GMAX > 1) clear(o);
             for (int kap = kfirst; kap <= kown; ++kap) {
                 const bool own = kap == kown;
                 Frag ka[2][C::KS], va[C::MT];
@@ -258,10 +272,15 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
 #pragma unroll
                     for (int e = 0; e < 8; ++e) mx = max_nan(mx, x[e]);
                 } else {
-                    accumulate(row, x, va, true);
+                    attend(x, va, lp, o, GMAX == 1);
+                    if (GMAX == 1) {          // (no registers to keep the sums over the groups)
+                        flush(row, lp, o, true);
+                        lp = 0.f;
+                    }
                 }
             }
             if (pass == 0) atomicMax(&mkey[row], float_key(mx));
+            else if (GMAX > 1) flush(row, lp, o, true);
         }
 
         // routed blocks
@@ -278,52 +297,67 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
             }
             const int nblk = *next;
 
-            // one unit = one 32-key group of a listed block
-            auto load_unit = [&](int e, int gi, Frag (&ka)[2][C::KS], Frag (&va)[C::MT], int& beg,
-                                 int& end) {
+            // one unit = one or two 32-key groups of a listed block: the operands of both stay in
+            // registers while the block's rows go by, sixteen at a time, and a row's sums over
+            // both groups reach LDS in one set of adds
+            auto load_unit = [&](int e, int gi, auto gc, Frag (&ka)[GMAX][2][C::KS], Frag (&va)[GMAX][C::MT],
+                                 int& beg, int& end) {
                 const int j = __builtin_amdgcn_readfirstlane((int)ulist[e]);
                 beg = offs[j];
                 end = offs[j + 1];
-                const int kap = (lo + j) * NG + gi;
-                load_k(kap, ka);
-                if (pass == 1) load_v(kap, va);
+#pragma unroll
+                for (int u = 0; u < decltype(gc)::value; ++u) {
+                    const int kap = (lo + j) * NG + gi + u;
+                    load_k(kap, ka[u]);
+                    if (pass == 1) load_v(kap, va[u]);
+                }
             };
-            auto run_unit = [&](int beg_v, int end_v, const Frag (&ka)[2][C::KS], const Frag (&va)[C::MT]) {
+            auto run_unit = [&](int beg_v, int end_v, auto gc, const Frag (&ka)[GMAX][2][C::KS],
+                                const Frag (&va)[GMAX][C::MT]) {
+                constexpr int GC = decltype(gc)::value;
                 const int beg = __builtin_amdgcn_readfirstlane(beg_v);
                 const int end = min(__builtin_amdgcn_readfirstlane(end_v), (int)C::LCAP);
                 // Sub-tiles of 16 listed rows.  Lanes beyond the list work on whatever row id they
                 // read (always inside the tile) and add nothing.
-                auto gather = [&](int row, Frag (&qb)[C::KS], float& mr) {
-                    gather_q(row, qb);
-                    mr = pass == 1 ? __int_as_float(mkey[row]) : 0.f;
-                };
-                auto compute = [&](bool valid, int row, const Frag (&qb)[C::KS], float mr) {
-                    f32x4_t sc[2];
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt) {
-                        sc[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                        for (int ks = 0; ks < C::KS; ++ks) sc[mt] = mfma16(ka[mt][ks], qb[ks], sc[mt]);
-                    }
-                    if (pass == 0) {
-                        // (a NaN score makes the row's reference, and with it the row, NaN)
-                        float mx = max_nan(max_nan(sc[0][0], sc[0][1]), max_nan(sc[0][2], sc[0][3]));
-                        mx = max_nan(mx, max_nan(max_nan(sc[1][0], sc[1][1]), max_nan(sc[1][2], sc[1][3])));
-                        if (valid) atomicMax(&mkey[row], float_key(mx * c2));
-                    } else {
-                        float x[8];
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) x[e] = fmaf(sc[e >> 2][e & 3], c2, -mr);
-                        accumulate(row, x, va, valid);
-                    }
-                };
                 for (int c0 = beg; c0 < end; c0 += 16) {
                     const bool valid = m16 < end - c0;
                     const int row = rows8[c0 + m16] & (C::TILE - 1);
-                    Frag qA[C::KS];
-                    float mA;
-                    gather(row, qA, mA);
-                    compute(valid, row, qA, mA);
+                    Frag qb[C::KS];
+                    gather_q(row, qb);
+                    const float mr = pass == 1 ? __int_as_float(mkey[row]) : 0.f;
+                    auto scores = [&](int u, f32x4_t (&sc)[2]) {
+#pragma unroll
+                        for (int mt = 0; mt < 2; ++mt) {
+                            sc[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int ks = 0; ks < C::KS; ++ks) sc[mt] = mfma16(ka[u][mt][ks], qb[ks], sc[mt]);
+                        }
+                    };
+                    if (pass == 0) {
+                        // (a NaN score makes the row's reference, and with it the row, NaN)
+                        float mx = -INFINITY;
+#pragma unroll
+                        for (int u = 0; u < GC; ++u) {
+                            f32x4_t sc[2];
+                            scores(u, sc);
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) mx = max_nan(mx, sc[e >> 2][e & 3]);
+                        }
+                        if (valid) atomicMax(&mkey[row], float_key(mx * c2));
+                    } else {
+                        float lp = 0.f;
+                        f32x4_t o[C::MT];
+#pragma unroll
+                        for (int u = 0; u < GC; ++u) {
+                            f32x4_t sc[2];
+                            scores(u, sc);
+                            float x[8];
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) x[e] = fmaf(sc[e >> 2][e & 3], c2, -mr);
+                            attend(x, va[u], lp, o, u == 0);
+                        }
+                        flush(row, lp, o, valid);
+                    }
                 }
             };
 
@@ -331,11 +365,16 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
             int e = take_unit(take, lane);
             while (e < nblk) {
                 const int en = take_unit(take, lane);     // asked for early: its latency hides behind this unit
-                for (int gi = 0; gi < NG; ++gi) {
-                    Frag ka[2][C::KS], va[C::MT];
+                for (int gi = 0; gi < NG; gi += GMAX) {
+                    Frag ka[GMAX][2][C::KS], va[GMAX][C::MT];
                     int beg, end;
-                    load_unit(e, gi, ka, va, beg, end);
-                    run_unit(beg, end, ka, va);
+                    if (GMAX == 2 && gi + 1 < NG) {
+                        load_unit(e, gi, std::integral_constant<int, GMAX>{}, ka, va, beg, end);
+                        run_unit(beg, end, std::integral_constant<int, GMAX>{}, ka, va);
+                    } else {
+                        load_unit(e, gi, std::integral_constant<int, 1>{}, ka, va, beg, end);
+                        run_unit(beg, end, std::integral_constant<int, 1>{}, ka, va);
+                    }
                 }
                 e = en;
             }
@@ -366,17 +405,17 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
     }
 }
 
-template <int D>
+template <int D, int GMAX>
 static hipError_t fwd_launch(const Dims& s, const void* Q, const void* K, const void* Vt,
                              const uint32_t* vmax, const int32_t* idx, void* O, float* lse,
                              hipStream_t st)
 {
     using C = FwdCfg<D>;
     const int ntiles = (s.N + C::TILE - 1) / C::TILE;
-    hipError_t e = ensure_dynamic_lds((const void*)forward_mfma_kernel<D>, (size_t)(C::LDS));
+    hipError_t e = ensure_dynamic_lds((const void*)forward_mfma_kernel<D, GMAX>, (size_t)(C::LDS));
     if (e != hipSuccess) return e;
     ProfileScope timing(MOBA_PROFILE_FORWARD, st);
-    hipLaunchKernelGGL((forward_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, ntiles)), dim3(C::NT), C::LDS,
+    hipLaunchKernelGGL((forward_mfma_kernel<D, GMAX>), dim3((unsigned)schedule_grid(s.bh, ntiles)), dim3(C::NT), C::LDS,
                        st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)Vt, vmax, idx,
                        (bf16_t*)O, lse, s.N, s.B, s.k, s.scale, ntiles, s.bh, s.G);
     return hipGetLastError();
@@ -404,8 +443,9 @@ hipError_t launch_forward_mfma(const Dims& s, const void* Q, const void* K, cons
     }
     hipError_t e = launch_prepare(kv_view(s), K, V, p, st);  // K and V: one slice per key/value head
     if (e != hipSuccess) return e;
-    return s.D == 64 ? fwd_launch<64>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, st)
-                     : fwd_launch<128>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, st);
+    if (s.D == 128) return fwd_launch<128, 1>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, st);
+    return s.B >= 64 ? fwd_launch<64, 2>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, st)
+                     : fwd_launch<64, 1>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, st);
 }
 
 }  // namespace moba
