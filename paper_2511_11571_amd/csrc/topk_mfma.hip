@@ -178,7 +178,7 @@ void topk_mfma_kernel(
     const int m16 = lane & 15, g = lane >> 4;
     const int strip = blockIdx.x;
     uint32_t* hist = smem;
-    uint32_t* st_lo = hist + 64 * kHistStride;
+    uint32_t* st_lo = hist + 64 * kHistStride + 64;   // (the first look's rows start one word in, see there)
     uint32_t* st_sh = st_lo + 64;
     uint32_t* st_need = st_sh + 64;                // blocks still to find inside the current interval
     uint32_t* st_state = st_need + 64;
@@ -352,13 +352,15 @@ void topk_mfma_kernel(
         if (!__syncthreads_or(st_state[lane] == kUndecided && st_w[lane] > 0.f)) break;
         for (int i = tid; i < 64 * kHistStride; i += kTopkWaves * kWave) hist[i] = 0u;
         // bin = floor(x), x = (score - a) / w, taken from the mantissa of (x - 0.5) + 1.5 * 2^23
-        // (off by one bin where x is a whole number, which the first look can afford); queries
-        // without a window get bin -2
+        // (off by one bin where x is a whole number, which the first look can afford), clamped
+        // to -1 .. 64: a query's row of bins starts one word into its 65, so that scores below the
+        // window (and queries without a window: x = -2) count into a word in front of it and
+        // scores above a closed window into the word behind it, neither of which is ever read --
+        // no branch and no compare per score.
         constexpr float kMagic = 12582912.f;                   // 1.5 * 2^23
         constexpr int kMagicBits = 0x4B400000;
         uint32_t first4[4], span4[4];
-        float inv4[4], off4[4];
-        int cap4[4];
+        float inv4[4], off4[4], cap4[4];
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) {
             const int q = 16 * qt + m16;
@@ -367,17 +369,18 @@ void topk_mfma_kernel(
             span4[qt] = st_past[q] - first4[qt];
             inv4[qt] = w > 0.f ? 1.f / w : 0.f;
             off4[qt] = (w > 0.f ? -st_a[q] / w : -1.f) - 0.5f;
-            cap4[qt] = kMagicBits + (st_open[q] ? 63 : 64);    // open at the top: the last bin takes the rest
+            cap4[qt] = kMagic + (st_open[q] ? 63.f : 64.f);    // open at the top: the last bin takes the rest
         }
         __syncthreads();
         sweep_sample(1, [&](int qt, const f32x4_t& sc, int j0, auto tail) {
-            uint32_t* row = hist + (16 * qt + m16) * kHistStride;
+            uint32_t* row = hist + 1 + (16 * qt + m16) * kHistStride;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int bi = min(__float_as_int(fmaf(sc[i], inv4[qt], off4[qt]) + kMagic), cap4[qt]) - kMagicBits;
-                bool in = (uint32_t)bi < 64u;
-                if (decltype(tail)::value) in = in && (uint32_t)(j0 + i) - first4[qt] < span4[qt];
-                if (in) atomicAdd(&row[bi], 1u);
+                // (fminf takes a NaN to the cap, like the scores above the window)
+                const float x = fmaxf(fminf(fmaf(sc[i], inv4[qt], off4[qt]) + kMagic, cap4[qt]), kMagic - 1.f);
+                int bi = __float_as_int(x) - kMagicBits;
+                if (decltype(tail)::value) bi = (uint32_t)(j0 + i) - first4[qt] < span4[qt] ? bi : -1;
+                atomicAdd(&row[bi], 1u);
             }
         });
         __syncthreads();
@@ -385,7 +388,7 @@ void topk_mfma_kernel(
             const uint32_t need = st_cnt[lane];
             const float a = st_a[lane], w = st_w[lane];
             const bool open = st_open[lane] != 0u;
-            const uint32_t* row = hist + lane * kHistStride;
+            const uint32_t* row = hist + 1 + lane * kHistStride;
             uint32_t cum = 0, c = 0;
             int b = -1;
             for (int b0 = 60; b0 >= 0 && b < 0; b0 -= 4) {
@@ -552,24 +555,33 @@ void topk_mfma_kernel(
             }
         }
         __syncthreads();
-        // 4. the best of each band
-        int c = 0, want = 0;
+        // 4. the best of each band: how many of its records a query still wants (st_fill, free
+        // again), then a thread per record ranks it among the records of its query
         bool fits = true;
         if (band) {
             const int met = (int)st_cnt[q];
-            c = min(met, kCand);
-            want = (int)min((uint32_t)k, st_past[q] - st_first[q]) - kept;
-            fits = room && met <= kCand && want >= 0 && want <= c;
+            const int want = (int)min((uint32_t)k, st_past[q] - st_first[q]) - kept;
+            fits = room && met <= kCand && want >= 0 && want <= min(met, kCand);
+            if (half == 0) st_fill[q] = fits || !retry ? (uint32_t)max(want, 0) : 0u;
+        } else if (half == 0) {
+            st_fill[q] = 0u;
         }
-        if (band && (fits || !retry)) {
-            // (eight records are read at a time, so that the loop waits for LDS once per eight)
+        __syncthreads();
+        {
             // (key, then lower block first) as one 64-bit number: larger = better
             auto order = [](const uint2& r) { return ((uint64_t)r.x << 32) | (uint64_t)(~r.y); };
-            const uint2* seg = sorted + st_off[q];
-            for (int i = half; i < c; i += 2) {
-                const uint2 me = seg[i];
+            const int nrec_all = (int)(st_off[63] + st_cnt[63]);
+            for (int r = tid; r < nrec_all; r += kTopkWaves * kWave) {
+                const uint2 me = sorted[r];
+                const int rq = (int)(me.y >> 16);
+                const int want = (int)st_fill[rq];
+                const int c = min((int)st_cnt[rq], kCand);
+                const int base = (int)st_off[rq];
+                if (want == 0 || r - base >= c) continue;            // (records beyond kCand are not ranked)
+                const uint2* seg = sorted + base;
                 const uint64_t mine64 = order(me);
                 int rank = 0;
+                // (eight records are read at a time, so that the loop waits for LDS once per eight)
                 for (int o = 0; o < c; o += 8) {
                     uint2 v[8];
 #pragma unroll
@@ -577,7 +589,7 @@ void topk_mfma_kernel(
 #pragma unroll
                     for (int u = 0; u < 8; ++u) rank += (int)(o + u < c) & (int)(order(v[u]) > mine64);
                 }
-                if (rank < want) keep_atomic(q, (int)(me.y & 0xffffu));
+                if (rank < want) keep_atomic(rq, (int)(me.y & 0xffffu));
             }
         }
         __syncthreads();
@@ -742,8 +754,11 @@ void topk_mfma_kernel(
     // together in LDS (over the histograms) and leave as one run of consecutive 16-byte stores.
     __syncthreads();
     if (k <= 64) {
-        int32_t* stage = reinterpret_cast<int32_t*>(hist);           // [64][k]
-        for (int i = tid; i < 64 * k; i += kTopkWaves * kWave) stage[i] = -1;
+        // (rows of k + 1 words: the queries of a wave, which fill their rows side by side, then
+        // land on different banks)
+        int32_t* stage = reinterpret_cast<int32_t*>(hist);           // [64][k + 1]
+        const int ks1 = k + 1;
+        for (int i = tid; i < 64 * ks1; i += kTopkWaves * kWave) stage[i] = -1;
         __syncthreads();
         if constexpr (LISTS) {
             if (wave == 0) {
@@ -755,7 +770,7 @@ void topk_mfma_kernel(
                     for (; b >= 0 && mine[b] > v; --b) mine[b + 1] = mine[b];
                     mine[b + 1] = v;
                 }
-                for (int pos = 0; pos < c; ++pos) stage[lane * k + pos] = mine[pos];
+                for (int pos = 0; pos < c; ++pos) stage[lane * ks1 + pos] = mine[pos];
             }
         } else {
             // wave 0 takes the first half of a query's bit row, wave 1 the second, starting
@@ -769,7 +784,7 @@ void topk_mfma_kernel(
                 uint32_t word = selm[lane * Wn + w];
                 while (word) {
                     const int b = __ffs(word) - 1;
-                    if (pos < k) stage[lane * k + pos] = 32 * w + b;
+                    if (pos < k) stage[lane * ks1 + pos] = 32 * w + b;
                     ++pos;
                     word &= word - 1;
                 }
@@ -777,12 +792,14 @@ void topk_mfma_kernel(
         }
         __syncthreads();
         const int total = rows_here * k;                              // the strip's rows are one run in memory
-        if ((k & 3) == 0) {
-            const int4* src = reinterpret_cast<const int4*>(stage);
-            int4* dst = reinterpret_cast<int4*>(out);
-            for (int i = tid; i < total / 4; i += kTopkWaves * kWave) dst[i] = src[i];
-        } else {
-            for (int i = tid; i < total; i += kTopkWaves * kWave) out[i] = stage[i];
+        constexpr int NTH = kTopkWaves * kWave;
+        const int dq = NTH / k, dp = NTH % k;
+        int sq = tid / k, sp = tid % k;
+        for (int i = tid; i < total; i += NTH) {                      // a wave stores 256 consecutive bytes
+            out[i] = stage[sq * ks1 + sp];
+            sq += dq;
+            sp += dp;
+            if (sp >= k) { sp -= k; ++sq; }
         }
     } else if (wave == 0 && lane < rows_here) {                       // lane = query
         int32_t* row = out + (int64_t)lane * k;
@@ -818,7 +835,7 @@ static hipError_t topk_launch2(const Dims& s, const void* Q, const bf16_t* c3, i
     const int sps = (s.N + 63) / 64;
     const int64_t strips = (int64_t)sps * s.bh;
     const int Wn = ((s.n + 31) / 32) | 1;      // words per bit row, odd for the same reason
-    const size_t lds = sizeof(uint32_t) * (size_t)(64 * kHistStride + 18 * 64 +
+    const size_t lds = sizeof(uint32_t) * (size_t)(64 * kHistStride + 64 + 18 * 64 +
                                                    (LISTS ? 64 * kKeptList / 2 + 64 : 64 * Wn));
     hipError_t e = ensure_dynamic_lds((const void*)topk_mfma_kernel<D, LISTS>, (size_t)lds);
     if (e != hipSuccess) return e;
