@@ -296,8 +296,9 @@ void topk_mfma_kernel(
     // below does not depend on these being right).
     // Where to look: the largest and the smallest score of every undecided query, over all its
     // blocks when there are few tiles, over every sm-th tile otherwise.  The first window is
-    // [max / 4, max] (from the smallest score when no score is positive), 64 bins, open at the
-    // top (its last bin also takes whatever lies above).
+    // [max / 4, max] (from the smallest score when no score is positive, or when the query keeps
+    // more than a fifth of its candidates), 64 bins, open at the top (its last bin also takes
+    // whatever lies above).
     const int sm = min(max((ntile - tbeg) / 8, 1), LISTS ? 8 : 4);
     if (!exact_only && __syncthreads_or(st_state[lane] == kUndecided)) {
         for (int i = tid; i < 64; i += kTopkWaves * kWave) { hist[i * kHistStride] = 0u; hist[i * kHistStride + 1] = 0xffffffffu; }
@@ -332,7 +333,9 @@ void topk_mfma_kernel(
             const float m = key_score(hist[lane * kHistStride + 1], NAN);
             float w = 0.f, a = 0.f;
             if (M >= m && fabsf(M) < INFINITY && fabsf(m) < INFINITY) {
-                a = M > 0.f ? fmaxf(0.25f * M, m) : m;
+                // (a query that keeps more than a fifth of its candidates looks at all of them)
+                const bool many = 5u * st_cnt[lane] > st_past[lane] - st_first[lane];
+                a = M > 0.f && !many ? fmaxf(0.25f * M, m) : m;
                 const float top = M + (sm > 1 ? 0.5f : 0.0625f) * fabsf(M) + 1e-30f;
                 w = (top - a) * (1.f / 64.f);
             }
