@@ -82,6 +82,10 @@ def parse():
                     help="instead of a training-shaped step: time the decode-shaped forward for the "
                          "last Q_LEN positions of the workload's sequence plus 37 tokens (a ragged "
                          "last block); prints one JSON line")
+    ap.add_argument("--varlen", default="", metavar="L1,L2,...",
+                    help="a packed variable-length batch of these sequence lengths instead of one "
+                         "sequence (heads, d, B, top-k of --config / --shape): pad, centroids, gate top-k "
+                         "per sequence, forward, backward, unpad")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB device to device once (a kernel of "
@@ -257,6 +261,77 @@ def decode_bench(w, a, moba, binding, torch):
                      "bytes_per_launch": bytes_call, "traffic": None}}))
 
 
+def ragged_pairs(L, B, k):
+    """Attended (query, key) pairs of one sequence of L tokens whose last block may be short."""
+    nf, r = divmod(L, B)
+    past = lambda c: min(c, k)
+    return (B * B * sum(past(c) for c in range(nf)) + nf * B * (B + 1) // 2 +
+            r * B * past(nf) + r * (r + 1) // 2)
+
+
+def varlen_bench(w, a, moba, binding, torch):
+    """One step = the whole path over a packed batch: copy into the padded layout, centroids, gate
+    top-k with per-sequence candidates + lists, forward, backward, copy results back."""
+    lens = [int(x) for x in a.varlen.split(",")]
+    offs = [0]
+    for L in lens:
+        offs.append(offs[-1] + L)
+    T = offs[-1]
+    lay = moba.VarlenLayout(offs, w.B)
+    Tp = lay.padded_tokens
+    dt = w.torch_dtype
+    g = torch.Generator(device="cuda").manual_seed(w.seed)
+    Q, dO = (torch.randn((1, w.heads, T, w.d), generator=g, device="cuda").to(dt) for _ in range(2))
+    K, V = (torch.randn((1, w.hkv, T, w.d), generator=g, device="cuda").to(dt) for _ in range(2))
+    flags = binding.FLAG_SHARED_WORKSPACE
+    sh = moba.Shape(1, w.heads, Tp, w.d, w.B, w.k, 0, binding.BF16 if w.dtype == "bf16" else binding.F32,
+                    0.0, flags, w.kv_heads)
+    sizes = moba.workspace_bytes(sh)
+    ws_topk = torch.empty(max(sizes[0], 256), dtype=torch.uint8, device="cuda")
+    ws_att = torch.empty(max(sizes[1], sizes[2], 256), dtype=torch.uint8, device="cuda")
+    stages = ["pad", "centroids", "topk_lists", "forward", "backward", "unpad"]
+
+    def step(ev=None):
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        mark(0)
+        Qp, Kp, Vp, dOp = (lay.pad(x) for x in (Q, K, V, dO))
+        mark(1)
+        _, cent = moba.centroids(sh, Kp)
+        mark(2)
+        idx, lists = moba.topk_varlen(sh, lay, Qp, cent, ws=ws_topk)
+        mark(3)
+        O, lse = moba.forward(sh, Qp, Kp, Vp, idx, lists, ws=ws_att)
+        mark(4)
+        grads = moba.backward(sh, Qp, Kp, Vp, O, lse, dOp, idx, lists, ws=ws_att)
+        mark(5)
+        out = [lay.unpad(x) for x in (O, lse) + tuple(grads)]
+        mark(6)
+        return out
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(a.steps)]
+    t0 = time.perf_counter()
+    for s in range(a.steps):
+        step(ev[s])
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / a.steps
+    stage_ms = {n: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(a.steps)) / a.steps
+                for i, n in enumerate(stages)}
+    pairs = w.heads * sum(ragged_pairs(L, w.B, w.k) for L in lens)
+    print(json.dumps({
+        "metric": "moba_fwd_bwd_effective_tflops", "value": 14.0 * w.d * pairs / (ms * 1e-3) / 1e12,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "packed batch of %d sequences (%s tokens, %d in all, %d after padding to "
+                               "blocks), heads %d (%d key/value heads), d %d, B %d, top-k %d, "
+                               "forward+backward" % (len(lens), a.varlen, T, Tp, w.heads, w.hkv, w.d, w.B, w.k)},
+        "stage_ms": stage_ms, "attended_pairs": pairs}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -310,6 +385,9 @@ def main():
         a.config = 0
     if a.decode:
         decode_bench(w, a, moba, binding, torch)
+        return
+    if a.varlen:
+        varlen_bench(w, a, moba, binding, torch)
         return
     m = measure(w, a, moba, binding, workloads, torch)
     t, d, sh, R, dev = m["t"], m["d"], m["sh"], m["R"], m["dev"]

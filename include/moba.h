@@ -185,6 +185,8 @@ int moba_topk_static(const moba_shape* shape, const void* Q, const float* centro
  *                            multiple of 4: Q, K, V, O, dO, gradients, lse); padding rows are
  *                            written as zeros and dropped on the way back.  seq_offsets and
  *                            pad_offsets are DEVICE arrays here.  Source and destination differ.
+ *                            At most 65535 slices and 2^31 - 1 four-byte words per padded slice
+ *                            (MOBA_EUNSUPPORTED beyond, nothing launched).
  *   moba_varlen_block_first  block_first [T' / B] (device): first block of the sequence each block
  *                            of the padded layout belongs to
  *   moba_topk_varlen         moba_topk on the padded layout (shape.batch = 1, shape.seqlen = T'),

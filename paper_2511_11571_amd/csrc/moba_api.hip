@@ -366,6 +366,8 @@ int varlen_copy(bool pad, int32_t num_seqs, const int32_t* seq_offsets, const in
     if (num_seqs <= 0 || !seq_offsets || !pad_offsets || slices <= 0 || tokens < 0 || padded_tokens < tokens)
         return MOBA_EINVAL;
     if (row_bytes <= 0 || (row_bytes & 3) || !src || !dst || src == dst) return MOBA_EINVAL;
+    // (the slice is a grid axis of the copy; a slice's words are counted in 32 bits)
+    if (slices > 65535 || (int64_t)padded_tokens * (row_bytes / 4) >= ((int64_t)1 << 31)) return MOBA_EUNSUPPORTED;
     return hip_status(launch_varlen_copy(pad, seq_offsets, pad_offsets, num_seqs, slices, tokens, padded_tokens,
                                          row_bytes, src, dst, (hipStream_t)stream));
 }

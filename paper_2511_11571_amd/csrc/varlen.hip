@@ -24,30 +24,30 @@ __device__ __forceinline__ int seq_of(const int32_t* __restrict__ offs, int num,
 }
 
 // PAD: Xp[s][p] <- X[s][row of token p] or zeros;  !PAD: X[s][r] <- Xp[s][padded place of r].
-// One thread per 4-byte word of a row of the destination.
-template <bool PAD>
+// One thread per element of type T (16 bytes where rows and pointers allow, else 4) of a row of
+// the destination; blockIdx.y is the slice.
+template <bool PAD, typename T>
 __global__ __launch_bounds__(256) void varlen_copy_kernel(
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ pad_off, int num_seqs, int tokens,
-    int padded_tokens, int row_words, const uint32_t* __restrict__ src, uint32_t* __restrict__ dst,
-    int64_t total_words)
+    int padded_tokens, int row_elems, const T* __restrict__ src, T* __restrict__ dst)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total_words) return;
     const int drows = PAD ? padded_tokens : tokens, srows = PAD ? tokens : padded_tokens;
-    const int wd = (int)(i % row_words);
-    const int64_t row = i / row_words;
-    const int r = (int)(row % drows);
-    const int64_t s = row / drows;
-    uint32_t v = 0u;
+    const int i = blockIdx.x * 256 + threadIdx.x;            // (rows * row_elems < 2^31: checked by the launcher)
+    if (i >= drows * row_elems) return;
+    const int r = i / row_elems, e = i - r * row_elems;
+    const int64_t s = blockIdx.y;
+    int from = -1;                                           // source row, -1: zeros
     if (PAD) {
         const int q = seq_of(pad_off, num_seqs, r);
         const int t = r - pad_off[q];
-        if (t < seq_off[q + 1] - seq_off[q]) v = src[(s * srows + seq_off[q] + t) * row_words + wd];
+        if (t < seq_off[q + 1] - seq_off[q]) from = seq_off[q] + t;
     } else {
         const int q = seq_of(seq_off, num_seqs, r);
-        v = src[(s * srows + pad_off[q] + (r - seq_off[q])) * row_words + wd];
+        from = pad_off[q] + (r - seq_off[q]);
     }
-    dst[i] = v;
+    T v{};
+    if (from >= 0) v = src[(s * srows + from) * row_elems + e];
+    dst[(s * drows + r) * row_elems + e] = v;
 }
 
 __global__ __launch_bounds__(256) void varlen_block_first_kernel(const int32_t* __restrict__ pad_off,
@@ -59,21 +59,33 @@ __global__ __launch_bounds__(256) void varlen_block_first_kernel(const int32_t* 
     first[c] = pad_off[seq_of(pad_off, num_seqs, c * B)] / B;
 }
 
+template <typename T>
+static hipError_t varlen_copy_launch(bool pad, const int32_t* seq_off, const int32_t* pad_off, int num_seqs,
+                                     int64_t slices, int tokens, int padded_tokens, int row_elems,
+                                     const void* src, void* dst, hipStream_t st)
+{
+    const int64_t per_slice = (int64_t)(pad ? padded_tokens : tokens) * row_elems;
+    if (per_slice == 0 || slices == 0) return hipSuccess;
+    if (per_slice >= ((int64_t)1 << 31) || slices > 65535) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((per_slice + 255) / 256), (unsigned)slices);
+    if (pad)
+        hipLaunchKernelGGL((varlen_copy_kernel<true, T>), grid, dim3(256), 0, st, seq_off, pad_off, num_seqs,
+                           tokens, padded_tokens, row_elems, (const T*)src, (T*)dst);
+    else
+        hipLaunchKernelGGL((varlen_copy_kernel<false, T>), grid, dim3(256), 0, st, seq_off, pad_off, num_seqs,
+                           tokens, padded_tokens, row_elems, (const T*)src, (T*)dst);
+    return hipGetLastError();
+}
+
 hipError_t launch_varlen_copy(bool pad, const int32_t* seq_off, const int32_t* pad_off, int num_seqs,
                               int64_t slices, int tokens, int padded_tokens, int row_bytes, const void* src,
                               void* dst, hipStream_t st)
 {
-    const int row_words = row_bytes / 4;
-    const int64_t total = slices * (pad ? padded_tokens : tokens) * row_words;
-    if (total == 0) return hipSuccess;
-    const unsigned grid = (unsigned)((total + 255) / 256);
-    if (pad)
-        hipLaunchKernelGGL(varlen_copy_kernel<true>, dim3(grid), dim3(256), 0, st, seq_off, pad_off, num_seqs,
-                           tokens, padded_tokens, row_words, (const uint32_t*)src, (uint32_t*)dst, total);
-    else
-        hipLaunchKernelGGL(varlen_copy_kernel<false>, dim3(grid), dim3(256), 0, st, seq_off, pad_off, num_seqs,
-                           tokens, padded_tokens, row_words, (const uint32_t*)src, (uint32_t*)dst, total);
-    return hipGetLastError();
+    const bool wide = row_bytes % 16 == 0 && ((uintptr_t)src | (uintptr_t)dst) % 16 == 0;
+    return wide ? varlen_copy_launch<uint4>(pad, seq_off, pad_off, num_seqs, slices, tokens, padded_tokens,
+                                            row_bytes / 16, src, dst, st)
+                : varlen_copy_launch<uint32_t>(pad, seq_off, pad_off, num_seqs, slices, tokens, padded_tokens,
+                                               row_bytes / 4, src, dst, st);
 }
 
 hipError_t launch_varlen_block_first(const int32_t* pad_off, int num_seqs, int B, int nblocks, int32_t* first,
