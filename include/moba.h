@@ -24,7 +24,8 @@
  *   - Return value: MOBA_OK (0) or a negative moba_status.  No exceptions, no abort.
  *   - Supported: head_dim 64 or 128; seqlen a multiple of block; block >= 1;
  *     topk >= 0 (topk >= n-1 is full causal attention); conv_width 0 (none) or 1..8;
- *     at most 4096 key blocks per head for moba_topk; seqlen <= 2^24; batch * heads
+ *     at most 16384 key blocks per head for moba_topk with bf16 tensors, 4096 otherwise
+ *     (and with MOBA_FLAG_REFERENCE_KERNELS); seqlen <= 2^24; batch * heads
  *     <= 65535; R < 2^31.
  *   - R below is the number of (query, kept past block) pairs of one [N, d]
  *     slice, R = B * sum_{c<n} min(c, topk); it depends on the shape only

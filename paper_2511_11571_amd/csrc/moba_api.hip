@@ -22,7 +22,7 @@ int hip_status(hipError_t e)
     return MOBA_EHIP;
 }
 
-constexpr int kMaxBlocks = 4096;   // key blocks per head the scoring kernels keep in LDS
+constexpr int kMaxBlocks = 4096;   // key blocks per head the plain gate kernel and the decode kernel keep in LDS
 constexpr int kMaxTopk = 4096;
 constexpr int kMaxSeqlen = 1 << 24;       // the gathering kernels hold a row's byte offset inside its slice in 32 bits
 
@@ -315,7 +315,7 @@ int topk_call(const moba_shape* shape, const void* Q, const float* centroids, co
     if (!Q || !centroids || !blk_off) return MOBA_EINVAL;
     if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
     if (d.R > 0 && !blk_q) return MOBA_EINVAL;
-    if (d.n > kMaxBlocks) return MOBA_EUNSUPPORTED;
+    if (d.n > kMaxBlocks && !topk_mfma_supported(d)) return MOBA_EUNSUPPORTED;   // (the MFMA gate takes four times as many)
     if (!ws || ws_bytes < topk_ws_bytes(d)) return MOBA_EWORKSPACE;
     hipError_t e = topk_mfma_supported(d)
                        ? launch_topk_mfma(d, Q, centroids, topk_idx, topk_terms(d, ws), (hipStream_t)stream)
@@ -408,7 +408,7 @@ int moba_topk_static(const moba_shape* shape, const void* Q, const float* centro
     if (!Q || !centroids || !blk_off) return MOBA_EINVAL;
     if (d.k > 0 && !topk_idx) return MOBA_EINVAL;
     if (d.R > 0 && !blk_q) return MOBA_EINVAL;
-    if (d.n > kMaxBlocks) return MOBA_EUNSUPPORTED;
+    if (d.n > kMaxBlocks && !topk_mfma_supported(d)) return MOBA_EUNSUPPORTED;
     if (topk_ws_bytes(d) > kStaticScratchBytes) return MOBA_EWORKSPACE;
     hipError_t e = hipSuccess;
     void* ws = static_scratch(&e);

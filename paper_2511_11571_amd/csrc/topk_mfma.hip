@@ -41,7 +41,7 @@ constexpr int kRecWave = 512;             // records (blocks inside bands) a wav
 constexpr int kCandExact = kRecWave / 64; // exact search: a final bin this small is collected (64 queries always fit one wave's records)
 constexpr int kBandBins = 24;             // first look: a bin with more approximate scores than this is cut again
 constexpr int kLookSweeps = 3;            // histogram sweeps of the first look at most
-constexpr int kTopkMfmaMaxBlocks = 4096;  // a 16-bit histogram bin holds any count of blocks up to this
+constexpr int kTopkMfmaMaxBlocks = 16384; // the bit rows of a strip (8 bytes per block) still fit the LDS; 16-bit bins and block ids hold it
 
 // c3 <- the three bf16 terms of the fp32 centroids, in MFMA operand order: the 16 bytes lane
 // (m, g) feeds to the MFMA for blocks 16 jt + m, channels 32 ks + 8 g .. + 8, term t, sit at

@@ -138,8 +138,12 @@ def test_null_pointers_and_short_workspace(lib):
     assert lib.moba_key_conv_backward(ctypes.byref(conv), one, one, one, one, one, one, big, z) == -1  # in place
     two = ctypes.c_void_p(512)
     assert lib.moba_key_conv_backward(ctypes.byref(conv), one, one, one, two, one, one, ctypes.c_size_t(8), z) == -3
-    many = _shape(seqlen=32 * 5000).c()
-    assert lib.moba_topk(ctypes.byref(many), one, one, one, one, one, one, big, z) == -2
+    # key blocks per head: 16384 for the bf16 gate kernel, 4096 for the plain one (fp32 tensors,
+    # or bf16 with the plain kernels asked for)
+    for many in (_shape(seqlen=32 * 17000), _shape(seqlen=32 * 5000, dtype=binding.F32),
+                 _shape(seqlen=32 * 5000, flags=binding.FLAG_REFERENCE_KERNELS)):
+        assert lib.moba_topk(ctypes.byref(many.c()), one, one, one, one, one, one, big, z) == -2
+        assert lib.moba_topk_static(ctypes.byref(many.c()), one, one, one, one, one, z) == -2
 
 
 def test_binding_raises(lib):

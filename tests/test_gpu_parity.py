@@ -146,6 +146,38 @@ def test_key_conv_backward(oracle, dtype, d, width, N):
 MANY_BLOCKS = [W("n4096_B2", 1, 1, 8192, 64, 2, 8, seed=23), W("n4000_B2_k40", 1, 1, 8000, 64, 2, 40, seed=24)]
 
 
+# more blocks than the plain gate kernel takes: bit rows of 12000 blocks (96 KB of LDS per strip),
+# and 16384 blocks, the most the library takes, with the short kept lists of a small top-k
+HUGE_BLOCKS = [W("n12000_B2_k40", 1, 1, 24000, 64, 2, 40, seed=25), W("n16384_B2", 1, 1, 32768, 64, 2, 8, seed=26)]
+
+
+@pytest.mark.parametrize("flags", [pytest.param(0, id="default"),
+                                   pytest.param(binding.FLAG_GATE_EXACT_SEARCH, id="exact_search")])
+@pytest.mark.parametrize("w", HUGE_BLOCKS, ids=[w.name for w in HUGE_BLOCKS])
+def test_topk_beyond_4096_blocks(oracle, w, flags):
+    """Routing of sampled queries (the late ones, which have the most candidates, and a spread of the
+    rest) and the lists as the exact inverse of the GPU's routing."""
+    t = workloads.generate(w)
+    Q, K, Kp, V, dO = oracle_inputs(oracle, w, t)
+    C = oracle.centroids(Kp, w.B)
+    rng = np.random.default_rng(w.seed)
+    rows = np.unique(np.concatenate([rng.integers(0, w.N, 1500), np.arange(w.N - 300, w.N)])).astype(np.int64)
+    ref_idx, kth = oracle.topk(Q, C, w.B, w.k, rows=rows)
+    sh = shape_of(w, flags)
+    cent = torch.from_numpy(C).float().reshape(w.batch, w.heads, w.n, w.d).cuda()
+    idx, (off, ql) = moba.topk(sh, t["Q"].cuda(), cent)
+    got = npi(idx).reshape(w.bh * w.N, w.k)
+    exact, exempt = parity.routing_check(oracle, got[rows], ref_idx, kth, Q, C, w.B, rows=rows)
+    assert exempt < 0.02
+    srt = np.where(got < 0, np.iinfo(np.int32).max, got)
+    assert (np.diff(srt, axis=-1) >= 0).all()
+    g_off, g_ql = oracle.csr(npi(idx), w.B)
+    parity.check_lists(npi(off), npi(ql), npi(idx), g_off, g_ql, w.k)
+    # the plain gate kernel keeps a row of scores per wave in LDS and stops at 4096 blocks
+    with pytest.raises(RuntimeError):
+        moba.topk(shape_of(w, binding.FLAG_REFERENCE_KERNELS), t["Q"].cuda(), cent)
+
+
 # the selection with and without its approximate first look (the exact search alone is also what
 # queries with many equal scores fall back to)
 TOPK_FLAGS = FLAGS + [pytest.param(binding.FLAG_GATE_EXACT_SEARCH, id="exact_search")]
