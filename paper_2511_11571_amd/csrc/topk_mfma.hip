@@ -150,10 +150,15 @@ __device__ __forceinline__ void sweep_tiles(const char* __restrict__ c3s, int ti
 }
 
 constexpr int kTopkWaves = 2;             // waves per 64-query strip (= per workgroup)
-// The kept blocks of a query are collected in LDS either as a bit row over the n blocks or, for
-// small top-k, as a list of at most kKeptList block ids (2 KB per strip instead of 8 n bytes:
-// with thousands of blocks the bit rows would cap the workgroups per CU).
+// The kept blocks of a query are collected in LDS either as a bit row over the n blocks (KL = 0)
+// or as a list of at most KL block ids: 16 for a small top-k (2 KB per strip instead of 8 n
+// bytes: with thousands of blocks the bit rows would cap the workgroups per CU), 64 for a top-k
+// up to 64 of more than kBitRowBlocks blocks (8 KB per strip where the bit rows would take 32 KB
+// and more; each kept block costs a returning LDS atomic there, which only pays when few of the
+// blocks that go by are kept).
 constexpr int kKeptList = 16;
+constexpr int kKeptListLong = 64;
+constexpr int kBitRowBlocks = 4096;
 
 // states of a query
 enum : uint32_t {
@@ -164,7 +169,7 @@ enum : uint32_t {
     kDone = 4
 };
 
-template <int D, bool LISTS>
+template <int D, int KL>
 __global__ __launch_bounds__(kTopkWaves * kWave) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2)))
 void topk_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ c3, int ntile_all,
@@ -173,6 +178,7 @@ void topk_mfma_kernel(
 {
     extern __shared__ uint32_t smem[];
     constexpr int KS = D / 32;
+    constexpr bool LISTS = KL > 0;
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int m16 = lane & 15, g = lane >> 4;
@@ -197,14 +203,14 @@ void topk_mfma_kernel(
     uint32_t* st_fill = st_off + 64;               //   the next free place among them
     uint32_t* wrec = st_fill + 64;                 // [kTopkWaves, padded to 64] records each wave wrote
     uint32_t* selm = wrec + 64;                    // [64][Wn] kept-block bits, or:
-    uint16_t* lst = reinterpret_cast<uint16_t*>(selm);      // [64][kKeptList] kept blocks, any order
-    uint32_t* lcnt = selm + 64 * kKeptList / 2;             // [64] their number
-    const int sel_words = LISTS ? 64 * kKeptList / 2 + 64 : 64 * Wn;
+    uint16_t* lst = reinterpret_cast<uint16_t*>(selm);      // [64][KL] kept blocks, any order
+    uint32_t* lcnt = selm + 64 * KL / 2;                    // [64] their number
+    const int sel_words = LISTS ? 64 * KL / 2 + 64 : 64 * Wn;
     // one more kept block of query q (concurrent callers) / (only caller for q)
     auto keep_atomic = [&](int q, int blk) {
         if constexpr (LISTS) {
             const uint32_t slot = atomicAdd(&lcnt[q], 1u);
-            if (slot < (uint32_t)kKeptList) lst[q * kKeptList + slot] = (uint16_t)blk;
+            if (slot < (uint32_t)KL) lst[q * KL + slot] = (uint16_t)blk;
         } else {
             atomicOr(&selm[q * Wn + (blk >> 5)], 1u << (blk & 31));
         }
@@ -212,7 +218,7 @@ void topk_mfma_kernel(
     auto keep_plain = [&](int q, int blk) {
         if constexpr (LISTS) {
             const uint32_t slot = lcnt[q]++;
-            if (slot < (uint32_t)kKeptList) lst[q * kKeptList + slot] = (uint16_t)blk;
+            if (slot < (uint32_t)KL) lst[q * KL + slot] = (uint16_t)blk;
         } else {
             selm[q * Wn + (blk >> 5)] |= 1u << (blk & 31);
         }
@@ -764,16 +770,16 @@ void topk_mfma_kernel(
         for (int i = tid; i < 64 * ks1; i += kTopkWaves * kWave) stage[i] = -1;
         __syncthreads();
         if constexpr (LISTS) {
-            if (wave == 0) {
-                uint16_t* mine = lst + lane * kKeptList;
-                const int c = min((int)lcnt[lane], min(k, kKeptList));
-                for (int a = 1; a < c; ++a) {                 // insertion sort, ascending
-                    const uint16_t v = mine[a];
-                    int b = a - 1;
-                    for (; b >= 0 && mine[b] > v; --b) mine[b + 1] = mine[b];
-                    mine[b + 1] = v;
-                }
-                for (int pos = 0; pos < c; ++pos) stage[lane * ks1 + pos] = mine[pos];
+            // two threads per query: a kept block goes to the place given by the number of
+            // smaller ones (block ids are distinct)
+            const int q = tid >> 1;
+            const uint16_t* mine = lst + q * KL;
+            const int c = min((int)lcnt[q], min(k, KL));
+            for (int a = tid & 1; a < c; a += 2) {
+                const uint16_t v = mine[a];
+                int rank = 0;
+                for (int b = 0; b < c; ++b) rank += (int)(mine[b] < v);
+                stage[q * ks1 + rank] = v;
             }
         } else {
             // wave 0 takes the first half of a query's bit row, wave 1 the second, starting
@@ -831,7 +837,7 @@ bool topk_mfma_supported(const Dims& s)
            s.n <= kTopkMfmaMaxBlocks && s.k > 0;
 }
 
-template <int D, bool LISTS>
+template <int D, int KL>
 static hipError_t topk_launch2(const Dims& s, const void* Q, const bf16_t* c3, int32_t* idx,
                                hipStream_t st)
 {
@@ -839,11 +845,11 @@ static hipError_t topk_launch2(const Dims& s, const void* Q, const bf16_t* c3, i
     const int64_t strips = (int64_t)sps * s.bh;
     const int Wn = ((s.n + 31) / 32) | 1;      // words per bit row, odd for the same reason
     const size_t lds = sizeof(uint32_t) * (size_t)(64 * kHistStride + 64 + 18 * 64 +
-                                                   (LISTS ? 64 * kKeptList / 2 + 64 : 64 * Wn));
-    hipError_t e = ensure_dynamic_lds((const void*)topk_mfma_kernel<D, LISTS>, (size_t)lds);
+                                                   (KL > 0 ? 64 * KL / 2 + 64 : 64 * Wn));
+    hipError_t e = ensure_dynamic_lds((const void*)topk_mfma_kernel<D, KL>, (size_t)lds);
     if (e != hipSuccess) return e;
     ProfileScope timing(MOBA_PROFILE_TOPK, st);
-    hipLaunchKernelGGL((topk_mfma_kernel<D, LISTS>), dim3((unsigned)strips), dim3(kTopkWaves * kWave), lds, st,
+    hipLaunchKernelGGL((topk_mfma_kernel<D, KL>), dim3((unsigned)strips), dim3(kTopkWaves * kWave), lds, st,
                        (const bf16_t*)Q, c3, (s.n + 15) / 16, idx, s.N, s.B, s.n, s.k, sps, Wn, s.G,
                        (s.flags & MOBA_FLAG_GATE_EXACT_SEARCH) ? 1 : 0, s.blk_first);
     return hipGetLastError();
@@ -853,8 +859,9 @@ template <int D>
 static hipError_t topk_launch(const Dims& s, const void* Q, const bf16_t* c3, int32_t* idx,
                               hipStream_t st)
 {
-    return s.k <= kKeptList ? topk_launch2<D, true>(s, Q, c3, idx, st)
-                            : topk_launch2<D, false>(s, Q, c3, idx, st);
+    if (s.k <= kKeptList) return topk_launch2<D, kKeptList>(s, Q, c3, idx, st);
+    if (s.k <= kKeptListLong && s.n > kBitRowBlocks) return topk_launch2<D, kKeptListLong>(s, Q, c3, idx, st);
+    return topk_launch2<D, 0>(s, Q, c3, idx, st);
 }
 
 hipError_t launch_topk_mfma(const Dims& s, const void* Q, const float* cent, int32_t* idx, void* ws,

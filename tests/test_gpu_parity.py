@@ -146,9 +146,11 @@ def test_key_conv_backward(oracle, dtype, d, width, N):
 MANY_BLOCKS = [W("n4096_B2", 1, 1, 8192, 64, 2, 8, seed=23), W("n4000_B2_k40", 1, 1, 8000, 64, 2, 40, seed=24)]
 
 
-# more blocks than the plain gate kernel takes: bit rows of 12000 blocks (96 KB of LDS per strip),
-# and 16384 blocks, the most the library takes, with the short kept lists of a small top-k
-HUGE_BLOCKS = [W("n12000_B2_k40", 1, 1, 24000, 64, 2, 40, seed=25), W("n16384_B2", 1, 1, 32768, 64, 2, 8, seed=26)]
+# more blocks than the plain gate kernel takes: kept lists of 64 entries (top-k 40 of 12000 blocks),
+# bit rows of 6000 blocks (top-k 80; 48 KB of LDS per strip), and 16384 blocks, the most the
+# library takes, with the short kept lists of a small top-k
+HUGE_BLOCKS = [W("n12000_B2_k40", 1, 1, 24000, 64, 2, 40, seed=25), W("n6000_B2_k80", 1, 1, 12000, 64, 2, 80, seed=27),
+               W("n16384_B2", 1, 1, 32768, 64, 2, 8, seed=26)]
 
 
 @pytest.mark.parametrize("flags", [pytest.param(0, id="default"),
