@@ -261,14 +261,6 @@ def decode_bench(w, a, moba, binding, torch):
                      "bytes_per_launch": bytes_call, "traffic": None}}))
 
 
-def ragged_pairs(L, B, k):
-    """Attended (query, key) pairs of one sequence of L tokens whose last block may be short."""
-    nf, r = divmod(L, B)
-    past = lambda c: min(c, k)
-    return (B * B * sum(past(c) for c in range(nf)) + nf * B * (B + 1) // 2 +
-            r * B * past(nf) + r * (r + 1) // 2)
-
-
 def varlen_bench(w, a, moba, binding, torch):
     """One step = the whole path over a packed batch: copy into the padded layout, centroids, gate
     top-k with per-sequence candidates + lists, forward, backward, copy results back."""
@@ -321,7 +313,8 @@ def varlen_bench(w, a, moba, binding, torch):
     ms = 1e3 * (time.perf_counter() - t0) / a.steps
     stage_ms = {n: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(a.steps)) / a.steps
                 for i, n in enumerate(stages)}
-    pairs = w.heads * sum(ragged_pairs(L, w.B, w.k) for L in lens)
+    import workloads
+    pairs = w.heads * sum(workloads.ragged_pairs(L, w.B, w.k) for L in lens)
     print(json.dumps({
         "metric": "moba_fwd_bwd_effective_tflops", "value": 14.0 * w.d * pairs / (ms * 1e-3) / 1e12,
         "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,

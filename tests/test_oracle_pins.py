@@ -608,3 +608,16 @@ def test_paper_sparsity_identity():
         # exact count by enumeration
         ref = sum(min(t // B, k) * B + (t % B) + 1 for t in range(N))
         assert pairs == ref
+
+
+def test_ragged_pair_count_is_the_size_of_the_mask():
+    """The pair counter of the packed-batch benchmark against the explicit mask of a sequence
+    with a short last block (tests/brute.py)."""
+    import workloads
+    rng = np.random.default_rng(77)
+    for L, B, k in ((37, 8, 2), (64, 8, 3), (5, 8, 4), (50, 4, 20), (33, 16, 1), (40, 8, 0)):
+        Q, K = rng.standard_normal((L, 8)), rng.standard_normal((L, 8))
+        mask, _ = brute.ragged_block_mask(Q, K, B, k)
+        assert int(mask.sum()) == workloads.ragged_pairs(L, B, k)
+        if L % B == 0:
+            assert workloads.ragged_pairs(L, B, k) == workloads.attended_pairs_per_slice(L, B, k)

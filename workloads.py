@@ -78,6 +78,15 @@ def attended_pairs_per_slice(N, B, k):
     return B * routes_per_slice(N, B, k) + n * B * (B + 1) // 2
 
 
+def ragged_pairs(L, B, k):
+    """Attended (query, key) pairs of one sequence of L tokens whose last block may be short
+    (packed variable-length batches): every query keeps min(k, complete blocks before its own)
+    past blocks of B keys and the causal part of its own block."""
+    nf, r = divmod(L, B)
+    return (B * B * sum(min(c, k) for c in range(nf)) + nf * B * (B + 1) // 2 +
+            r * B * min(nf, k) + r * (r + 1) // 2)
+
+
 def generate(w: Workload, device="cpu"):
     """Returns a dict of CPU tensors: Q,dO [batch,heads,N,d] and K,V [batch,kv_heads,N,d] in
     the I/O type, conv_w [kv_heads,d,W] fp32 (or None)."""
