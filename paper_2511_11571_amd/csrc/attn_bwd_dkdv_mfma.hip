@@ -71,7 +71,7 @@ void dkdv_mfma_kernel(
     const bf16_t* __restrict__ dO, const float2* __restrict__ ld,
     const int32_t* __restrict__ off, const int32_t* __restrict__ ql, bf16_t* __restrict__ dK,
     bf16_t* __restrict__ dV, int N, int B, int n, float scale, int64_t R, int groups_per_slice, int bhk,
-    int G, float* __restrict__ part)
+    int G, float* __restrict__ part, int order)
 {
     using C = DkvCfg<D>;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -89,7 +89,7 @@ void dkdv_mfma_kernel(
     // 15 % with 16 heads on one key/value head).
     const int slices = part ? bhk * G : bhk;
     int slice, unit;                                        // slice; 32-key group or 128-key part
-    if (!schedule(blockIdx.x, slices, groups_per_slice, slice, unit)) return;
+    if (!schedule(blockIdx.x, order * slices, groups_per_slice, slice, unit)) return;   // order -1: slice after slice
     const int skv = part ? slice / G : slice;               // key/value slice
     const int s_first = part ? slice : skv * G, s_last = part ? slice + 1 : (skv + 1) * G;
     const int kap = WIDE ? 4 * unit + wave : unit;          // this wave's 32-key group inside the slice
@@ -408,17 +408,18 @@ static hipError_t dkdv_launch(const Dims& s, const void* Q, const void* K, const
                         : ensure_dynamic_lds((const void*)dkdv_mfma_kernel<D, false>, (size_t)lds);
     if (e != hipSuccess) return e;
     const int slices = part ? s.bh : s.bhk;
+    const int order = slices > 1 ? slice_major(s, 2) : 1;       // (gathers Q and dO rows)
     ProfileScope timing(MOBA_PROFILE_DKDV, st);
     if (wide)
-        hipLaunchKernelGGL((dkdv_mfma_kernel<D, true>), dim3((unsigned)schedule_grid(slices, units)), dim3(C::NT),
+        hipLaunchKernelGGL((dkdv_mfma_kernel<D, true>), dim3((unsigned)schedule_grid(order * slices, units)), dim3(C::NT),
                            lds, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO,
                            ld, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
-                           s.bhk, s.G, part);
+                           s.bhk, s.G, part, order);
     else
-        hipLaunchKernelGGL((dkdv_mfma_kernel<D, false>), dim3((unsigned)schedule_grid(slices, units)), dim3(C::NT),
+        hipLaunchKernelGGL((dkdv_mfma_kernel<D, false>), dim3((unsigned)schedule_grid(order * slices, units)), dim3(C::NT),
                            lds, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO,
                            ld, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
-                           s.bhk, s.G, part);
+                           s.bhk, s.G, part, order);
     if (part) {
         const int64_t cps = (int64_t)s.N * D / 8, total = 2 * cps * s.bhk;
         hipLaunchKernelGGL(dkdv_heads_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, part,

@@ -305,10 +305,11 @@ static hipError_t dq_launch2(const Dims& s, const void* Q, const void* dO, const
     if (e != hipSuccess) return e;
     {
         ProfileScope timing(MOBA_PROFILE_DQ, st);
-        hipLaunchKernelGGL((dq_km_kernel<D, NG>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
+        const int bhs = slice_major(s, 2) * s.bh;           // (gathers Q and dO rows)
+        hipLaunchKernelGGL((dq_km_kernel<D, NG>), dim3((unsigned)schedule_grid(bhs, s.n * nsub)),
                            dim3(C::NT), C::lds(NG), st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)K,
                            (const bf16_t*)V, (const bf16_t*)Kt, ld, off, ql, PdQ, s.N, s.B, s.n,
-                           s.k, nsub, s.scale, s.R, s.bh, s.G);
+                           s.k, nsub, s.scale, s.R, bhs, s.G);
     }
     const int64_t rows = (int64_t)s.bh * s.N;
     const int rpw = 256 / (D / 8);

@@ -388,9 +388,10 @@ static hipError_t km_launch2(const Dims& s, const void* Q, const void* K, const 
     if (e != hipSuccess) return e;
     {
         ProfileScope timing(MOBA_PROFILE_FORWARD, st);
-        hipLaunchKernelGGL((fwd_km_kernel<D, NG>), dim3((unsigned)schedule_grid(s.bh, s.n * nsub)),
+        const int bhs = slice_major(s, 1) * s.bh;           // (gathers Q rows)
+        hipLaunchKernelGGL((fwd_km_kernel<D, NG>), dim3((unsigned)schedule_grid(bhs, s.n * nsub)),
                            dim3(C::NT), C::lds(NG), st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)Vt,
-                           off, ql, PO, Pml, s.N, s.B, s.n, s.k, nsub, s.scale, s.R, s.bh, s.G);
+                           off, ql, PO, Pml, s.N, s.B, s.n, s.k, nsub, s.scale, s.R, bhs, s.G);
     }
     const int64_t rows = (int64_t)s.bh * s.N;
     const int rpw = 256 / (D / 8);

@@ -200,6 +200,18 @@ def test_latency_sweep_shape_key_major(oracle):
         print(w.name, s, check_slice(oracle, w, t, out, s, 1024, [], rng), flush=True)
 
 
+def test_long_sequence_slice_after_slice(oracle):
+    """N = 131072 of the sweep's shape with three heads: Q and dO of a slice take 32 MB, from where
+    on the key-block-major dQ kernel and the dK/dV kernel work through one slice at a time over
+    the whole chip instead of one slice per XCD (the forward does at the config-4 shape)."""
+    w = workloads.Workload("sweep_N131072_h3", 1, 3, 131072, 64, 128, 8, backward=True, seed=9200)
+    t, out = run_gpu(w)
+    rng = np.random.default_rng(8)
+    print(w.name, 1, check_slice(oracle, w, t, out, 1, 768, [0, 3, 500, 1023], rng), flush=True)
+    for s in (0, 2):
+        print(w.name, s, check_slice(oracle, w, t, out, s, 512, [], rng), flush=True)
+
+
 def test_config4_conv_backward(oracle):
     """Backward of the key convolution at the config-4 shape (1024 chunks of 128 rows per slice,
     row offsets beyond 2^31 bytes): two whole slices against the oracle.  The weights are per
