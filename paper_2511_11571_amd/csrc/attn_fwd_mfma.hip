@@ -21,7 +21,10 @@
 // Which rows go with which key block is a set of compact row lists in LDS (one byte per
 // (row, block) pair, sorted by block), built once per tile from the query-major routing by a
 // counting sort and used by both passes; the earlier 32-key groups of a row's own block
-// (B > 32) are dense work and go with the own group.
+// (B > 32) are dense work and go with the own group.  With blocks of 64 keys and more (d = 64)
+// a wave takes two 32-key groups of a block at a time: their operands stay in registers while
+// the block's listed rows go by and a row's P V over both groups leaves the MFMA accumulators
+// as one set of LDS adds (half the adds per key).
 //
 // What bounds the kernel is the operand traffic, not the arithmetic: with scattered routing a
 // 256-query tile meets a key block with ~16 of its rows, so every 1-2 MFMA sub-tiles need a
