@@ -631,3 +631,68 @@ def test_kernel_timing_session():
 def _closed_session():
     moba.profile_begin()
     return moba.profile_end()
+
+
+# ------------------------------------------------------------------ buffers
+
+GUARD = 4096
+
+
+def _guarded(nbytes, like_dtype=torch.uint8, shape=None):
+    """A buffer of nbytes (or of `shape` elements of like_dtype) inside a larger allocation whose
+    GUARD bytes in front and behind hold a pattern: -> (view, check) where check() fails if a kernel
+    wrote outside the view."""
+    if shape is not None:
+        nbytes = int(np.prod(shape)) * torch.empty((), dtype=like_dtype).element_size()
+    nbytes = max(int(nbytes), 256)
+    padded = (nbytes + 255) // 256 * 256
+    big = torch.full((padded + 2 * GUARD,), 0x5A, dtype=torch.uint8, device="cuda")
+    view = big[GUARD:GUARD + nbytes]
+    if shape is not None:
+        view = view.view(like_dtype).reshape(shape)
+
+    def check(what):
+        torch.cuda.synchronize()
+        assert bool((big[:GUARD] == 0x5A).all()) and bool((big[GUARD + nbytes:] == 0x5A).all()), \
+            "%s: bytes outside the buffer were written" % what
+    return view, check
+
+
+@pytest.mark.parametrize("flags", [pytest.param(0, id="default"), pytest.param(REF, id="plain"),
+                                   pytest.param(binding.FLAG_KEY_MAJOR, id="keymajor"),
+                                   pytest.param(binding.FLAG_QUERY_TILES, id="tiles"),
+                                   pytest.param(binding.FLAG_QUERY_TILES | binding.FLAG_SHARED_WORKSPACE, id="tiles_shared")])
+@pytest.mark.parametrize("w", [SMALL[0], SMALL[1], SMALL[2], SMALL[10], SMALL[11],
+                               W("gqa_B64", 1, 4, 1536, 64, 64, 5, kv_heads=2, seed=81),
+                               W("conv_d128_B128", 1, 2, 1280, 128, 128, 3, conv_width=3, seed=82)],
+                         ids=lambda w: w.name)
+def test_no_kernel_writes_outside_its_buffers(w, flags):
+    """Every workspace and every output the caller hands over lies between guard bytes; the whole
+    chain (centroids, gate top-k + lists, forward, backward) must leave them as they were."""
+    t = dev(workloads.generate(w))
+    sh = shape_of(w, flags)
+    dt = t["Q"].dtype
+    sizes = moba.workspace_bytes(sh)
+    ws_topk, c_topk = _guarded(sizes[0])
+    if flags & binding.FLAG_SHARED_WORKSPACE:
+        ws_fwd, c_fwd = _guarded(max(sizes[1], sizes[2]))
+        ws_bwd, c_bwd = ws_fwd, c_fwd
+    else:
+        ws_fwd, c_fwd = _guarded(sizes[1])
+        ws_bwd, c_bwd = _guarded(sizes[2])
+    cent, c_cent = _guarded(0, torch.float32, (w.batch, w.hkv, w.n, w.d))
+    Keff, c_keff = _guarded(0, dt, tuple(t["K"].shape))
+    O, c_O = _guarded(0, dt, tuple(t["Q"].shape))
+    lse, c_lse = _guarded(0, torch.float32, (w.batch, w.heads, w.N))
+    dQ, c_dQ = _guarded(0, dt, tuple(t["Q"].shape))
+    dK, c_dK = _guarded(0, dt, tuple(t["K"].shape))
+    dV, c_dV = _guarded(0, dt, tuple(t["V"].shape))
+    Ke, c = moba.centroids(sh, t["K"], t["conv_w"], K_eff=Keff, out=cent)
+    idx, lists = moba.topk(sh, t["Q"], c, ws=ws_topk)
+    moba.forward(sh, t["Q"], Ke, t["V"], idx, lists, ws=ws_fwd, O=O, lse=lse)
+    moba.backward(sh, t["Q"], Ke, t["V"], O, lse, t["dO"], idx, lists, ws=ws_bwd, out=(dQ, dK, dV))
+    for what, chk in (("top-k workspace", c_topk), ("forward workspace", c_fwd), ("backward workspace", c_bwd),
+                      ("centroids", c_cent), ("K_eff", c_keff), ("O", c_O), ("lse", c_lse), ("dQ", c_dQ),
+                      ("dK", c_dK), ("dV", c_dV)):
+        chk(what)
+    assert torch.isfinite(O.float()).all() and torch.isfinite(dK.float()).all()
