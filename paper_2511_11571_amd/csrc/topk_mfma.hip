@@ -230,7 +230,9 @@ void topk_mfma_kernel(
     };
 
     const int s = strip / strips_per_slice;
-    const int t0 = (strip % strips_per_slice) * 64;
+    // (the late strips of a slice, which have the most candidates, start first: the kernel then
+    // ends on short strips)
+    const int t0 = (strips_per_slice - 1 - strip % strips_per_slice) * 64;
     const int rows_here = min(64, N - t0);
     const char* c3s = reinterpret_cast<const char*>(c3) + (int64_t)(s / G) * ntile_all * (3 * KS * 1024);   // G query heads share the centroids
     int32_t* out = idx + ((int64_t)s * N + t0) * k;
