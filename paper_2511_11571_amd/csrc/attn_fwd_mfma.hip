@@ -121,6 +121,24 @@ __device__ __forceinline__ float key_float(int k)
 {
     return __int_as_float(k ^ ((k >> 31) & 0x7fffffff));
 }
+// sum / maximum (NaN-propagating) over the four lanes m16 + 16 g, g = 0 .. 3, in all of them:
+// v_permlane32_swap / v_permlane16_swap exchange the halves / the odd and even quarters of a wave
+__device__ __forceinline__ float sum_over_g(float x)
+{
+    const uint32_t b = __float_as_uint(x);
+    const auto h = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+    const uint32_t y = __float_as_uint(__uint_as_float(h[0]) + __uint_as_float(h[1]));
+    const auto q = __builtin_amdgcn_permlane16_swap(y, y, false, false);
+    return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
+__device__ __forceinline__ float max_over_g(float x)
+{
+    const uint32_t b = __float_as_uint(x);
+    const auto h = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+    const uint32_t y = __float_as_uint(max_nan(__uint_as_float(h[0]), __uint_as_float(h[1])));
+    const auto q = __builtin_amdgcn_permlane16_swap(y, y, false, false);
+    return max_nan(__uint_as_float(q[0]), __uint_as_float(q[1]));
+}
 
 // GMAX: 32-key groups of a block that one unit takes together (2 needs B >= 64 and the registers
 // of d = 64)
@@ -223,8 +241,9 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
         for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
             for (int i = 0; i < 4; ++i) oi[mt][i] = __float2int_rn(o[mt][i]);
+        lp = sum_over_g(lp);                       // the row's 32 (64) keys in one add, from one lane
         if (valid) {
-            atomicAdd(&lsum[row], __float2int_rn(lp));
+            if (g == 0) atomicAdd(&lsum[row], __float2int_rn(lp));
             int* orow = Os + (uint32_t)row * C::OSTRIDE + g * (D / 4);
 #pragma unroll
             for (int mt = 0; mt < C::MT; ++mt)
@@ -282,7 +301,10 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                     }
                 }
             }
-            if (pass == 0) atomicMax(&mkey[row], float_key(mx));
+            if (pass == 0) {
+                mx = max_over_g(mx);
+                if (g == 0) atomicMax(&mkey[row], float_key(mx));
+            }
             else if (GMAX > 1) flush(row, lp, o, true);
         }
 
@@ -346,7 +368,10 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
 #pragma unroll
                             for (int e = 0; e < 8; ++e) mx = max_nan(mx, sc[e >> 2][e & 3]);
                         }
-                        if (valid) atomicMax(&mkey[row], float_key(mx * c2));
+                        // the four lanes of a row (g = 0 .. 3) hold different keys: their maximum by
+                        // two lane swaps, so that one lane per row goes to LDS
+                        mx = max_over_g(mx);
+                        if (valid && g == 0) atomicMax(&mkey[row], float_key(mx * c2));
                     } else {
                         float lp = 0.f;
                         f32x4_t o[C::MT];

@@ -278,12 +278,13 @@ inline bool mfma_path(const Dims& s)
 }
 
 // The query-tile forward accumulates the row sums and P V as 32-bit fixed point with
-// F = 30 - bitlen(keys a query can attend) fraction bits, eight keys of a row per add: a partial sum
-// below 2^-(F+1) is lost, so a row with one dominant logit beside very many tiny ones can lose up to
-// keys * 2^-(F+4) of its denominator (the sum is biased: every term is positive).  With at most
-// 4096 keys per query F is at least 17 and that loss at most 0.2 % in the worst case (16384 keys
-// would allow 1.6 %, which shows in the output); longer rows go to the key-major or the plain
-// kernels, which keep their sums in floating point.
+// F = 30 - bitlen(keys a query can attend) fraction bits, the 32 keys of a row and group per add
+// (the channel sums of P V likewise): a partial sum below 2^-(F+1) is lost, so a row with one
+// dominant logit beside very many tiny ones can lose up to keys * 2^-(F+6) of its denominator (the
+// sum is biased: every term is positive).  With at most 4096 keys per query F is at least 17 and
+// that loss at most 0.05 % in the worst case (16384 keys would allow 0.4 %, 32768 keys 1.6 %,
+// which shows in the output); longer rows go to the key-major or the plain kernels, which keep
+// their sums in floating point.
 constexpr int64_t kTileForwardMaxKeys = 4096;
 inline int64_t keys_per_query(const Dims& s)
 {
