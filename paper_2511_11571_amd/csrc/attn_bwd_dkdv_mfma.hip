@@ -59,12 +59,13 @@ __device__ __forceinline__ uint2 lds_read_tr16(const unsigned char* p)
     return *reinterpret_cast<const uint2*>(&r);
 }
 
-// WIDE (key blocks of whole 128-key parts): a workgroup owns four consecutive 32-key groups, one
-// per wave; a step covers 128 positions of the walk -- every wave gathers and parks 32 of them,
-// and after a barrier every wave works through all four slots with its own keys.  The block's
-// list is then gathered once per 128 keys instead of once per 32, and nothing has to be summed
-// over the waves.
-template <int D, bool WIDE>
+// GPW > 1 (key blocks of whole 64- or 128-key parts): a workgroup owns GPW = 2 or 4 consecutive
+// 32-key groups of one block, wave w the group w mod GPW; a step covers 128 positions of the walk
+// -- every wave gathers and parks 32 of them, and after a barrier every wave works through GPW of
+// the four slots with its own keys (GPW = 4: all of them; GPW = 2: waves 0, 1 the first two,
+// waves 2, 3 the others).  The block's list is then gathered once per 32 GPW keys instead of once
+// per 32, and with GPW = 4 nothing has to be summed over the waves (GPW = 2: over two).
+template <int D, int GPW>
 __global__ __launch_bounds__(DkvCfg<D>::NT) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1)))
 void dkdv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
@@ -75,6 +76,7 @@ void dkdv_mfma_kernel(
 {
     using C = DkvCfg<D>;
     extern __shared__ __align__(16) unsigned char smem[];
+    constexpr bool WIDE = GPW > 1;
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int m16 = lane & 15, g = lane >> 4;
     constexpr size_t SLOT = C::STAGE + 256;                 // parked Q rows, dO rows, lse, -D of 32 positions
@@ -88,17 +90,17 @@ void dkdv_mfma_kernel(
     // (walking all G heads in every workgroup, the L2 hit rate of the gathers fell from 80 % to
     // 15 % with 16 heads on one key/value head).
     const int slices = part ? bhk * G : bhk;
-    int slice, unit;                                        // slice; 32-key group or 128-key part
+    int slice, unit;                                        // slice; 32-key group or part of GPW groups
     if (!schedule(blockIdx.x, order * slices, groups_per_slice, slice, unit)) return;   // order -1: slice after slice
     const int skv = part ? slice / G : slice;               // key/value slice
     const int s_first = part ? slice : skv * G, s_last = part ? slice + 1 : (skv + 1) * G;
-    const int kap = WIDE ? 4 * unit + wave : unit;          // this wave's 32-key group inside the slice
+    const int kap = WIDE ? GPW * unit + wave % GPW : unit;  // this wave's 32-key group inside the slice
     const int NG = B / 32;
     const int j = kap / NG;
     const int64_t kvbase = (int64_t)skv * N;
     const float c2 = scale * kLog2e;
-    const int own0 = WIDE ? 128 * unit : 32 * kap;          // first own query that sees the workgroup's keys
-    const int kfirst = WIDE ? 32 * wave : 0;                // this wave's first key, counted from there
+    const int own0 = WIDE ? 32 * GPW * unit : 32 * kap;     // first own query that sees the workgroup's keys
+    const int kfirst = WIDE ? 32 * (wave % GPW) : 0;        // this wave's first key, counted from there
     int parity = 0;                                         // WIDE: which set of slots the next step parks in
 
     // B operands: the group's keys and values (lane = key m16 of tile nt)
@@ -284,8 +286,9 @@ void dkdv_mfma_kernel(
             // one barrier per step is enough: a slot set is parked again two steps later, and no
             // wave gets there before all have passed the barrier of the step in between
             __syncthreads();
+            const int sl0 = wave / GPW * GPW;               // the GPW slots that waves with other keys do not share out among them
 #pragma unroll 1
-            for (int sl = 0; sl < 4; ++sl) work(smem + (size_t)(4 * parity + sl) * SLOT, a0 - 32 * wave + 32 * sl, inside);
+            for (int sl = sl0; sl < sl0 + GPW; ++sl) work(smem + (size_t)(4 * parity + sl) * SLOT, a0 - 32 * wave + 32 * sl, inside);
             parity ^= 1;
         } else {
             __builtin_amdgcn_wave_barrier();
@@ -306,9 +309,36 @@ void dkdv_mfma_kernel(
     }
 
     if constexpr (WIDE) {
-        // every wave has the whole sums of its own 32 keys: turn them over in LDS (channels of a
-        // key side by side) and write them out
         __syncthreads();                                    // the slots are no longer read
+        if constexpr (GPW < C::NW) {
+            // waves w, w + GPW, ... hold parts of the sums of the same keys: the later ones leave
+            // theirs in LDS, the first GPW waves add them up
+            if (wave >= GPW) {
+#pragma unroll
+                for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt) {
+                        float* pk = red + (16 * nt + m16) * C::RSTRIDE + 16 * mt + 4 * g;
+                        *reinterpret_cast<f32x4_t*>(pk) = dKT[mt][nt];
+                        *reinterpret_cast<f32x4_t*>(pk + 32 * C::RSTRIDE) = dVT[mt][nt];
+                    }
+            }
+            __syncthreads();
+            if (wave >= GPW) return;                        // (no workgroup barrier follows)
+            for (int w2 = wave + GPW; w2 < C::NW; w2 += GPW) {
+                const float* other = reinterpret_cast<const float*>(smem + (size_t)w2 * 2 * 32 * C::RSTRIDE * 4);
+#pragma unroll
+                for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt) {
+                        const float* pk = other + (16 * nt + m16) * C::RSTRIDE + 16 * mt + 4 * g;
+                        dKT[mt][nt] += *reinterpret_cast<const f32x4_t*>(pk);
+                        dVT[mt][nt] += *reinterpret_cast<const f32x4_t*>(pk + 32 * C::RSTRIDE);
+                    }
+            }
+        }
+        // every wave (of the first GPW) has the whole sums of its own 32 keys: turn them over in
+        // LDS (channels of a key side by side) and write them out
 #pragma unroll
         for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
@@ -401,25 +431,26 @@ static hipError_t dkdv_launch(const Dims& s, const void* Q, const void* K, const
     using C = DkvCfg<D>;
     const int gps = s.N / 32;
     if (gps == 0) return hipSuccess;
-    const bool wide = s.B % 128 == 0;                       // four 32-key groups of one block per workgroup
-    const size_t lds = wide ? C::LDS_WIDE : C::LDS;
-    const int units = wide ? gps / 4 : gps;
-    hipError_t e = wide ? ensure_dynamic_lds((const void*)dkdv_mfma_kernel<D, true>, (size_t)lds)
-                        : ensure_dynamic_lds((const void*)dkdv_mfma_kernel<D, false>, (size_t)lds);
+    // 32-key groups of one block per workgroup: four, two or one
+    const int gpw = s.B % 128 == 0 ? 4 : s.B % 64 == 0 ? 2 : 1;
+    const size_t lds = gpw > 1 ? C::LDS_WIDE : C::LDS;
+    const int units = gps / gpw;
+    hipError_t e = gpw == 4   ? ensure_dynamic_lds((const void*)dkdv_mfma_kernel<D, 4>, (size_t)lds)
+                   : gpw == 2 ? ensure_dynamic_lds((const void*)dkdv_mfma_kernel<D, 2>, (size_t)lds)
+                              : ensure_dynamic_lds((const void*)dkdv_mfma_kernel<D, 1>, (size_t)lds);
     if (e != hipSuccess) return e;
     const int slices = part ? s.bh : s.bhk;
     const int order = slices > 1 ? slice_major(s, 2) : 1;       // (gathers Q and dO rows)
     ProfileScope timing(MOBA_PROFILE_DKDV, st);
-    if (wide)
-        hipLaunchKernelGGL((dkdv_mfma_kernel<D, true>), dim3((unsigned)schedule_grid(order * slices, units)), dim3(C::NT),
-                           lds, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO,
-                           ld, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
-                           s.bhk, s.G, part, order);
-    else
-        hipLaunchKernelGGL((dkdv_mfma_kernel<D, false>), dim3((unsigned)schedule_grid(order * slices, units)), dim3(C::NT),
-                           lds, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO,
-                           ld, off, ql, (bf16_t*)dK, (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units,
-                           s.bhk, s.G, part, order);
+    const dim3 grid((unsigned)schedule_grid(order * slices, units));
+#define MOBA_DKDV_LAUNCH(GPW)                                                                                  \
+    hipLaunchKernelGGL((dkdv_mfma_kernel<D, GPW>), grid, dim3(C::NT), lds, st, (const bf16_t*)Q,              \
+                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, ld, off, ql, (bf16_t*)dK,       \
+                       (bf16_t*)dV, s.N, s.B, s.n, s.scale, s.R, units, s.bhk, s.G, part, order)
+    if (gpw == 4) MOBA_DKDV_LAUNCH(4);
+    else if (gpw == 2) MOBA_DKDV_LAUNCH(2);
+    else MOBA_DKDV_LAUNCH(1);
+#undef MOBA_DKDV_LAUNCH
     if (part) {
         const int64_t cps = (int64_t)s.N * D / 8, total = 2 * cps * s.bhk;
         hipLaunchKernelGGL(dkdv_heads_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, part,
