@@ -322,7 +322,7 @@ inline bool key_major_path(const Dims& s)
     const double parts = (double)(s.B / km_part_keys(s.B, s.D));
     const double tiles = (d64 ? 0.6 : 1.1) + 0.0013 * s.B +
                          s.k * (s.B / 32.0) * (d64 ? 0.015 + 0.14 / rows : 0.033 + 0.272 / rows);
-    const double keymajor = (d64 ? 0.145 : 0.23) * (s.k + 1) * (1.0 + 0.7 * (parts - 1.0));
+    const double keymajor = (d64 ? 0.115 : 0.17) * (s.k + 1) * (1.0 + 0.7 * (parts - 1.0));
     return keymajor < tiles;
 }
 
