@@ -164,7 +164,7 @@ int moba_topk(const moba_shape* shape, const void* Q, const float* centroids,
  * long, one copy per GPU, held until the process ends.  The call allocates nothing.  Same
  * arguments, outputs and checks as moba_topk without `ws`; a shape whose topk_ws (see
  * moba_workspace_bytes) exceeds MOBA_TOPK_STATIC_MAX_BYTES returns MOBA_EWORKSPACE and launches
- * nothing (batch 1, 16 heads, N = 32768, B = 32 needs 23 MiB).  All calls on one GPU share that
+ * nothing (batch 1, 16 heads, N = 32768, B = 32 needs 15 MiB).  All calls on one GPU share that
  * GPU's array: calls that may overlap in time on one GPU (different streams, different threads)
  * race and must be ordered by the caller.  Nothing in the array has to survive between calls.
  */

@@ -10,7 +10,7 @@ namespace moba {
 typedef uint16_t bf16_t;   // raw bfloat16 bits
 
 constexpr int kWave = 64;
-constexpr int kChunkQ = 128;   // queries per chunk of the list builder's per-(chunk, block) counts
+constexpr int kChunkQ = 256;   // queries per chunk of the list builder's per-(chunk, block) counts (= per workgroup there)
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t x)
 {

@@ -2,7 +2,7 @@
 // "Reformatting Indices to Varlen Key-Block-Major").  The paper scatters with global
 // atomics, which leaves the order inside a list to chance; here the lists come out
 // ascending and bit-reproducible:
-//   1. count: a workgroup takes 256 consecutive queries (two chunks of 128) and ORs one bit per
+//   1. count: a workgroup takes a chunk of 256 consecutive queries and ORs one bit per
 //      (query, kept block) into an LDS bit matrix [block][256 bits]; the population
 //      count of a row is the number of queries of this chunk that kept that block.
 //   2. scan: per key block an exclusive scan over chunks (start of each chunk's segment
@@ -23,7 +23,7 @@
 namespace moba {
 
 constexpr int kRange = 1024;                    // key blocks per LDS bit matrix (32 KB)
-constexpr int kListQ = 2 * kChunkQ;              // queries per workgroup: two chunks of 128
+constexpr int kListQ = kChunkQ;                  // queries per workgroup: one chunk
 constexpr int kWords = kListQ / 32;             // 8 words of 32 query bits per block
 constexpr int kQueryBits = 24;                  // low bits of a list entry: the query
 
@@ -93,22 +93,17 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
     // consecutive query chunks of a slice go to the same XCD: the 128-byte lines of a block's
     // list are completed by neighbouring chunks and should meet in one L2 before they are written back
     int c, s;
-    if (!schedule(blockIdx.x, bh, (nchunk + 1) / 2, s, c)) return;
+    if (!schedule(blockIdx.x, bh, nchunk, s, c)) return;
     const int lo = blockIdx.y * kRange;
     const int hi = min(n, lo + kRange);
     const int t0 = c * kListQ;
     const int rows = min(N - t0, kListQ);
     const int nblk = min(hi, (t0 + rows - 1) / B) - lo;   // kept blocks are < own block of the last query
     const int tid = threadIdx.x;
-    // this workgroup covers chunks 2c and 2c+1 (the second may not exist)
-    int32_t* crow = cnt2 + ((int64_t)s * (nchunk + 1) + 2 * c) * n + lo;
-    const bool two = 2 * c + 1 < nchunk;
+    int32_t* crow = cnt2 + ((int64_t)s * (nchunk + 1) + c) * n + lo;
     if (nblk <= 0) {
         if (!FILL)
-            for (int j = tid; j < hi - lo; j += 256) {
-                crow[j] = 0;
-                if (two) crow[n + j] = 0;
-            }
+            for (int j = tid; j < hi - lo; j += 256) crow[j] = 0;
         return;
     }
     for (int i = tid; i < nblk * kWords; i += 256) mask[i] = 0u;
@@ -128,16 +123,12 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
     __syncthreads();
     if (!FILL) {
         for (int j = tid; j < hi - lo; j += 256) {
-            int c0 = 0, c1 = 0;
+            int c0 = 0;
             if (j < nblk) {
 #pragma unroll
-                for (int wd = 0; wd < kWords / 2; ++wd) {
-                    c0 += __popc(mask[j * kWords + wd]);
-                    c1 += __popc(mask[j * kWords + kWords / 2 + wd]);
-                }
+                for (int wd = 0; wd < kWords; ++wd) c0 += __popc(mask[j * kWords + wd]);
             }
             crow[j] = c0;
-            if (two) crow[n + j] = c1;
         }
     } else {
         if constexpr (SLOTS) {
@@ -275,7 +266,7 @@ hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, i
                               int32_t* cnt2, hipStream_t st)
 {
     const int nranges = (s.n + kRange - 1) / kRange;
-    dim3 grid(schedule_grid(s.bh, (s.nchunk + 1) / 2), nranges), block(256);
+    dim3 grid(schedule_grid(s.bh, s.nchunk), nranges), block(256);
     hipLaunchKernelGGL((lists_chunk_kernel<false, false>), grid, block, 0, st, idx, cnt2,
                        (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R, s.bh);
     hipLaunchKernelGGL(lists_scan_kernel, dim3((s.n + 31) / 32, s.bh), block, 0, st, cnt2, off, s.n,

@@ -70,7 +70,7 @@ int make_dims(const moba_shape* sh, Dims& d, bool ragged_ok = false)
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// top-k: the list builder's per-(128-query chunk, key block) counts, then the three bf16 terms
+// top-k: the list builder's per-(256-query chunk, key block) counts, then the three bf16 terms
 // of the centroids (MFMA scoring)
 size_t chunk_counts_bytes(const Dims& d)
 {
