@@ -27,33 +27,9 @@ constexpr int kListQ = kChunkQ;                  // queries per workgroup: one c
 constexpr int kWords = kListQ / 32;             // 8 words of 32 query bits per block
 constexpr int kQueryBits = 24;                  // low bits of a list entry: the query
 
-// f(r, b) for every entry b of the routing rows r = 0 .. rows-1 of this workgroup (k entries per
-// row, rows contiguous in memory), all 256 threads, 16-byte loads when the row length allows
-template <typename F>
-__device__ __forceinline__ void for_each_entry(const int32_t* __restrict__ rows0, int rows, int k,
-                                               int tid, F f)
-{
-    const int total = rows * k;
-    if ((k & 3) == 0) {
-        const int4* p4 = reinterpret_cast<const int4*>(rows0);
-        const int n4 = total >> 2;
-        for (int i0 = tid; i0 < n4; i0 += 4 * 256) {
-            int4 v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                v[u] = i0 + u * 256 < n4 ? p4[i0 + u * 256] : make_int4(-1, -1, -1, -1);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int r = ((i0 + u * 256) << 2) / k;     // a 16-byte piece never straddles rows
-                f(r, v[u].x); f(r, v[u].y); f(r, v[u].z); f(r, v[u].w);
-            }
-        }
-    } else {
-        for (int i = tid; i < total; i += 256) f(i / k, rows0[i]);
-    }
-}
-
-// the same with the position of every entry in its row: f(r, b, e)
+// f(r, b, e) for every entry b = row r's e-th of the routing rows r = 0 .. rows-1 of this workgroup
+// (k entries per row, rows contiguous in memory), all 256 threads, 16-byte loads when the row length
+// allows.  The row and place of a thread's entries advance by additions (one division per thread).
 template <typename F>
 __device__ __forceinline__ void for_each_entry_slot(const int32_t* __restrict__ rows0, int rows, int k,
                                                     int tid, F f)
@@ -62,6 +38,8 @@ __device__ __forceinline__ void for_each_entry_slot(const int32_t* __restrict__ 
     if ((k & 3) == 0) {
         const int4* p4 = reinterpret_cast<const int4*>(rows0);
         const int n4 = total >> 2;
+        const int dr = 1024 / k, de = 1024 % k;             // 256 pieces of four entries further on
+        int r = 4 * tid / k, e = 4 * tid - r * k;           // a 16-byte piece never straddles rows
         for (int i0 = tid; i0 < n4; i0 += 4 * 256) {
             int4 v[4];
 #pragma unroll
@@ -69,14 +47,29 @@ __device__ __forceinline__ void for_each_entry_slot(const int32_t* __restrict__ 
                 v[u] = i0 + u * 256 < n4 ? p4[i0 + u * 256] : make_int4(-1, -1, -1, -1);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int q = (i0 + u * 256) << 2;
-                const int r = q / k, e = q - r * k;
                 f(r, v[u].x, e); f(r, v[u].y, e + 1); f(r, v[u].z, e + 2); f(r, v[u].w, e + 3);
+                r += dr;
+                e += de;
+                if (e >= k) { e -= k; ++r; }
             }
         }
     } else {
-        for (int i = tid; i < total; i += 256) f(i / k, rows0[i], i % k);
+        const int dr = 256 / k, de = 256 % k;
+        int r = tid / k, e = tid - r * k;
+        for (int i = tid; i < total; i += 256) {
+            f(r, rows0[i], e);
+            r += dr;
+            e += de;
+            if (e >= k) { e -= k; ++r; }
+        }
     }
+}
+
+// the same without the place: f(r, b)
+template <typename F>
+__device__ __forceinline__ void for_each_entry(const int32_t* __restrict__ rows0, int rows, int k, int tid, F f)
+{
+    for_each_entry_slot(rows0, rows, k, tid, [&](int r, int b, int) { f(r, b); });
 }
 
 template <bool FILL, bool SLOTS>
@@ -118,7 +111,8 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
     // only past blocks count: lists never exceed R
     for_each_entry(rows0, rows, k, tid, [&](int r, int b) {
         b -= lo;
-        if (b >= 0 && b < nblk && b + lo < (t0 + r) / B) atomicOr(&mask[b * kWords + (r >> 5)], 1u << (r & 31));
+        // (block b + lo lies before the own block of query t0 + r: its last key does)
+        if (b >= 0 && b < nblk && (b + lo + 1) * B <= t0 + r) atomicOr(&mask[b * kWords + (r >> 5)], 1u << (r & 31));
     });
     __syncthreads();
     if (!FILL) {
@@ -164,7 +158,7 @@ __global__ __launch_bounds__(256) void lists_chunk_kernel(
             // a query keeps at most k blocks, so the runs hold at most kListQ * k entries
             for_each_entry_slot(rows0, rows, k, tid, [&](int r, int b, int e) {
                 b -= lo;
-                if (b >= 0 && b < nblk && b + lo < (t0 + r) / B) {
+                if (b >= 0 && b < nblk && (b + lo + 1) * B <= t0 + r) {
                     const uint32_t* mrow = mask + b * kWords;
                     int rank = __popc(mrow[r >> 5] & ((1u << (r & 31)) - 1u));
                     for (int wd = 0; wd < (r >> 5); ++wd) rank += __popc(mrow[wd]);
