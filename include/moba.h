@@ -63,11 +63,10 @@ typedef enum moba_dtype { MOBA_F32 = 0, MOBA_BF16 = 1 } moba_dtype;
                                         * search on exact scores from the start (slower, same result; the
                                         * path that queries with many equal scores take anyway)          */
 #define MOBA_FLAG_SHARED_WORKSPACE 16u  /* the caller hands moba_forward and the following moba_backward /
-                                        * moba_backward_parts of the same K_eff, V and topk_idx the SAME
-                                        * workspace (then fwd_ws == bwd_ws in moba_workspace_bytes): the
-                                        * copies of K and V that the query-tile kernels read, and the row
-                                        * lists of the query tiles, are made once, by the forward call, and
-                                        * the backward trusts what it finds there.
+                                        * moba_backward_parts of the same K_eff and V the SAME workspace
+                                        * (then fwd_ws == bwd_ws in moba_workspace_bytes): the copies of K
+                                        * and V that the query-tile kernels read are made once, by the
+                                        * forward call, and the backward trusts what it finds there.
                                         * Without the flag every call prepares its own.  No effect where
                                         * the other kernels run.                                         */
 /* With neither of KEY_MAJOR and QUERY_TILES the library picks by a cost estimate of both from the shape: key blocks

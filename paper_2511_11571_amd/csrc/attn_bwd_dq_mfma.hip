@@ -34,7 +34,6 @@ struct DqCfg {
     static constexpr int KS = D / 32;
     static constexpr int RANGE = 1024;                 // key blocks per set of row lists (at most)
     static constexpr int LCAP = 16384;                 // (row, block) pairs per set of row lists
-    static_assert(RANGE == kTileRange && LCAP == kTileListCap, "the forward's tile lists are read as they are");
     static constexpr size_t LDS = (size_t)2 * TILE * ROWB + 4 * TILE * OSTRIDE + 4 * 3 * TILE +
                                   4 * 2 * (RANGE + 1) + 4 * NW + 8 + LCAP + 64;
 };
@@ -48,7 +47,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
     const bf16_t* __restrict__ Kt, const uint32_t* __restrict__ kmax,
     const uint32_t* __restrict__ vmax, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ Dv, const int32_t* __restrict__ idx, bf16_t* __restrict__ dQ, int N,
-    int B, int k, float scale, int ntiles, int bh, int G, const unsigned char* __restrict__ tile_lists)
+    int B, int k, float scale, int ntiles, int bh, int G)
 {
     using C = DqCfg<D>;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -228,26 +227,10 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
     for (int lo = 0; lo < pastmax; lo += range) {
         const int hi = min(pastmax, lo + range);
         __syncthreads();
-        if (tile_lists) {
-            // the forward left this tile's lists (the library asks for them only where one range
-            // covers every tile)
-            const unsigned char* rec = tile_lists + ((int64_t)s * ntiles + tile) * kTileRecStride;
-            const uint32_t* goffs = reinterpret_cast<const uint32_t*>(rec + kTileRecOffs);
-            const int nb = hi - lo, cnt = *reinterpret_cast<const int*>(rec);
-            const int used = min((int)goffs[nb], (int)C::LCAP);
-            for (int i = tid; i <= nb; i += C::NT) offs[i] = goffs[i];
-            for (int i = tid; i < (cnt + 1) / 2; i += C::NT)
-                reinterpret_cast<uint32_t*>(ulist)[i] = reinterpret_cast<const uint32_t*>(rec + kTileRecUlist)[i];
-            for (int i = tid; i < (used + 15) / 16; i += C::NT)
-                reinterpret_cast<uint4*>(rows8)[i] = reinterpret_cast<const uint4*>(rec + kTileRecRows)[i];
-            if (tid == 0) { *take = 0; *next = cnt; }
-            __syncthreads();
-        } else {
-            build_block_lists<C::TILE, C::NT>(idx + (sbase + t0) * k, t0, rows_here, k, B, lo, hi, cur, offs,
-                                              rows8, C::LCAP, wsum, tid);
-            if (tid == 0) *take = 0;
-            list_nonempty<C::NT>(offs, hi - lo, ulist, next, wsum, tid);
-        }
+        build_block_lists<C::TILE, C::NT>(idx + (sbase + t0) * k, t0, rows_here, k, B, lo, hi, cur, offs,
+                                          rows8, C::LCAP, wsum, tid);
+        if (tid == 0) *take = 0;
+        list_nonempty<C::NT>(offs, hi - lo, ulist, next, wsum, tid);
         const int nblk = *next;
 
         // waves take the listed blocks as they get free; one unit = one 32-key group of a block
@@ -309,7 +292,7 @@ __global__ __launch_bounds__(DqCfg<D>::NT) void dq_mfma_kernel(
 }
 
 template <int D>
-static hipError_t dq_launch(const unsigned char* tile_lists, const Dims& s, const void* Q, const void* Ka, const void* Va, const void* Kt,
+static hipError_t dq_launch(const Dims& s, const void* Q, const void* Ka, const void* Va, const void* Kt,
                             const uint32_t* kmax, const uint32_t* vmax, const void* dO,
                             const float* lse, const float* Dv, const int32_t* idx, void* dQ,
                             hipStream_t st)
@@ -322,7 +305,7 @@ static hipError_t dq_launch(const unsigned char* tile_lists, const Dims& s, cons
     hipLaunchKernelGGL((dq_mfma_kernel<D>), dim3((unsigned)schedule_grid(s.bh, ntiles)), dim3(C::NT), C::LDS, st,
                        (const bf16_t*)Q, (const bf16_t*)Ka, (const bf16_t*)Va, (const bf16_t*)Kt, kmax,
                        vmax, (const bf16_t*)dO, lse, Dv, idx, (bf16_t*)dQ, s.N, s.B, s.k, s.scale,
-                       ntiles, s.bh, s.G, tile_lists);
+                       ntiles, s.bh, s.G);
     return hipGetLastError();
 }
 
@@ -334,8 +317,7 @@ static hipError_t dq_launch(const unsigned char* tile_lists, const Dims& s, cons
 size_t backward_mfma_ws_bytes(const Dims& s)
 {
     return a256(sizeof(float) * (size_t)s.bh * s.N) +
-           prepared_layout(s, shared_workspace(s) ? kPrepAll : kPrepBackward, nullptr, nullptr) +
-           tile_lists_bytes(s);                  // (shared workspace: the forward's row lists, last)
+           prepared_layout(s, shared_workspace(s) ? kPrepAll : kPrepBackward, nullptr, nullptr);
 }
 
 hipError_t launch_dq_mfma(const Dims& s, const void* Q, const void* K, const void* V, const void* dO,
@@ -344,15 +326,14 @@ hipError_t launch_dq_mfma(const Dims& s, const void* Q, const void* K, const voi
 {
     const float* Dv = (const float*)ws;
     Prepared p;
-    char* prep = (char*)ws + a256(sizeof(float) * (size_t)s.bh * s.N);
-    const size_t prep_bytes = prepared_layout(s, shared_workspace(s) ? kPrepAll : kPrepBackward, prep, &p);
-    const unsigned char* tile_lists = share_tile_lists(s) ? (const unsigned char*)(prep + prep_bytes) : nullptr;
+    prepared_layout(s, shared_workspace(s) ? kPrepAll : kPrepBackward,
+                    (char*)ws + a256(sizeof(float) * (size_t)s.bh * s.N), &p);
     if (!shared_workspace(s)) {
         hipError_t e = launch_prepare(kv_view(s), K, V, p, st);
         if (e != hipSuccess) return e;
     }
-    return s.D == 64 ? dq_launch<64>(tile_lists, s, Q, p.Ka, p.Va, p.Kt, p.kmax, p.vmax, dO, lse, Dv, idx, dQ, st)
-                     : dq_launch<128>(tile_lists, s, Q, p.Ka, p.Va, p.Kt, p.kmax, p.vmax, dO, lse, Dv, idx, dQ, st);
+    return s.D == 64 ? dq_launch<64>(s, Q, p.Ka, p.Va, p.Kt, p.kmax, p.vmax, dO, lse, Dv, idx, dQ, st)
+                     : dq_launch<128>(s, Q, p.Ka, p.Va, p.Kt, p.kmax, p.vmax, dO, lse, Dv, idx, dQ, st);
 }
 
 }  // namespace moba

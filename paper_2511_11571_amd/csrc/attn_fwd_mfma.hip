@@ -50,7 +50,6 @@ struct FwdCfg {
     static constexpr int KS = D / 32;                  // contraction steps of q.k
     static constexpr int RANGE = 1024;                 // key blocks per set of row lists (at most)
     static constexpr int LCAP = 16384;                 // (row, block) pairs per set of row lists
-    static_assert(RANGE == kTileRange && LCAP == kTileListCap, "the dQ kernel reads the tile lists as they are");
     static constexpr size_t LDS = (size_t)TILE * QSTRIDE + 4 * TILE * OSTRIDE + 4 * 2 * TILE +
                                   4 * 2 * (RANGE + 1) + 4 * NW + 8 + LCAP + 64;
 };
@@ -147,8 +146,7 @@ template <int D, int GMAX>
 __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Ka, const bf16_t* __restrict__ Vt,
     const uint32_t* __restrict__ vmax, const int32_t* __restrict__ idx, bf16_t* __restrict__ O,
-    float* __restrict__ lse, int N, int B, int k, float scale, int ntiles, int bh, int G,
-    unsigned char* __restrict__ tile_lists)
+    float* __restrict__ lse, int N, int B, int k, float scale, int ntiles, int bh, int G)
 {
     using C = FwdCfg<D>;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -321,18 +319,6 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
                 // K and V in the same order and find each other's blocks in the L2.
                 if (tid == 0) *take = 0;
                 list_nonempty<C::NT>(offs, hi - lo, ulist, next, wsum, tid);
-                if (tile_lists) {
-                    // a copy of the lists for the dQ kernel of the backward, whose tiles are the same
-                    // (asked for only where one range covers every tile)
-                    unsigned char* rec = tile_lists + ((int64_t)s * ntiles + tile) * kTileRecStride;
-                    const int nb = hi - lo, cnt = *next, used = min((int)offs[nb], (int)C::LCAP);
-                    if (tid == 0) *reinterpret_cast<int*>(rec) = cnt;
-                    for (int i = tid; i <= nb; i += C::NT) reinterpret_cast<uint32_t*>(rec + kTileRecOffs)[i] = offs[i];
-                    for (int i = tid; i < (cnt + 1) / 2; i += C::NT)
-                        reinterpret_cast<uint32_t*>(rec + kTileRecUlist)[i] = reinterpret_cast<const uint32_t*>(ulist)[i];
-                    for (int i = tid; i < (used + 15) / 16; i += C::NT)
-                        reinterpret_cast<uint4*>(rec + kTileRecRows)[i] = reinterpret_cast<const uint4*>(rows8)[i];
-                }
             }
             const int nblk = *next;
 
@@ -450,7 +436,7 @@ __global__ __launch_bounds__(FwdCfg<D>::NT) void forward_mfma_kernel(
 template <int D, int GMAX>
 static hipError_t fwd_launch(const Dims& s, const void* Q, const void* K, const void* Vt,
                              const uint32_t* vmax, const int32_t* idx, void* O, float* lse,
-                             unsigned char* tile_lists, hipStream_t st)
+                             hipStream_t st)
 {
     using C = FwdCfg<D>;
     const int ntiles = (s.N + C::TILE - 1) / C::TILE;
@@ -459,7 +445,7 @@ static hipError_t fwd_launch(const Dims& s, const void* Q, const void* K, const 
     ProfileScope timing(MOBA_PROFILE_FORWARD, st);
     hipLaunchKernelGGL((forward_mfma_kernel<D, GMAX>), dim3((unsigned)schedule_grid(s.bh, ntiles)), dim3(C::NT), C::LDS,
                        st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)Vt, vmax, idx,
-                       (bf16_t*)O, lse, s.N, s.B, s.k, s.scale, ntiles, s.bh, s.G, tile_lists);
+                       (bf16_t*)O, lse, s.N, s.B, s.k, s.scale, ntiles, s.bh, s.G);
     return hipGetLastError();
 }
 
@@ -477,20 +463,17 @@ hipError_t launch_forward_mfma(const Dims& s, const void* Q, const void* K, cons
                                void* O, float* lse, hipStream_t st)
 {
     Prepared p;
-    unsigned char* tile_lists = nullptr;
     if (shared_workspace(s)) {
-        char* prep = (char*)ws + a256(sizeof(float) * (size_t)s.bh * s.N);
-        const size_t prep_bytes = prepared_layout(s, kPrepAll, prep, &p);
-        if (share_tile_lists(s)) tile_lists = (unsigned char*)(prep + prep_bytes);
+        prepared_layout(s, kPrepAll, (char*)ws + a256(sizeof(float) * (size_t)s.bh * s.N), &p);
     } else {
         prepared_layout(s, kPrepForward, ws, &p);
         p.kmax = nullptr;                                    // (only the dQ kernel scales K)
     }
     hipError_t e = launch_prepare(kv_view(s), K, V, p, st);  // K and V: one slice per key/value head
     if (e != hipSuccess) return e;
-    if (s.D == 128) return fwd_launch<128, 1>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, tile_lists, st);
-    return s.B >= 64 ? fwd_launch<64, 2>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, tile_lists, st)
-                     : fwd_launch<64, 1>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, tile_lists, st);
+    if (s.D == 128) return fwd_launch<128, 1>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, st);
+    return s.B >= 64 ? fwd_launch<64, 2>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, st)
+                     : fwd_launch<64, 1>(s, Q, p.Ka, p.Vt, p.vmax, idx, O, lse, st);
 }
 
 }  // namespace moba

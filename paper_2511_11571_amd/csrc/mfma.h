@@ -333,26 +333,6 @@ inline bool shared_workspace(const Dims& s)
     return (s.flags & MOBA_FLAG_SHARED_WORKSPACE) && mfma_path(s) && tile_forward_ok(s) && !key_major_path(s);
 }
 
-// In a shared workspace the forward also leaves the row lists of its query tiles (which rows of
-// the tile kept which key block: build_block_lists above) for the dQ kernel, whose tiles are the
-// same -- where one set of lists covers a tile (up to kTileRange key blocks, kTileListCap pairs).
-// Record of a tile: [number of non-empty blocks][offs: kTileRange + 1 words][ulist: kTileRange
-// 16-bit block numbers][rows8: kTileListCap bytes].
-constexpr int kTileRange = 1024, kTileListCap = 16384;
-constexpr size_t kTileRecOffs = 16, kTileRecUlist = kTileRecOffs + 4 * (kTileRange + 4),
-                 kTileRecRows = kTileRecUlist + 2 * kTileRange,
-                 kTileRecStride = (kTileRecRows + kTileListCap + 255) / 256 * 256;
-inline int tile_queries(int D) { return D == 64 ? 256 : 128; }
-inline bool share_tile_lists(const Dims& s)
-{
-    return shared_workspace(s) && (int64_t)s.k * tile_queries(s.D) <= kTileListCap && s.n <= kTileRange;
-}
-inline size_t tile_lists_bytes(const Dims& s)
-{
-    const int64_t ntiles = (s.N + tile_queries(s.D) - 1) / tile_queries(s.D);
-    return share_tile_lists(s) ? (size_t)s.bh * ntiles * kTileRecStride : 0;
-}
-
 size_t forward_km_ws_bytes(const Dims& s);
 size_t backward_km_ws_bytes(const Dims& s);
 hipError_t launch_dq_km(const Dims& s, const void* Q, const void* K, const void* V, const void* dO,
