@@ -9,7 +9,7 @@
 //      inside the block's list), then an exclusive scan of the block totals (blk_off).
 //   3. fill: the bit matrix is rebuilt and its rows are written out in ascending order at
 //      blk_off[j] + chunk start, eight lanes per row.
-// The bit matrix lives in LDS only and covers 1024 key blocks at a time.
+// The bit matrix lives in LDS only and covers 1024 key blocks at a time (512 where a slice has more).
 //
 // A list entry holds the query in its low 24 bits (sequences are at most 2^24 long).  Where the
 // key-block-major attention kernels will run (key_major_path() of the shape and its flags) the
@@ -22,7 +22,8 @@
 
 namespace moba {
 
-constexpr int kRange = 1024;                    // key blocks per LDS bit matrix (32 KB)
+constexpr int kRangeMax = 1024;                 // key blocks per LDS bit matrix at most (32 KB)
+constexpr int kRangeLong = 512;                 // ... where a slice has more blocks than that
 constexpr int kListQ = kChunkQ;                  // queries per workgroup: one chunk
 constexpr int kWords = kListQ / 32;             // 8 words of 32 query bits per block
 constexpr int kQueryBits = 24;                  // low bits of a list entry: the query
@@ -72,7 +73,8 @@ __device__ __forceinline__ void for_each_entry(const int32_t* __restrict__ rows0
     for_each_entry_slot(rows0, rows, k, tid, [&](int r, int b, int) { f(r, b); });
 }
 
-template <bool FILL, bool SLOTS>
+// kRange: key blocks per LDS bit matrix (blockIdx.y counts the ranges of a slice's blocks)
+template <bool FILL, bool SLOTS, int kRange>
 __global__ __launch_bounds__(256) void lists_chunk_kernel(
     const int32_t* __restrict__ idx, int32_t* __restrict__ cnt2, const int32_t* __restrict__ off,
     int32_t* __restrict__ ql, int N, int B, int n, int k, int nchunk, int64_t R, int bh)
@@ -256,12 +258,13 @@ __global__ __launch_bounds__(256) void lists_offsets_kernel(int32_t* __restrict_
     for (int j = a; j < b; ++j) { run += os[j + 1]; os[j + 1] = run; }
 }
 
-hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, int32_t* ql,
-                              int32_t* cnt2, hipStream_t st)
+template <int RANGE>
+static hipError_t build_lists_launch(const Dims& s, const int32_t* idx, int32_t* off, int32_t* ql,
+                                     int32_t* cnt2, hipStream_t st)
 {
-    const int nranges = (s.n + kRange - 1) / kRange;
+    const int nranges = (s.n + RANGE - 1) / RANGE;
     dim3 grid(schedule_grid(s.bh, s.nchunk), nranges), block(256);
-    hipLaunchKernelGGL((lists_chunk_kernel<false, false>), grid, block, 0, st, idx, cnt2,
+    hipLaunchKernelGGL((lists_chunk_kernel<false, false, RANGE>), grid, block, 0, st, idx, cnt2,
                        (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R, s.bh);
     hipLaunchKernelGGL(lists_scan_kernel, dim3((s.n + 31) / 32, s.bh), block, 0, st, cnt2, off, s.n,
                        s.nchunk);
@@ -269,13 +272,24 @@ hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, i
     if (s.R > 0) {
         static_assert(kKeyMajorMaxTopk <= 255 && kListQ * kKeyMajorMaxTopk <= 65535, "slot byte, 16-bit run starts");
         if (key_major_path(s))
-            hipLaunchKernelGGL((lists_chunk_kernel<true, true>), grid, block, (size_t)kListQ * s.k, st, idx,
+            hipLaunchKernelGGL((lists_chunk_kernel<true, true, RANGE>), grid, block, (size_t)kListQ * s.k, st, idx,
                                cnt2, (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R, s.bh);
         else
-            hipLaunchKernelGGL((lists_chunk_kernel<true, false>), grid, block, 0, st, idx, cnt2,
+            hipLaunchKernelGGL((lists_chunk_kernel<true, false, RANGE>), grid, block, 0, st, idx, cnt2,
                                (const int32_t*)off, ql, s.N, s.B, s.n, s.k, s.nchunk, s.R, s.bh);
     }
     return hipGetLastError();
+}
+
+// Up to kRangeMax blocks one range covers a slice and a workgroup reads its routing rows once.
+// Beyond that the rows are read once per range anyway, and a workgroup's cost is that of walking
+// its bit matrix, however few pairs fall into it: smaller ranges, more workgroups (N = 524288,
+// B = 128, top-k 8: fill pass 3.9 ms with ranges of 1024 blocks, 2.6 ms with 512, 3.5 ms with 256).
+hipError_t launch_build_lists(const Dims& s, const int32_t* idx, int32_t* off, int32_t* ql,
+                              int32_t* cnt2, hipStream_t st)
+{
+    return s.n <= kRangeMax ? build_lists_launch<kRangeMax>(s, idx, off, ql, cnt2, st)
+                            : build_lists_launch<kRangeLong>(s, idx, off, ql, cnt2, st);
 }
 
 }  // namespace moba
